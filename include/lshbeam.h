@@ -1,0 +1,154 @@
+/* lshbeam -- LSH reduced-vocabulary softmax + beam expansion on one MI355X (gfx950).
+ *
+ * C ABI of the decode-time hot path of Shi, Xu & Knight, "Fast Locality Sensitive Hashing for
+ * Beam Search on GPU":  winner-take-all hashing of the hidden states (Eq. 4-8), lookup of the
+ * band codes in per-band cuckoo tables (section "Cuckoo lookup", Algorithm 1), the candidate
+ * list shared across a sentence's beams and merged with the top-frequent words (Eq. 3, Eq. 10),
+ * the gathered product H * E_LSH (Eq. 2), the log-softmax over the candidate list (Eq. 1) and
+ * the beam expansion (Introduction, "Beam expansion") -- all on the device.
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller; *_host is host memory.
+ *  - The library allocates device memory only inside lsh_build_tables (freed by
+ *    lsh_free_tables).  lsh_decode_step allocates nothing, works in a caller workspace, is
+ *    asynchronous on the given HIP stream and performs no host synchronisation and no
+ *    device-to-host copy.
+ *  - Errors are return codes; arguments are validated on the host before any launch and a
+ *    failed call leaves the outputs untouched.  No C++ exception crosses this boundary.
+ *  - All calls on one lsh_tables must be made with the device it was built on current.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *  - Word ids and beam ids are 0-based; a beam id is the row index inside its sentence.
+ */
+#ifndef LSHBEAM_H
+#define LSHBEAM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lsh_tables lsh_tables; /* opaque; owns the device tables */
+
+typedef enum {
+    LSH_OK = 0,
+    LSH_ERR_INVALID_ARG = 1,
+    LSH_ERR_UNSUPPORTED = 2,
+    LSH_ERR_BUILD_FAILED = 3,
+    LSH_ERR_OOM = 4,
+    LSH_ERR_HIP = 5,
+    LSH_ERR_WORKSPACE_TOO_SMALL = 6
+} lsh_status;
+
+typedef enum { LSH_F32 = 0, LSH_BF16 = 1 } lsh_dtype;
+
+/* The paper's hash hyper-parameters {K, u, W} (text after Eq. 8) plus the layout of E. */
+typedef struct {
+    int32_t V;       /* vocabulary size = rows of E, 1 .. 2^24                                   */
+    int32_t d;       /* hidden size = columns of E                                               */
+    int64_t ld_e;    /* row pitch of E in elements, >= d                                         */
+    int32_t e_dtype; /* lsh_dtype: fp32, or bf16 bit patterns                                    */
+    int32_t K;       /* WTA window: each code is the argmax over K permuted dims, 2 <= K <= d    */
+    int32_t P;       /* number of permutations = codes per vector                                */
+    int32_t bands;   /* W; P % W == 0; u = P / W codes per band; u * ceil(log2 K) <= 30          */
+    uint64_t seed;   /* seeds the cuckoo hash functions only (results never depend on it)        */
+} lsh_build_params;
+
+/* Build the index over the rows of E (once, after training; section "Cuckoo lookup", first step).
+ *   E_dev      [V, ld_e] row-major, fp32 or bf16.  BORROWED: must stay valid and unchanged until
+ *              lsh_free_tables; the decode step gathers its rows.
+ *   perms_dev  int32 [P, K]: row p holds the first K entries of permutation p of 0..d-1
+ *              (Eq. 5: Permute_p(x)[k] = x[perms[p][k]]).  Copied; validated to lie in [0, d).
+ * Computes the band code of every row on the device (ties in the argmax go to the lowest k),
+ * groups word ids by band code into one flat array per band (ids ascending inside a span) and
+ * stores (start, length) of every span in a two-choice cuckoo table per band.
+ * Synchronous.  On success *out receives the handle. */
+lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const lsh_build_params* p,
+                            void* hip_stream, lsh_tables** out);
+
+void lsh_free_tables(lsh_tables* t); /* NULL-safe */
+
+/* Per-call shape of a decode step; the paper's remaining hyper-parameters {B, T, t}. */
+typedef struct {
+    int32_t S;          /* sentences in the call; hidden rows R = S * B                          */
+    int32_t B;          /* beams per sentence, 1 .. 256; also the number of results per sentence */
+    int32_t T;          /* length of the top-frequent word list (may be 0)                       */
+    int32_t threshold;  /* t of Eq. 10; only t = 1 is implemented (else LSH_ERR_UNSUPPORTED)     */
+    int32_t full_vocab; /* 1: skip hashing, the candidate list is all of V (Eq. 1-2 as printed)  */
+} lsh_step_params;
+
+/* Bytes of workspace lsh_decode_step needs for these parameters (0 on invalid arguments). */
+size_t lsh_step_workspace_bytes(const lsh_tables* t, const lsh_step_params* sp);
+
+/* One decode step for S sentences of B beams.
+ *   H_dev            fp32 [S*B, d], pitch d: top-layer hidden states, sentence-major.
+ *   beam_scores_dev  fp32 [S*B]: accumulated log-probability of each beam (-inf = dead beam).
+ *   topfreq_dev      int32 [T]: ids of the top-frequent words V_T (Eq. 3); ids outside [0, V)
+ *                    are ignored; duplicates are harmless.
+ *   workspace_dev    >= lsh_step_workspace_bytes() bytes, 256-byte aligned; contents need not be
+ *                    initialised and are overwritten.  Two steps that overlap in time must not
+ *                    share a workspace.
+ * Per sentence s: V_LSH,s = V_T U { j : some row of s shares a band code with E_j } in ascending
+ * id order; logit = H_s * E[V_LSH,s]^T accumulated in fp32; log-probabilities normalised over
+ * V_LSH,s; the B best (beam, word) pairs by beam_score + log-probability, best first, equal
+ * scores ordered by lower beam then lower word id.
+ *   out_beam_dev / out_word_dev / out_score_dev   [S, B].  If fewer than B pairs have a finite
+ *   score the tail is (-1, -1, -inf). */
+lsh_status lsh_decode_step(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
+                           const int32_t* topfreq_dev, const lsh_step_params* sp,
+                           void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
+                           int32_t* out_word_dev, float* out_score_dev, void* hip_stream);
+
+/* ---- inspection (synchronous device-to-host copies; never on the timed path) ---------------- */
+
+/* Band codes (Eq. 6-8) of R fp32 rows of pitch d, computed by the same device hash routine the
+ * step uses.  codes_host is int32 [R, W]. */
+lsh_status lsh_debug_codes(const lsh_tables* t, const float* H_dev, int32_t R, int32_t* codes_host);
+
+/* Band codes of the embedding rows [row0, row0+n) as computed at build time; int32 [n, W]. */
+lsh_status lsh_debug_embedding_codes(const lsh_tables* t, int32_t row0, int32_t n,
+                                     int32_t* codes_host);
+
+/* T_w[code] read THROUGH the device cuckoo table: *n_out = span length or -1 if the code has no
+ * bucket; up to cap ids are written. */
+lsh_status lsh_debug_bucket(const lsh_tables* t, int32_t band, int32_t code, int32_t* words_host,
+                            int32_t cap, int32_t* n_out);
+
+/* The flat layout of one band: distinct codes ascending, span offsets, word ids [V]. */
+lsh_status lsh_debug_csr(const lsh_tables* t, int32_t band, int32_t* n_keys_out, int32_t* keys_host,
+                         int32_t* offsets_host, int32_t cap_keys, int32_t* words_host);
+
+/* Slots in one band's cuckoo table and keys stored (capacity is a power of two >= 2 * keys). */
+lsh_status lsh_debug_cuckoo_shape(const lsh_tables* t, int32_t band, int32_t* capacity_out,
+                                  int32_t* n_keys_out);
+
+/* Candidate list of sentence s left in the workspace by the last LSH step on it. */
+lsh_status lsh_debug_candidates(const lsh_tables* t, const void* workspace_dev,
+                                const lsh_step_params* sp, int32_t s, int32_t* cand_host,
+                                int32_t cap, int32_t* n_out);
+
+/* Log-probabilities of sentence s from the last step on this workspace: lp_host is fp32
+ * [B, cap] (row pitch cap), columns in candidate-list order; *n_out = candidate count. */
+lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
+                              const lsh_step_params* sp, int32_t s, float* lp_host, int32_t cap,
+                              int32_t* n_out);
+
+/* ---- per-kernel timing -------------------------------------------------------------------- */
+
+#define LSH_NUM_KERNELS 3 /* 0 candidates (hash+probe+merge), 1 gathered logits, 2 select */
+
+/* Start recording the device start/stop time of every kernel of the next steps (at most
+ * max_steps of them) on this handle; lsh_profile_end synchronises the device, writes the mean
+ * duration in milliseconds of each kernel and the number of recorded launches, and stops. */
+lsh_status lsh_profile_begin(lsh_tables* t, int32_t max_steps);
+lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
+                           int32_t launches_out[LSH_NUM_KERNELS]);
+const char* lsh_kernel_name(int32_t which);
+
+const char* lsh_status_string(lsh_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSHBEAM_H */

@@ -1,0 +1,273 @@
+"""ctypes binding of include/lshbeam.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblshbeam.so")
+
+LSH_F32, LSH_BF16 = 0, 1
+NUM_KERNELS = 3
+
+# every symbol include/lshbeam.h declares
+EXPORTED_SYMBOLS = (
+    "lsh_build_tables", "lsh_free_tables", "lsh_step_workspace_bytes", "lsh_decode_step",
+    "lsh_debug_codes", "lsh_debug_embedding_codes", "lsh_debug_bucket", "lsh_debug_csr",
+    "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profile_begin",
+    "lsh_profile_end", "lsh_kernel_name", "lsh_status_string",
+)
+
+
+class LshBeamError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {_status_string(status)} (status {status})")
+
+
+class BuildParams(ctypes.Structure):
+    _fields_ = [("V", ctypes.c_int32), ("d", ctypes.c_int32), ("ld_e", ctypes.c_int64),
+                ("e_dtype", ctypes.c_int32), ("K", ctypes.c_int32), ("P", ctypes.c_int32),
+                ("bands", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+
+
+class StepParams(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int32), ("B", ctypes.c_int32), ("T", ctypes.c_int32),
+                ("threshold", ctypes.c_int32), ("full_vocab", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load liblshbeam.so (built in-tree by `python -m paper_1806_00588_amd.build`).  Raises if
+    it is missing: there is no fallback implementation."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_1806_00588_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.lsh_build_tables.argtypes = [vp, vp, ctypes.POINTER(BuildParams), vp, ctypes.POINTER(vp)]
+    lib.lsh_free_tables.argtypes = [vp]
+    lib.lsh_free_tables.restype = None
+    lib.lsh_step_workspace_bytes.argtypes = [vp, ctypes.POINTER(StepParams)]
+    lib.lsh_step_workspace_bytes.restype = sz
+    lib.lsh_decode_step.argtypes = [vp, vp, vp, vp, ctypes.POINTER(StepParams), vp, sz, vp, vp, vp, vp]
+    lib.lsh_debug_codes.argtypes = [vp, vp, i32, i32p]
+    lib.lsh_debug_embedding_codes.argtypes = [vp, i32, i32, i32p]
+    lib.lsh_debug_bucket.argtypes = [vp, i32, i32, i32p, i32, i32p]
+    lib.lsh_debug_csr.argtypes = [vp, i32, i32p, i32p, i32p, i32, i32p]
+    lib.lsh_debug_cuckoo_shape.argtypes = [vp, i32, i32p, i32p]
+    lib.lsh_debug_candidates.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32, i32p, i32, i32p]
+    lib.lsh_debug_logprobs.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32,
+                                       ctypes.POINTER(ctypes.c_float), i32, i32p]
+    lib.lsh_profile_begin.argtypes = [vp, i32]
+    lib.lsh_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_double), i32p]
+    lib.lsh_kernel_name.argtypes = [i32]
+    lib.lsh_kernel_name.restype = ctypes.c_char_p
+    lib.lsh_status_string.argtypes = [ctypes.c_int]
+    lib.lsh_status_string.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _status_string(status: int) -> str:
+    try:
+        return load_library().lsh_status_string(status).decode()
+    except Exception:
+        return "?"
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise LshBeamError(status, what)
+
+
+def kernel_names():
+    lib = load_library()
+    return [lib.lsh_kernel_name(i).decode() for i in range(NUM_KERNELS)]
+
+
+def _i32p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+
+
+def _stream_ptr(stream) -> int:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def _require_cuda(x, name, dtypes):
+    if not x.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if x.dtype not in dtypes:
+        raise ValueError(f"{name}: dtype {x.dtype} not in {dtypes}")
+    if not x.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+class Tables:
+    """Owns an lsh_tables handle and keeps the borrowed embedding tensor alive."""
+
+    def __init__(self, handle: int, E, K: int, P: int, W: int, e_dtype: int):
+        self._h = handle
+        self.E = E
+        self.V, self.d = int(E.shape[0]), int(E.shape[1])
+        self.K, self.P, self.W, self.e_dtype = K, P, W, e_dtype
+
+    @property
+    def handle(self) -> int:
+        if not self._h:
+            raise ValueError("tables already freed")
+        return self._h
+
+    def close(self):
+        if self._h:
+            load_library().lsh_free_tables(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- inspection -------------------------------------------------------------------------
+    def debug_codes(self, H) -> np.ndarray:
+        import torch
+        _require_cuda(H, "H", (torch.float32,))
+        R = int(H.shape[0])
+        out = np.empty((R, self.W), dtype=np.int32)
+        _check(load_library().lsh_debug_codes(self.handle, H.data_ptr(), R, _i32p(out)),
+               "lsh_debug_codes")
+        return out
+
+    def debug_embedding_codes(self, row0: int = 0, n: Optional[int] = None) -> np.ndarray:
+        n = self.V - row0 if n is None else n
+        out = np.empty((n, self.W), dtype=np.int32)
+        _check(load_library().lsh_debug_embedding_codes(self.handle, row0, n, _i32p(out)),
+               "lsh_debug_embedding_codes")
+        return out
+
+    def debug_bucket(self, band: int, code: int):
+        out = np.empty(self.V, dtype=np.int32)
+        n = ctypes.c_int32(0)
+        _check(load_library().lsh_debug_bucket(self.handle, band, int(code), _i32p(out), self.V,
+                                               ctypes.byref(n)), "lsh_debug_bucket")
+        return None if n.value < 0 else out[: n.value].copy()
+
+    def debug_csr(self, band: int):
+        nk = ctypes.c_int32(0)
+        lib = load_library()
+        _check(lib.lsh_debug_csr(self.handle, band, ctypes.byref(nk), None, None, 0, None),
+               "lsh_debug_csr")
+        keys = np.empty(nk.value, dtype=np.int32)
+        offs = np.empty(nk.value + 1, dtype=np.int32)
+        words = np.empty(self.V, dtype=np.int32)
+        _check(lib.lsh_debug_csr(self.handle, band, ctypes.byref(nk), _i32p(keys), _i32p(offs),
+                                 nk.value, _i32p(words)), "lsh_debug_csr")
+        return keys, offs, words
+
+    def debug_cuckoo_shape(self, band: int):
+        cap, nk = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(load_library().lsh_debug_cuckoo_shape(self.handle, band, ctypes.byref(cap),
+                                                     ctypes.byref(nk)), "lsh_debug_cuckoo_shape")
+        return cap.value, nk.value
+
+    def debug_candidates(self, workspace, sp: StepParams, s: int) -> np.ndarray:
+        out = np.empty(self.V, dtype=np.int32)
+        n = ctypes.c_int32(0)
+        _check(load_library().lsh_debug_candidates(self.handle, workspace.data_ptr(),
+                                                   ctypes.byref(sp), s, _i32p(out), self.V,
+                                                   ctypes.byref(n)), "lsh_debug_candidates")
+        return out[: n.value].copy()
+
+    def debug_logprobs(self, workspace, sp: StepParams, s: int, cap: Optional[int] = None):
+        cap = self.V if cap is None else cap
+        out = np.empty((sp.B, cap), dtype=np.float32)
+        n = ctypes.c_int32(0)
+        _check(load_library().lsh_debug_logprobs(
+            self.handle, workspace.data_ptr(), ctypes.byref(sp), s,
+            out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), cap, ctypes.byref(n)),
+            "lsh_debug_logprobs")
+        return out[:, : min(n.value, cap)].copy()
+
+    # ---- per-kernel timing ------------------------------------------------------------------
+    def profile_begin(self, max_steps: int):
+        _check(load_library().lsh_profile_begin(self.handle, max_steps), "lsh_profile_begin")
+
+    def profile_end(self):
+        ms = (ctypes.c_double * NUM_KERNELS)()
+        n = (ctypes.c_int32 * NUM_KERNELS)()
+        _check(load_library().lsh_profile_end(self.handle, ms, n), "lsh_profile_end")
+        return {name: (ms[i], n[i]) for i, name in enumerate(kernel_names())}
+
+
+def build_tables(E, perms, K: int, bands: int, seed: int = 0, stream=None) -> Tables:
+    """lsh_build_tables.  E: device tensor [V, d], float32, or bfloat16 / int16 / uint16 holding
+    bf16 bit patterns; perms: device int32 [P, K]."""
+    import torch
+    lib = load_library()
+    if E.dtype == torch.float32:
+        dt = LSH_F32
+    elif E.dtype in (torch.bfloat16, torch.int16, torch.uint16):
+        dt = LSH_BF16
+    else:
+        raise ValueError(f"E: unsupported dtype {E.dtype}")
+    _require_cuda(E, "E", (E.dtype,))
+    _require_cuda(perms, "perms", (torch.int32,))
+    if E.dim() != 2 or perms.dim() != 2 or int(perms.shape[1]) != K:
+        raise ValueError("E must be [V, d] and perms [P, K]")
+    bp = BuildParams(int(E.shape[0]), int(E.shape[1]), int(E.stride(0)), dt, K,
+                     int(perms.shape[0]), bands, seed)
+    out = ctypes.c_void_p(0)
+    _check(lib.lsh_build_tables(E.data_ptr(), perms.data_ptr(), ctypes.byref(bp),
+                                _stream_ptr(stream), ctypes.byref(out)), "lsh_build_tables")
+    return Tables(out.value, E, K, int(perms.shape[0]), bands, dt)
+
+
+def step_params(S: int, B: int, T: int, threshold: int = 1, full_vocab: bool = False) -> StepParams:
+    return StepParams(S, B, T, threshold, 1 if full_vocab else 0)
+
+
+def step_workspace_bytes(tables: Tables, sp: StepParams) -> int:
+    return int(load_library().lsh_step_workspace_bytes(tables.handle, ctypes.byref(sp)))
+
+
+def decode_step(tables: Tables, H, beam_scores, topfreq, sp: StepParams, workspace, out_beam,
+                out_word, out_score, stream=None):
+    """lsh_decode_step: asynchronous on `stream` (default: torch's current stream)."""
+    import torch
+    _require_cuda(H, "H", (torch.float32,))
+    _require_cuda(beam_scores, "beam_scores", (torch.float32,))
+    _require_cuda(out_beam, "out_beam", (torch.int32,))
+    _require_cuda(out_word, "out_word", (torch.int32,))
+    _require_cuda(out_score, "out_score", (torch.float32,))
+    R = sp.S * sp.B
+    if H.numel() != R * tables.d or beam_scores.numel() != R:
+        raise ValueError("H must be [S*B, d] and beam_scores [S*B]")
+    if min(out_beam.numel(), out_word.numel(), out_score.numel()) < R:
+        raise ValueError("outputs must hold S*B elements")
+    tf_ptr = 0
+    if topfreq is not None:
+        _require_cuda(topfreq, "topfreq", (torch.int32,))
+        if topfreq.numel() < sp.T:
+            raise ValueError("topfreq shorter than T")
+        tf_ptr = topfreq.data_ptr()
+    _check(load_library().lsh_decode_step(
+        tables.handle, H.data_ptr(), beam_scores.data_ptr(), tf_ptr, ctypes.byref(sp),
+        workspace.data_ptr(), workspace.numel() * workspace.element_size(), out_beam.data_ptr(),
+        out_word.data_ptr(), out_score.data_ptr(), _stream_ptr(stream)), "lsh_decode_step")

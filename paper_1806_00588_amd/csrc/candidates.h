@@ -1,0 +1,190 @@
+// Winner-take-all hashing, cuckoo probe, bucket walk and candidate-list compaction.
+//
+//   k_band_codes  : band codes (Eq. 4-8) of n rows; used on E at build time and for inspection.
+//   k_candidates  : one workgroup per sentence.  Hashes the sentence's B hidden rows, probes the
+//                   per-band cuckoo tables (Algorithm 1, lines 1-2), walks the hit spans
+//                   (lines 3-6) marking a V-bit presence bitmap held in LDS, ORs in the
+//                   top-frequent words (Eq. 3) and compacts the bitmap into an ascending id list
+//                   (Eq. 10 with t = 1).
+//
+// The paper keeps an integer hit matrix L[B,V] in global memory and compacts it with a shared-
+// memory scan by lane 0 of each warp.  With t = 1 only "hit at least once" matters, so L
+// collapses to one bit per word per sentence; V bits fit in LDS (25 KB at V = 200k), the marks
+// are idempotent LDS atomic ORs, and compaction is a popcount + wave prefix sum.  Unequal span
+// lengths (the paper's warp-divergence problem) are handled by flattening: span lengths are
+// prefix-summed across all (row, band) pairs and the flat element range is dealt to threads
+// evenly, each finding its span by binary search.
+#pragma once
+#include "device_utils.h"
+
+namespace lshbeam {
+
+// One slot of a cuckoo table: 16 bytes so a probe is a single 128-bit load.
+struct __attribute__((aligned(16))) Slot {
+    int32_t key;     // band code, or -1 when empty (codes are >= 0)
+    uint32_t start;  // first position of the span in the band's flat word array
+    uint32_t len;    // span length
+    uint32_t pad;
+};
+
+// Per-band description of its cuckoo table: two multiplicative hashes over one slot array.
+struct __attribute__((aligned(32))) BandMeta {
+    uint32_t slot_off;  // first slot of this band in the concatenated slot array
+    uint32_t shift;     // 32 - log2(capacity)
+    uint32_t a0, b0, a1, b1;
+    uint32_t pad0, pad1;
+};
+
+__host__ __device__ __forceinline__ uint32_t cuckoo_hash(uint32_t a, uint32_t b, uint32_t key,
+                                                         uint32_t shift) {
+    return (a * key + b) >> shift;
+}
+
+// Both slots are loaded unconditionally: no dependent second probe, no divergence.
+__device__ __forceinline__ void cuckoo_find(const Slot* __restrict__ slots, const BandMeta& m,
+                                            int32_t code, uint32_t* start, uint32_t* len) {
+    const uint32_t h0 = cuckoo_hash(m.a0, m.b0, (uint32_t)code, m.shift);
+    const uint32_t h1 = cuckoo_hash(m.a1, m.b1, (uint32_t)code, m.shift);
+    const int4 s0 = *reinterpret_cast<const int4*>(slots + m.slot_off + h0);
+    const int4 s1 = *reinterpret_cast<const int4*>(slots + m.slot_off + h1);
+    const bool hit0 = s0.x == code, hit1 = s1.x == code;
+    *start = hit0 ? (uint32_t)s0.y : (uint32_t)s1.y;
+    *len = hit0 ? (uint32_t)s0.z : (hit1 ? (uint32_t)s1.z : 0u);
+}
+
+// Eq. 4-8 for one (row, band): u windowed argmaxes (strict '>', so the lowest k wins a tie),
+// packed with the first code in the most significant bits.
+template <typename ET>
+__device__ __forceinline__ int32_t band_code_of(const ET* __restrict__ row,
+                                                const int32_t* __restrict__ perms, int w, int u,
+                                                int K, int bits) {
+    int32_t code = 0;
+    for (int i = 0; i < u; ++i) {
+        const int32_t* pm = perms + (size_t)(w * u + i) * K;
+        int best = 0;
+        float bv = elem_f32(row + pm[0]);
+        for (int k = 1; k < K; ++k) {
+            const float v = elem_f32(row + pm[k]);
+            if (v > bv) { bv = v; best = k; }
+        }
+        code = (code << bits) | best;
+    }
+    return code;
+}
+
+template <typename ET>
+__global__ void __launch_bounds__(256)
+k_band_codes(const ET* __restrict__ X, int64_t ld, int64_t n, const int32_t* __restrict__ perms,
+             int P, int K, int W, int bits, int32_t* __restrict__ out) {
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= n * W) return;
+    const int64_t row = idx / W;
+    const int w = (int)(idx - row * W);
+    out[idx] = band_code_of<ET>(X + row * ld, perms, w, P / W, K, bits);
+}
+
+constexpr int kCandThreads = 1024;
+constexpr int kCandWaves = kCandThreads / kWave;
+
+// LDS words k_candidates needs for a vocabulary of V words.
+__host__ __device__ inline size_t candidates_lds_words(int V) {
+    const size_t nwords = ((size_t)V + 31) / 32;
+    return nwords + 3 * (size_t)kCandThreads + 64;
+}
+
+__global__ void __launch_bounds__(kCandThreads)
+k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restrict__ perms, int P,
+             int K, int W, int bits, const Slot* __restrict__ slots,
+             const BandMeta* __restrict__ bands, const int32_t* __restrict__ words, int V,
+             const int32_t* __restrict__ topfreq, int T, int32_t* __restrict__ cand,
+             int32_t* __restrict__ count) {
+    extern __shared__ uint32_t smem[];
+    const int nwords = (V + 31) >> 5;
+    uint32_t* bm = smem;                         // presence bitmap, V bits
+    uint32_t* p_start = bm + nwords;             // span start of each pair in the chunk
+    uint32_t* p_band = p_start + kCandThreads;   // its band
+    uint32_t* p_pref = p_band + kCandThreads;    // exclusive prefix of span lengths
+    uint32_t* wsum = p_pref + kCandThreads;      // scan scratch (>= kCandWaves + 1)
+
+    const int s = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int u = P / W;
+
+    for (int i = tid; i < nwords; i += kCandThreads) bm[i] = 0u;
+    __syncthreads();
+
+    // Eq. 3: the top-frequent words are members of every candidate list.
+    for (int i = tid; i < T; i += kCandThreads) {
+        const int32_t id = topfreq[i];
+        if (id >= 0 && id < V) atomicOr(&bm[id >> 5], 1u << (id & 31));
+    }
+
+    // Algorithm 1 for every (row, band) pair of the sentence, kCandThreads pairs at a time.
+    const int npairs = B * W;
+    for (int base = 0; base < npairs; base += kCandThreads) {
+        const int pair = base + tid;
+        uint32_t start = 0, len = 0, w = 0;
+        if (pair < npairs) {
+            const int i = pair / W;
+            w = pair - i * W;
+            const float* row = H + ((size_t)s * B + i) * d;
+            const int32_t code = band_code_of<float>(row, perms, (int)w, u, K, bits);
+            const BandMeta m = bands[w];
+            cuckoo_find(slots, m, code, &start, &len);
+        }
+        uint32_t total;
+        const uint32_t incl = block_incl_scan(len, wsum, &total);
+        p_start[tid] = start;
+        p_band[tid] = w;
+        p_pref[tid] = incl - len;
+        __syncthreads();
+        // flat walk over all spans of the chunk: element e belongs to the last pair whose
+        // exclusive prefix is <= e
+        for (uint32_t e = tid; e < total; e += kCandThreads) {
+            int lo = 0, hi = kCandThreads;  // first index with p_pref > e, in (lo, hi]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (p_pref[mid] <= e) lo = mid; else hi = mid;
+            }
+            const int32_t id =
+                words[(size_t)p_band[lo] * V + p_start[lo] + (e - p_pref[lo])];
+            atomicOr(&bm[id >> 5], 1u << (id & 31));
+        }
+        __syncthreads();
+    }
+
+    // Compaction: each wave owns a contiguous range of bitmap words (a multiple of 64 of them).
+    const int wv = wave_id(), ln = lane_id();
+    int per_wave = (nwords + kCandWaves - 1) / kCandWaves;
+    per_wave = (per_wave + kWave - 1) / kWave * kWave;
+    const int wbeg = wv * per_wave;
+    const int wend = min(nwords, wbeg + per_wave);
+    uint32_t cnt = 0;
+    for (int i = wbeg + ln; i < wend; i += kWave) cnt += __popc(bm[i]);
+    cnt = wave_sum(cnt);
+    if (ln == 0) wsum[wv] = cnt;
+    __syncthreads();
+    uint32_t running = 0, total = 0;
+    for (int i = 0; i < kCandWaves; ++i) {
+        const uint32_t x = wsum[i];
+        if (i < wv) running += x;
+        total += x;
+    }
+    int32_t* out = cand + (size_t)s * V;
+    for (int i0 = wbeg; i0 < wend; i0 += kWave) {
+        const int i = i0 + ln;
+        uint32_t bitsw = (i < wend) ? bm[i] : 0u;
+        const uint32_t c = __popc(bitsw);
+        const uint32_t incl = wave_incl_scan(c);
+        uint32_t off = running + incl - c;
+        while (bitsw) {
+            const int b = __ffs(bitsw) - 1;
+            out[off++] = (i << 5) + b;
+            bitsw &= bitsw - 1;
+        }
+        running += __shfl(incl, kWave - 1, kWave);
+    }
+    if (tid == 0) count[s] = (int32_t)total;
+}
+
+}  // namespace lshbeam

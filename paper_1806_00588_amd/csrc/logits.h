@@ -1,0 +1,165 @@
+// Gathered contraction  Logit[r, c] = sum_k H[r, k] * E[cand_s[c], k]   (Eq. 2 on the columns of
+// the candidate list; the paper's separate "construct E_LSH" copy is fused away: candidate rows
+// of E are gathered straight into the matrix-core operands).
+//
+// Work unit ("tile"): one sentence s, one group of 16 hidden rows (M-tile) and 16 candidates.
+// A workgroup of WAVES waves splits the hidden dimension between its waves; every wave issues
+// v_mfma_f32_16x16x4_f32 over its share of k and the partial 16x16 tiles are summed through LDS
+// in a fixed wave order (deterministic).
+//
+// Operand layout of v_mfma_f32_16x16x4_f32 (A is 16x4, B is 4x16, D is 16x16, 64 lanes):
+//   lane l supplies A[i = l % 16][k = l / 16] and B[k = l / 16][j = l % 16];
+//   lane l receives D[i = 4 * (l / 16) + r][j = l % 16] in accumulator register r = 0..3.
+// The k slots of one instruction may hold any four k indices as long as A and B agree, so lane l
+// loads ONE 16-byte chunk of its candidate's row (fp32: 4 consecutive k, bf16: 8) and feeds one
+// element per instruction: per load instruction a wave touches 16 rows x 64 contiguous bytes.
+#pragma once
+#include "device_utils.h"
+
+namespace lshbeam {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+template <typename ET> struct ElemTraits;
+template <> struct ElemTraits<float> {
+    static constexpr int VEC = 4;  // elements per 16-byte load
+    __device__ static __forceinline__ void load16(const float* p, float (&out)[4]) {
+        const float4 v = *reinterpret_cast<const float4*>(p);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    }
+};
+template <> struct ElemTraits<uint16_t> {
+    static constexpr int VEC = 8;
+    __device__ static __forceinline__ void load16(const uint16_t* p, float (&out)[8]) {
+        const uint4 v = *reinterpret_cast<const uint4*>(p);
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            out[2 * i] = __uint_as_float(w[i] << 16);
+            out[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+
+constexpr int kTileN = 16;  // candidates per tile
+constexpr int kTileM = 16;  // hidden rows per tile
+constexpr int kMaxSentencesLogits = 4096;
+
+// ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
+// d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
+__global__ void __launch_bounds__(WAVES * kWave)
+k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
+         const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
+         float* __restrict__ logits, int64_t cpitch, int32_t* __restrict__ tickets) {
+    constexpr int VEC = ElemTraits<ET>::VEC;
+    constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
+    __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
+    __shared__ float red[WAVES][4][kWave];
+
+    const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    const int MT = (B + kTileM - 1) / kTileM;
+
+    // The select kernel counts finished rows per sentence; its counters start from zero.
+    if (blockIdx.x == 0)
+        for (int i = tid; i < S; i += WAVES * kWave) tickets[i] = 0;
+
+    // exclusive prefix of tiles per sentence (wave 0, 64 sentences at a time)
+    if (wv == 0) {
+        uint32_t carry = 0;
+        for (int base = 0; base < S; base += kWave) {
+            const int s = base + ln;
+            uint32_t n = 0;
+            if (s < S) {
+                const int C = count ? count[s] : V;
+                n = (uint32_t)MT * (uint32_t)((C + kTileN - 1) / kTileN);
+            }
+            const uint32_t incl = wave_incl_scan(n);
+            if (s < S) tile_pref[s] = carry + incl - n;
+            carry += __shfl(incl, kWave - 1, kWave);
+        }
+        if (ln == 0) tile_pref[S] = carry;
+    }
+    __syncthreads();
+    const uint32_t total_tiles = tile_pref[S];
+
+    // Workgroups are dealt to the 8 XCDs round-robin by the dispatcher; renumber them so that
+    // consecutive logical ids (which take neighbouring tiles) share an XCD and its L2.
+    const uint32_t G = gridDim.x;
+    const uint32_t per_xcd = G >> 3;
+    const uint32_t logical = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+
+    const int col = ln & 15, kq = ln >> 4;
+    const int nks = (d + KSTEP - 1) / KSTEP;
+
+    for (uint32_t t = logical; t < total_tiles; t += G) {
+        int lo = 0, hi = S;  // sentence: last s with tile_pref[s] <= t
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tile_pref[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int s = lo;
+        const uint32_t tl = t - tile_pref[s];
+        const int nt = tl / MT, mt = tl - nt * MT;
+        const int C = count ? count[s] : V;
+        const int n0 = nt * kTileN;
+
+        // out-of-range lanes are clamped onto a valid row; their results are never stored
+        const int cidx = min(n0 + col, C - 1);
+        const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        const ET* erow = E + j * ld;
+        const int hr = min(mt * kTileM + col, B - 1);
+        const float* hrow = H + ((size_t)s * B + hr) * d;
+
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int ks0 = wv; ks0 < nks; ks0 += WAVES * UNROLL) {
+            float ev[UNROLL][VEC], hv[UNROLL][VEC];
+#pragma unroll
+            for (int uu = 0; uu < UNROLL; ++uu) {
+                const int k = (ks0 + uu * WAVES) * KSTEP + kq * VEC;
+                if (ALIGNED) {
+                    if (k < d) {
+                        ElemTraits<ET>::load16(erow + k, ev[uu]);
+#pragma unroll
+                        for (int q = 0; q < VEC; q += 4) {
+                            const float4 h4 = *reinterpret_cast<const float4*>(hrow + k + q);
+                            hv[uu][q] = h4.x; hv[uu][q + 1] = h4.y;
+                            hv[uu][q + 2] = h4.z; hv[uu][q + 3] = h4.w;
+                        }
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) { ev[uu][q] = 0.f; hv[uu][q] = 0.f; }
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) {
+                        const bool in = (k + q) < d;
+                        ev[uu][q] = in ? elem_f32(erow + k + q) : 0.f;
+                        hv[uu][q] = in ? hrow[k + q] : 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int uu = 0; uu < UNROLL; ++uu)
+#pragma unroll
+                for (int q = 0; q < VEC; ++q)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[uu][q], ev[uu][q], acc, 0, 0, 0);
+        }
+
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[r];
+        __syncthreads();
+        if (tid < kTileM * kTileN) {
+            const int i = tid >> 4, jc = tid & 15;
+            const int src = (i >> 2) * 16 + jc, r = i & 3;
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
+            const int row = mt * kTileM + i, c = n0 + jc;
+            if (row < B && c < C) logits[((size_t)s * B + row) * cpitch + c] = sum;
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace lshbeam

@@ -1,0 +1,559 @@
+// C ABI of the lshbeam library (see include/lshbeam.h): table build, decode step, inspection.
+// gfx950 only.  Host side: argument validation, the once-only grouping of word ids by band code
+// and cuckoo insertion, kernel launches.  Every per-step computation runs in the HIP kernels of
+// candidates.h / logits.h / select.h.
+#include "../../include/lshbeam.h"
+
+#include <hip/hip_ext.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "candidates.h"
+#include "logits.h"
+#include "select.h"
+
+using namespace lshbeam;
+
+namespace {
+
+constexpr int kMaxV = 1 << 24;
+constexpr int kMaxB = 256;
+constexpr size_t kAlign = 256;
+constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
+
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct HostBand {
+    std::vector<int32_t> keys;     // distinct band codes, ascending
+    std::vector<int32_t> offsets;  // keys.size() + 1 span boundaries into the band's word array
+    int capacity = 0;
+    BandMeta meta{};
+};
+
+struct Profiler {
+    bool on = false;
+    int max_steps = 0;
+    std::vector<hipEvent_t> ev[LSH_NUM_KERNELS];  // start/stop pairs
+    int used[LSH_NUM_KERNELS] = {0, 0, 0};
+};
+
+}  // namespace
+
+struct lsh_tables {
+    int device = 0;
+    const void* E = nullptr;
+    int V = 0, d = 0, dtype = 0, K = 0, P = 0, W = 0, u = 0, bits = 0;
+    int64_t ld = 0;
+    int32_t* perms_dev = nullptr;    // [P, K]
+    int32_t* codes_dev = nullptr;    // [V, W] band codes of the embedding rows
+    int32_t* words_dev = nullptr;    // [W, V] word ids grouped by band code
+    Slot* slots_dev = nullptr;       // all bands' cuckoo slots, concatenated
+    BandMeta* bands_dev = nullptr;   // [W]
+    std::vector<HostBand> bands;
+    std::vector<Slot> slots_host;
+    int wg_candidates_lds = 0;
+    Profiler prof;
+};
+
+namespace {
+
+struct SplitMix64 {
+    uint64_t s;
+    uint64_t next() {
+        uint64_t z = (s += 0x9E3779B97F4A7C15ull);
+        z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+        z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+        return z ^ (z >> 31);
+    }
+};
+
+inline int code_bits(int K) {
+    int b = 0;
+    while ((1 << b) < K) ++b;
+    return b;
+}
+
+// Two-choice cuckoo insertion (Pagh & Rodler) of the band's keys into `cap` slots.  Returns false
+// if some insertion exceeds the eviction limit with these hash parameters.
+bool cuckoo_try(const HostBand& hb, const BandMeta& m, int cap, Slot* slots) {
+    for (int i = 0; i < cap; ++i) slots[i] = Slot{-1, 0u, 0u, 0u};
+    int lg = 0;
+    while ((1 << lg) < cap) ++lg;
+    const int max_kicks = 16 * (lg + 1);
+    for (size_t q = 0; q < hb.keys.size(); ++q) {
+        Slot cur{hb.keys[q], (uint32_t)hb.offsets[q], (uint32_t)(hb.offsets[q + 1] - hb.offsets[q]), 0u};
+        const uint32_t h0 = cuckoo_hash(m.a0, m.b0, (uint32_t)cur.key, m.shift);
+        const uint32_t h1 = cuckoo_hash(m.a1, m.b1, (uint32_t)cur.key, m.shift);
+        bool placed = false;
+        if (slots[h0].key < 0) { slots[h0] = cur; placed = true; }
+        else if (slots[h1].key < 0) { slots[h1] = cur; placed = true; }
+        uint32_t pos = h0;
+        for (int kick = 0; !placed && kick < max_kicks; ++kick) {
+            // take slot `pos`; its occupant moves to its own other slot, evicting in turn
+            std::swap(cur, slots[pos]);
+            const uint32_t e0 = cuckoo_hash(m.a0, m.b0, (uint32_t)cur.key, m.shift);
+            const uint32_t e1 = cuckoo_hash(m.a1, m.b1, (uint32_t)cur.key, m.shift);
+            pos = (pos == e0) ? e1 : e0;
+            if (slots[pos].key < 0) { slots[pos] = cur; placed = true; }
+        }
+        if (!placed) return false;
+    }
+    return true;
+}
+
+lsh_status build_cuckoo(HostBand& hb, SplitMix64& rng, std::vector<Slot>& out, uint32_t slot_off) {
+    int cap = 2;
+    while ((size_t)cap < 2 * hb.keys.size()) cap <<= 1;
+    std::vector<Slot> slots;
+    for (int grow = 0; grow < 4; ++grow, cap <<= 1) {
+        slots.resize(cap);
+        int lg = 0;
+        while ((1 << lg) < cap) ++lg;
+        for (int attempt = 0; attempt < 16; ++attempt) {
+            BandMeta m{};
+            m.slot_off = slot_off;
+            m.shift = 32u - (uint32_t)lg;
+            m.a0 = (uint32_t)rng.next() | 1u;
+            m.b0 = (uint32_t)rng.next();
+            m.a1 = (uint32_t)rng.next() | 1u;
+            m.b1 = (uint32_t)rng.next();
+            if (cuckoo_try(hb, m, cap, slots.data())) {
+                hb.capacity = cap;
+                hb.meta = m;
+                out.insert(out.end(), slots.begin(), slots.end());
+                return LSH_OK;
+            }
+        }
+    }
+    return LSH_ERR_BUILD_FAILED;
+}
+
+template <typename... KArgs, typename... Args>
+void launch(lsh_tables* t, int which, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem,
+            hipStream_t stream, Args... args) {
+    Profiler& pf = t->prof;
+    if (pf.on && which >= 0 && pf.used[which] < pf.max_steps) {
+        const int i = pf.used[which]++;
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, stream, pf.ev[which][2 * i],
+                              pf.ev[which][2 * i + 1], 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, stream, args...);
+    }
+}
+
+// Workspace layout of one step.
+struct Workspace {
+    int32_t* cand;       // [S, V]
+    int32_t* count;      // [S]
+    int32_t* tickets;    // [S]
+    float* logits;       // [R, cpitch]
+    uint64_t* part;      // [R, B]
+    int32_t* part_n;     // [R]
+    float* lse;          // [R]
+    uint64_t* merge;     // [S, B*B]
+    int64_t cpitch;
+    size_t bytes;
+};
+
+Workspace carve(const lsh_tables* t, const lsh_step_params* sp, void* base) {
+    Workspace w{};
+    const size_t S = sp->S, B = sp->B, R = S * B, V = t->V;
+    w.cpitch = (int64_t)((V + 63) / 64 * 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return (char*)base + o; };
+    w.cand = (int32_t*)take(sp->full_vocab ? 0 : S * V * sizeof(int32_t));
+    w.count = (int32_t*)take(S * sizeof(int32_t));
+    w.tickets = (int32_t*)take(S * sizeof(int32_t));
+    w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
+    w.part = (uint64_t*)take(R * B * sizeof(uint64_t));
+    w.part_n = (int32_t*)take(R * sizeof(int32_t));
+    w.lse = (float*)take(R * sizeof(float));
+    w.merge = (uint64_t*)take(S * B * B * sizeof(uint64_t));
+    w.bytes = off;
+    return w;
+}
+
+bool step_params_ok(const lsh_tables* t, const lsh_step_params* sp) {
+    return t && sp && sp->S >= 1 && sp->B >= 1 && sp->B <= kMaxB && sp->T >= 0 &&
+           sp->S <= kMaxSentencesLogits && (int64_t)sp->S * sp->B <= (int64_t)INT32_MAX / 2;
+}
+
+int env_int(const char* name, int dflt) {
+    const char* v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : dflt;
+}
+
+template <typename ET, int WAVES>
+void launch_logits_w(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
+                     const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
+                     const Workspace& w) {
+    constexpr int UNROLL = (WAVES >= 16) ? 4 : 8;
+    const ET* E = (const ET*)t->E;
+    if (aligned)
+        launch(t, 1, k_logits<ET, WAVES, UNROLL, true>, dim3(grid), dim3(WAVES * kWave), 0, st, E,
+               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.tickets);
+    else
+        launch(t, 1, k_logits<ET, WAVES, UNROLL, false>, dim3(grid), dim3(WAVES * kWave), 0, st, E,
+               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.tickets);
+}
+
+template <typename ET>
+void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
+                   const int32_t* cand, const int32_t* count, const Workspace& w) {
+    constexpr int VEC = ElemTraits<ET>::VEC;
+    const bool aligned = (t->d % VEC == 0) && (t->ld % VEC == 0) && ((uintptr_t)t->E % 16 == 0) &&
+                         (t->d % 4 == 0) && ((uintptr_t)H % 16 == 0);
+    const int MT = (sp->B + kTileM - 1) / kTileM;
+    const int64_t max_tiles = (int64_t)sp->S * MT * ((t->V + kTileN - 1) / kTileN);
+    // few (sentence, M-tile) groups: little work per step, split k across many waves so that
+    // enough loads are in flight; otherwise 4 waves per tile
+    int waves = (sp->S * MT <= 8) ? 16 : 4;
+    waves = env_int("LSHBEAM_LOGITS_WAVES", waves);
+    if (waves >= 16) {
+        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 512));
+        launch_logits_w<ET, 16>(t, st, grid, aligned, H, sp, cand, count, w);
+    } else if (waves >= 8) {
+        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 1024));
+        launch_logits_w<ET, 8>(t, st, grid, aligned, H, sp, cand, count, w);
+    } else {
+        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 2048));
+        launch_logits_w<ET, 4>(t, st, grid, aligned, H, sp, cand, count, w);
+    }
+}
+
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) {                         \
+            (void)hipGetLastError();                    \
+            return e_ == hipErrorOutOfMemory ? LSH_ERR_OOM : LSH_ERR_HIP; \
+        }                                               \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+const char* lsh_status_string(lsh_status s) {
+    switch (s) {
+        case LSH_OK: return "ok";
+        case LSH_ERR_INVALID_ARG: return "invalid argument";
+        case LSH_ERR_UNSUPPORTED: return "unsupported parameter";
+        case LSH_ERR_BUILD_FAILED: return "cuckoo table build failed";
+        case LSH_ERR_OOM: return "out of device memory";
+        case LSH_ERR_HIP: return "HIP runtime error";
+        case LSH_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    }
+    return "unknown status";
+}
+
+const char* lsh_kernel_name(int32_t which) {
+    switch (which) {
+        case 0: return "k_candidates";
+        case 1: return "k_logits";
+        case 2: return "k_select";
+    }
+    return "";
+}
+
+void lsh_free_tables(lsh_tables* t) {
+    if (!t) return;
+    (void)hipFree(t->perms_dev);
+    (void)hipFree(t->codes_dev);
+    (void)hipFree(t->words_dev);
+    (void)hipFree(t->slots_dev);
+    (void)hipFree(t->bands_dev);
+    for (int k = 0; k < LSH_NUM_KERNELS; ++k)
+        for (hipEvent_t e : t->prof.ev[k]) (void)hipEventDestroy(e);
+    delete t;
+}
+
+lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const lsh_build_params* p,
+                            void* hip_stream, lsh_tables** out) {
+    if (!E_dev || !perms_dev || !p || !out) return LSH_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (p->V < 1 || p->V > kMaxV || p->d < 1 || p->ld_e < p->d) return LSH_ERR_INVALID_ARG;
+    if (p->e_dtype != LSH_F32 && p->e_dtype != LSH_BF16) return LSH_ERR_INVALID_ARG;
+    if (p->K < 2 || p->K > p->d || p->K > 32768) return LSH_ERR_INVALID_ARG;
+    if (p->P < 1 || p->bands < 1 || p->P % p->bands != 0) return LSH_ERR_INVALID_ARG;
+    const int bits = code_bits(p->K), u = p->P / p->bands;
+    if ((int64_t)u * bits > 30) return LSH_ERR_INVALID_ARG;
+    if (candidates_lds_words(p->V) * 4 > kMaxDynLds) return LSH_ERR_UNSUPPORTED;
+    hipStream_t st = (hipStream_t)hip_stream;
+
+    lsh_tables* t = new (std::nothrow) lsh_tables();
+    if (!t) return LSH_ERR_OOM;
+    struct Guard { lsh_tables* t; ~Guard() { if (t) lsh_free_tables(t); } } guard{t};
+    HIP_TRY(hipGetDevice(&t->device));
+    t->E = E_dev; t->V = p->V; t->d = p->d; t->ld = p->ld_e; t->dtype = p->e_dtype;
+    t->K = p->K; t->P = p->P; t->W = p->bands; t->u = u; t->bits = bits;
+    const size_t V = t->V, W = t->W, PK = (size_t)t->P * t->K;
+
+    // permutations: copy, validate on the host
+    std::vector<int32_t> perms(PK);
+    HIP_TRY(hipMemcpyAsync(perms.data(), perms_dev, PK * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int32_t x : perms)
+        if (x < 0 || x >= t->d) return LSH_ERR_INVALID_ARG;
+    HIP_TRY(hipMalloc((void**)&t->perms_dev, PK * sizeof(int32_t)));
+    HIP_TRY(hipMemcpyAsync(t->perms_dev, perms.data(), PK * sizeof(int32_t), hipMemcpyHostToDevice, st));
+
+    // band codes of every embedding row, on the device
+    HIP_TRY(hipMalloc((void**)&t->codes_dev, V * W * sizeof(int32_t)));
+    {
+        const int64_t n = (int64_t)V * W;
+        const dim3 grid((unsigned)((n + 255) / 256)), block(256);
+        if (t->dtype == LSH_F32)
+            hipLaunchKernelGGL(k_band_codes<float>, grid, block, 0, st, (const float*)E_dev, t->ld,
+                               (int64_t)V, t->perms_dev, t->P, t->K, t->W, bits, t->codes_dev);
+        else
+            hipLaunchKernelGGL(k_band_codes<uint16_t>, grid, block, 0, st, (const uint16_t*)E_dev,
+                               t->ld, (int64_t)V, t->perms_dev, t->P, t->K, t->W, bits, t->codes_dev);
+        HIP_TRY(hipGetLastError());
+    }
+    std::vector<int32_t> codes(V * W);
+    HIP_TRY(hipMemcpyAsync(codes.data(), t->codes_dev, V * W * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    // per band: group word ids by code (ids ascending inside a span), then the cuckoo table
+    std::vector<int32_t> words(V * W);
+    std::vector<uint64_t> order(V);
+    t->bands.resize(W);
+    SplitMix64 rng{p->seed ^ 0xC0FFEE1234ABCDEFull};
+    for (size_t w = 0; w < W; ++w) {
+        for (size_t j = 0; j < V; ++j)
+            order[j] = ((uint64_t)(uint32_t)codes[j * W + w] << 32) | (uint64_t)j;
+        std::sort(order.begin(), order.end());
+        HostBand& hb = t->bands[w];
+        for (size_t i = 0; i < V; ++i) {
+            const int32_t code = (int32_t)(order[i] >> 32);
+            if (i == 0 || code != hb.keys.back()) {
+                hb.keys.push_back(code);
+                hb.offsets.push_back((int32_t)i);
+            }
+            words[w * V + i] = (int32_t)(uint32_t)order[i];
+        }
+        hb.offsets.push_back((int32_t)V);
+        const lsh_status rc = build_cuckoo(hb, rng, t->slots_host, (uint32_t)t->slots_host.size());
+        if (rc != LSH_OK) return rc;
+    }
+    std::vector<BandMeta> metas(W);
+    for (size_t w = 0; w < W; ++w) metas[w] = t->bands[w].meta;
+
+    HIP_TRY(hipMalloc((void**)&t->words_dev, V * W * sizeof(int32_t)));
+    HIP_TRY(hipMalloc((void**)&t->slots_dev, t->slots_host.size() * sizeof(Slot)));
+    HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
+    HIP_TRY(hipMemcpyAsync(t->words_dev, words.data(), V * W * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(t->slots_dev, t->slots_host.data(), t->slots_host.size() * sizeof(Slot),
+                           hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(t->bands_dev, metas.data(), W * sizeof(BandMeta), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    t->wg_candidates_lds = (int)(candidates_lds_words(t->V) * sizeof(uint32_t));
+    if (t->wg_candidates_lds > 48 * 1024)
+        HIP_TRY(hipFuncSetAttribute((const void*)k_candidates,
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_candidates_lds));
+    guard.t = nullptr;
+    *out = t;
+    return LSH_OK;
+}
+
+size_t lsh_step_workspace_bytes(const lsh_tables* t, const lsh_step_params* sp) {
+    if (!step_params_ok(t, sp)) return 0;
+    return carve(t, sp, nullptr).bytes;
+}
+
+lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float* beam_scores_dev,
+                           const int32_t* topfreq_dev, const lsh_step_params* sp,
+                           void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
+                           int32_t* out_word_dev, float* out_score_dev, void* hip_stream) {
+    if (!tc || !H_dev || !beam_scores_dev || !sp || !workspace_dev || !out_beam_dev ||
+        !out_word_dev || !out_score_dev)
+        return LSH_ERR_INVALID_ARG;
+    if (!step_params_ok(tc, sp)) return LSH_ERR_INVALID_ARG;
+    if (!sp->full_vocab && sp->T > 0 && !topfreq_dev) return LSH_ERR_INVALID_ARG;
+    if (!sp->full_vocab && sp->threshold != 1) return LSH_ERR_UNSUPPORTED;
+    if ((uintptr_t)workspace_dev % kAlign) return LSH_ERR_INVALID_ARG;
+    lsh_tables* t = const_cast<lsh_tables*>(tc);  // only the profiler state is touched
+    const Workspace w = carve(t, sp, workspace_dev);
+    if (workspace_bytes < w.bytes) return LSH_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const int R = sp->S * sp->B;
+
+    const int32_t* cand = nullptr;
+    const int32_t* count = nullptr;
+    if (!sp->full_vocab) {
+        launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads), (size_t)t->wg_candidates_lds, st,
+               H_dev, sp->B, t->d, (const int32_t*)t->perms_dev, t->P, t->K, t->W, t->bits,
+               (const Slot*)t->slots_dev, (const BandMeta*)t->bands_dev, (const int32_t*)t->words_dev,
+               t->V, topfreq_dev, sp->T, w.cand, w.count);
+        cand = w.cand;
+        count = w.count;
+    }
+    if (t->dtype == LSH_F32) launch_logits<float>(t, st, H_dev, sp, cand, count, w);
+    else launch_logits<uint16_t>(t, st, H_dev, sp, cand, count, w);
+    launch(t, 2, k_select, dim3(R), dim3(kSelThreads), 0, st, (const float*)w.logits, w.cpitch, cand,
+           count, t->V, sp->B, beam_scores_dev, w.part, w.part_n, w.lse, w.merge, w.tickets,
+           out_beam_dev, out_word_dev, out_score_dev);
+    HIP_TRY(hipGetLastError());
+    return LSH_OK;
+}
+
+/* ---- inspection ----------------------------------------------------------------------------- */
+
+lsh_status lsh_debug_codes(const lsh_tables* t, const float* H_dev, int32_t R, int32_t* codes_host) {
+    if (!t || !H_dev || !codes_host || R < 1) return LSH_ERR_INVALID_ARG;
+    int32_t* tmp = nullptr;
+    const int64_t n = (int64_t)R * t->W;
+    HIP_TRY(hipMalloc((void**)&tmp, n * sizeof(int32_t)));
+    hipLaunchKernelGGL(k_band_codes<float>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, 0, H_dev,
+                       (int64_t)t->d, (int64_t)R, (const int32_t*)t->perms_dev, t->P, t->K, t->W,
+                       t->bits, tmp);
+    hipError_t e = hipMemcpy(codes_host, tmp, n * sizeof(int32_t), hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    HIP_TRY(e);
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_embedding_codes(const lsh_tables* t, int32_t row0, int32_t n, int32_t* codes_host) {
+    if (!t || !codes_host || row0 < 0 || n < 0 || (int64_t)row0 + n > t->V) return LSH_ERR_INVALID_ARG;
+    HIP_TRY(hipMemcpy(codes_host, t->codes_dev + (size_t)row0 * t->W, (size_t)n * t->W * sizeof(int32_t),
+                      hipMemcpyDeviceToHost));
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_bucket(const lsh_tables* t, int32_t band, int32_t code, int32_t* words_host,
+                            int32_t cap, int32_t* n_out) {
+    if (!t || !n_out || band < 0 || band >= t->W || cap < 0 || (cap > 0 && !words_host))
+        return LSH_ERR_INVALID_ARG;
+    // read the two slots the device would read, from device memory
+    const BandMeta& m = t->bands[band].meta;
+    *n_out = -1;
+    if (code < 0) return LSH_OK;
+    const uint32_t h[2] = {cuckoo_hash(m.a0, m.b0, (uint32_t)code, m.shift),
+                           cuckoo_hash(m.a1, m.b1, (uint32_t)code, m.shift)};
+    for (int q = 0; q < 2; ++q) {
+        Slot sl;
+        HIP_TRY(hipMemcpy(&sl, t->slots_dev + m.slot_off + h[q], sizeof(Slot), hipMemcpyDeviceToHost));
+        if (sl.key == code) {
+            *n_out = (int32_t)sl.len;
+            const size_t ncopy = std::min<size_t>(sl.len, (size_t)cap);
+            if (ncopy)
+                HIP_TRY(hipMemcpy(words_host, t->words_dev + (size_t)band * t->V + sl.start,
+                                  ncopy * sizeof(int32_t), hipMemcpyDeviceToHost));
+            return LSH_OK;
+        }
+    }
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_csr(const lsh_tables* t, int32_t band, int32_t* n_keys_out, int32_t* keys_host,
+                         int32_t* offsets_host, int32_t cap_keys, int32_t* words_host) {
+    if (!t || band < 0 || band >= t->W || !n_keys_out) return LSH_ERR_INVALID_ARG;
+    const HostBand& hb = t->bands[band];
+    *n_keys_out = (int32_t)hb.keys.size();
+    if (keys_host && offsets_host && cap_keys >= (int32_t)hb.keys.size()) {
+        std::memcpy(keys_host, hb.keys.data(), hb.keys.size() * sizeof(int32_t));
+        std::memcpy(offsets_host, hb.offsets.data(), hb.offsets.size() * sizeof(int32_t));
+    }
+    if (words_host)
+        HIP_TRY(hipMemcpy(words_host, t->words_dev + (size_t)band * t->V, (size_t)t->V * sizeof(int32_t),
+                          hipMemcpyDeviceToHost));
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_cuckoo_shape(const lsh_tables* t, int32_t band, int32_t* capacity_out,
+                                  int32_t* n_keys_out) {
+    if (!t || band < 0 || band >= t->W || !capacity_out || !n_keys_out) return LSH_ERR_INVALID_ARG;
+    *capacity_out = t->bands[band].capacity;
+    *n_keys_out = (int32_t)t->bands[band].keys.size();
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_candidates(const lsh_tables* t, const void* workspace_dev,
+                                const lsh_step_params* sp, int32_t s, int32_t* cand_host,
+                                int32_t cap, int32_t* n_out) {
+    if (!t || !workspace_dev || !n_out || !step_params_ok(t, sp) || sp->full_vocab || s < 0 ||
+        s >= sp->S || cap < 0 || (cap > 0 && !cand_host))
+        return LSH_ERR_INVALID_ARG;
+    const Workspace w = carve(t, sp, const_cast<void*>(workspace_dev));
+    HIP_TRY(hipDeviceSynchronize());
+    int32_t n = 0;
+    HIP_TRY(hipMemcpy(&n, w.count + s, sizeof(int32_t), hipMemcpyDeviceToHost));
+    *n_out = n;
+    const size_t ncopy = (size_t)std::min(n, cap);
+    if (ncopy)
+        HIP_TRY(hipMemcpy(cand_host, w.cand + (size_t)s * t->V, ncopy * sizeof(int32_t),
+                          hipMemcpyDeviceToHost));
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
+                              const lsh_step_params* sp, int32_t s, float* lp_host, int32_t cap,
+                              int32_t* n_out) {
+    if (!t || !workspace_dev || !n_out || !lp_host || !step_params_ok(t, sp) || s < 0 ||
+        s >= sp->S || cap < 1)
+        return LSH_ERR_INVALID_ARG;
+    const Workspace w = carve(t, sp, const_cast<void*>(workspace_dev));
+    HIP_TRY(hipDeviceSynchronize());
+    int32_t C = t->V;
+    if (!sp->full_vocab) HIP_TRY(hipMemcpy(&C, w.count + s, sizeof(int32_t), hipMemcpyDeviceToHost));
+    *n_out = C;
+    const int n = std::min(C, cap);
+    if (n == 0) return LSH_OK;
+    float* tmp = nullptr;
+    HIP_TRY(hipMalloc((void**)&tmp, (size_t)sp->B * cap * sizeof(float)));
+    hipLaunchKernelGGL(k_logprobs_dump, dim3((unsigned)((n + 255) / 256), (unsigned)sp->B), dim3(256), 0,
+                       0, (const float*)w.logits, w.cpitch, (const float*)w.lse, s * sp->B, sp->B, n,
+                       tmp, (int64_t)cap);
+    hipError_t e = hipMemcpy(lp_host, tmp, (size_t)sp->B * cap * sizeof(float), hipMemcpyDeviceToHost);
+    (void)hipFree(tmp);
+    HIP_TRY(e);
+    return LSH_OK;
+}
+
+/* ---- per-kernel timing ---------------------------------------------------------------------- */
+
+lsh_status lsh_profile_begin(lsh_tables* t, int32_t max_steps) {
+    if (!t || max_steps < 1 || max_steps > (1 << 16)) return LSH_ERR_INVALID_ARG;
+    Profiler& pf = t->prof;
+    for (int k = 0; k < LSH_NUM_KERNELS; ++k) {
+        while ((int)pf.ev[k].size() < 2 * max_steps) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            pf.ev[k].push_back(e);
+        }
+        pf.used[k] = 0;
+    }
+    pf.max_steps = max_steps;
+    pf.on = true;
+    return LSH_OK;
+}
+
+lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
+                           int32_t launches_out[LSH_NUM_KERNELS]) {
+    if (!t || !mean_ms_out || !launches_out) return LSH_ERR_INVALID_ARG;
+    Profiler& pf = t->prof;
+    if (!pf.on) return LSH_ERR_INVALID_ARG;
+    pf.on = false;
+    HIP_TRY(hipDeviceSynchronize());
+    for (int k = 0; k < LSH_NUM_KERNELS; ++k) {
+        double total = 0.0;
+        for (int i = 0; i < pf.used[k]; ++i) {
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, pf.ev[k][2 * i], pf.ev[k][2 * i + 1]));
+            total += ms;
+        }
+        launches_out[k] = pf.used[k];
+        mean_ms_out[k] = pf.used[k] ? total / pf.used[k] : 0.0;
+    }
+    return LSH_OK;
+}
+
+}  // extern "C"

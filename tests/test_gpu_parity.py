@@ -1,0 +1,312 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Bit-exact on band codes, bucket contents and candidate lists; log-probabilities and
+scores within 1e-5 * max(1, |lp|, |logit|, |lse|) (the magnitudes entering the fp32 subtraction,
+see gpu_harness); top-B ids equal except inside score ties (gpu_harness.assert_topb_matches)."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_harness import GpuCase, assert_close_logprobs, assert_topb_matches, to_dev
+
+pytestmark = pytest.mark.gpu
+
+_CASES = {}
+
+
+def case(name):
+    if name not in _CASES:
+        _CASES[name] = (workloads.CONFIGS[name], GpuCase.from_config(workloads.CONFIGS[name]))
+    return _CASES[name]
+
+
+def hidden(cfg, gc, steps):
+    return workloads.make_hidden(cfg, gc.E, seed=0, steps=steps)
+
+
+# ---------------------------------------------------------------------------------------------
+# build: codes, buckets, cuckoo
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "paper", "widebeam", "largevocab"])
+def test_embedding_band_codes_bit_exact(name):
+    cfg, gc = case(name)
+    n = min(cfg.V, 50000)
+    want = oracle.band_codes(oracle.wta_codes(gc.E[:n], gc.perms), cfg.W, cfg.K)
+    assert np.array_equal(gc.tables.debug_embedding_codes(0, n), want)
+
+
+@pytest.mark.parametrize("name", ["tiny", "paper", "widebeam", "largevocab"])
+def test_hidden_band_codes_bit_exact(name):
+    cfg, gc = case(name)
+    H = hidden(cfg, gc, 2).reshape(-1, cfg.d)
+    assert np.array_equal(gc.tables.debug_codes(to_dev(H)), gc.index.hidden_band_codes(H))
+
+
+@pytest.mark.parametrize("name,max_keys", [("tiny", None), ("paper", None), ("widebeam", 300),
+                                           ("largevocab", 150)])
+def test_buckets_through_cuckoo_bit_exact(name, max_keys):
+    cfg, gc = case(name)
+    rng = np.random.default_rng(0)
+    for w in range(cfg.W):
+        okeys = np.sort(gc.index.bucket_keys(w))
+        keys, offs, words = gc.tables.debug_csr(w)
+        assert np.array_equal(keys, okeys)                       # distinct codes, ascending
+        assert offs[0] == 0 and offs[-1] == cfg.V and np.all(np.diff(offs) > 0)
+        assert np.array_equal(np.sort(words), np.arange(cfg.V))  # a partition of 0..V-1
+        cap, nk = gc.tables.debug_cuckoo_shape(w)
+        assert nk == len(keys) and cap >= 2 * nk and cap & (cap - 1) == 0
+        probe = okeys if max_keys is None else rng.choice(okeys, size=min(max_keys, len(okeys)),
+                                                          replace=False)
+        for code in probe:
+            got = gc.tables.debug_bucket(w, int(code))
+            assert got is not None and np.array_equal(got, gc.index.bucket(w, int(code)))
+            i = np.searchsorted(keys, code)
+            assert np.array_equal(words[offs[i]:offs[i + 1]], got)
+        present = set(okeys.tolist())
+        limit = 1 << (cfg.u * int(np.ceil(np.log2(cfg.K))))
+        absent = [c for c in rng.integers(0, limit, size=300).tolist() if c not in present]
+        for code in absent[:100]:
+            assert gc.tables.debug_bucket(w, code) is None
+
+
+def test_cuckoo_with_wide_band_codes():
+    # 24-bit band codes (K=64, u=4): far too many possible codes for direct addressing
+    rng = np.random.default_rng(11)
+    V, d, K, P, W = 5000, 96, 64, 8, 2
+    E = rng.standard_normal((V, d)).astype(np.float32)
+    E[1000:2000] = E[:1000]                                       # force multi-word buckets
+    perms = np.stack([rng.permutation(d)[:K] for _ in range(P)]).astype(np.int32)
+    gc = GpuCase(E, perms, np.zeros(0, dtype=np.int32), W)
+    want = oracle.band_codes(oracle.wta_codes(E, perms), W, K)
+    assert want.max() >= 1 << 20
+    assert np.array_equal(gc.tables.debug_embedding_codes(), want)
+    for w in range(W):
+        for code in gc.index.bucket_keys(w):
+            assert np.array_equal(gc.tables.debug_bucket(w, int(code)), gc.index.bucket(w, int(code)))
+    H = E[[5, 1005, 4000]] * 2.0
+    _, _, _, sp, ws = gc.step(H, np.zeros(3, np.float32), 1, 3)
+    assert np.array_equal(gc.tables.debug_candidates(ws, sp, 0),
+                          gc.index.candidates(H, np.zeros(0, np.int32)))
+
+
+# ---------------------------------------------------------------------------------------------
+# decode step
+# ---------------------------------------------------------------------------------------------
+
+def run_and_check(cfg, gc, H, bs, S, B, full_vocab=False, check_lp=True):
+    gb, gw, gs, sp, ws = gc.step(H, bs, S, B, full_vocab=full_vocab)
+    swaps = 0
+    for s in range(S):
+        Hs, bss = H[s * B:(s + 1) * B], bs[s * B:(s + 1) * B]
+        ref = gc.oracle_sentence(Hs, bss, B, full_vocab=full_vocab)
+        if not full_vocab:
+            assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), ref.cand)   # bit-exact list
+        if check_lp:
+            assert_close_logprobs(gc.tables.debug_logprobs(ws, sp, s, cap=len(ref.cand)), ref)
+        swaps += assert_topb_matches(gb[s], gw[s], gs[s], ref, bss)
+    return gb, gw, gs, swaps
+
+
+def test_tiny_all_steps_with_score_feedback():
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, cfg.steps)
+    bs = np.zeros(cfg.R, dtype=np.float32)
+    for step in range(cfg.steps):
+        # each step is checked with the oracle's previous scores fed to both sides (no drift)
+        run_and_check(cfg, gc, H[step], bs, cfg.S, cfg.B)
+        bs = gc.oracle_sentence(H[step], bs, cfg.B).score.astype(np.float32)
+
+
+def test_tiny_full_vocab_equals_oracle_brute_force():
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 3)
+    rng = np.random.default_rng(1)
+    for step in range(3):
+        run_and_check(cfg, gc, H[step], rng.standard_normal(cfg.R).astype(np.float32), 1, cfg.B,
+                      full_vocab=True)
+
+
+def test_tiny_many_sentences_and_other_beam_counts():
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)          # 80 rows
+    rng = np.random.default_rng(2)
+    for S, B in [(5, 16), (2, 17), (80, 1), (3, 20), (1, 33)]:
+        bs = (rng.standard_normal(S * B) * 2).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B)
+    run_and_check(cfg, gc, H[:34], np.zeros(34, np.float32), 2, 17, full_vocab=True)
+
+
+def test_paper_shape_steps():
+    cfg, gc = case("paper")
+    H = hidden(cfg, gc, cfg.steps)
+    bs = np.zeros(cfg.R, dtype=np.float32)
+    for step in range(0, cfg.steps, 5):
+        run_and_check(cfg, gc, H[step], bs, cfg.S, cfg.B)
+        bs = gc.oracle_sentence(H[step], bs, cfg.B).score.astype(np.float32)
+
+
+def test_paper_shape_full_vocab():
+    cfg, gc = case("paper")
+    H = hidden(cfg, gc, 1)
+    run_and_check(cfg, gc, H[0], np.linspace(-3, 0, cfg.R).astype(np.float32), 1, cfg.B,
+                  full_vocab=True)
+
+
+def test_batched_shape():
+    cfg, gc0 = case("paper")                       # same E / perms / top-freq as the paper shape
+    cfg = workloads.CONFIGS["batched"]
+    H = workloads.make_hidden(cfg, gc0.E, seed=0, steps=2)
+    rng = np.random.default_rng(3)
+    run_and_check(cfg, gc0, H[1], -rng.random(cfg.R).astype(np.float32), cfg.S, cfg.B)
+
+
+def test_widebeam_shape():
+    cfg, gc = case("widebeam")
+    H = hidden(cfg, gc, 1)
+    run_and_check(cfg, gc, H[0], np.zeros(cfg.R, np.float32), cfg.S, cfg.B)
+
+
+def test_largevocab_bf16_shape():
+    cfg, gc = case("largevocab")
+    H = hidden(cfg, gc, 1)
+    nS = 12                                         # oracle time: 12 of the 64 sentences
+    gb, gw, gs, sp, ws = gc.step(H[0], np.zeros(cfg.R, np.float32), cfg.S, cfg.B)
+    for s in list(range(nS - 1)) + [cfg.S - 1]:
+        Hs = H[0][s * cfg.B:(s + 1) * cfg.B]
+        ref = gc.oracle_sentence(Hs, np.zeros(cfg.B), cfg.B)
+        assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), ref.cand)
+        assert_close_logprobs(gc.tables.debug_logprobs(ws, sp, s, cap=len(ref.cand)), ref)
+        assert_topb_matches(gb[s], gw[s], gs[s], ref, np.zeros(cfg.B))
+
+
+# ---------------------------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------------------------
+
+def test_no_topfreq_and_empty_candidate_list():
+    cfg, gc = case("tiny")
+    from paper_1806_00588_amd import binding
+    H = hidden(cfg, gc, 2)
+    gb, gw, gs, sp, ws = gc.step(H[0], np.zeros(4, np.float32), 1, 4, T=0)
+    ref = gc.oracle_sentence(H[0], np.zeros(4), 4, topfreq=np.zeros(0, np.int32))
+    assert np.array_equal(gc.tables.debug_candidates(ws, sp, 0), ref.cand)
+    assert_topb_matches(gb[0], gw[0], gs[0], ref, np.zeros(4))
+    # a hidden row whose band codes hit no bucket, and no top-freq list: zero candidates
+    Hz = np.zeros((1, cfg.d), dtype=np.float32)      # all-tie windows: every code is 0
+    codes = gc.index.hidden_band_codes(Hz)[0]
+    if all(gc.index.bucket(w, int(codes[w])) is None for w in range(cfg.W)):
+        gb, gw, gs, sp, ws = gc.step(Hz, np.zeros(1, np.float32), 1, 1, T=0)
+        assert gc.tables.debug_candidates(ws, sp, 0).size == 0
+        assert gb[0, 0] == -1 and gw[0, 0] == -1 and np.isneginf(gs[0, 0])
+
+
+def test_dead_beams_and_padding():
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 1)[0]
+    bs = np.array([-np.inf, -1.0, -np.inf, -2.0], dtype=np.float32)
+    gb, gw, gs, _ = run_and_check(cfg, gc, H, bs, 1, 4)
+    assert set(gb[0].tolist()) <= {1, 3}
+    bs[:] = -np.inf
+    gb, gw, gs, sp, ws = gc.step(H, bs, 1, 4)
+    assert np.all(gb == -1) and np.all(gw == -1) and np.all(np.isneginf(gs))
+
+
+def test_fewer_candidates_than_beams():
+    rng = np.random.default_rng(5)
+    V, d = 6, 32
+    E = rng.standard_normal((V, d)).astype(np.float32)
+    perms = np.stack([rng.permutation(d)[:4] for _ in range(4)]).astype(np.int32)
+    gc = GpuCase(E, perms, np.array([0, 3], dtype=np.int32), 2)
+    H = rng.standard_normal((3, d)).astype(np.float32)
+    cfg = None
+    run_and_check(cfg, gc, H, np.zeros(3, np.float32), 1, 3)            # <= 6 candidates, B*C >= B
+    run_and_check(cfg, gc, H[:1], np.zeros(1, np.float32), 1, 1)
+    # B = 8 beams over at most 6 words with 1 live beam: fewer than B finite pairs -> padded tail
+    H8 = rng.standard_normal((8, d)).astype(np.float32)
+    bs = np.full(8, -np.inf, dtype=np.float32)
+    bs[2] = 0.0
+    gb, gw, gs, _ = run_and_check(cfg, gc, H8, bs, 1, 8, full_vocab=True)
+    assert (gb[0] >= 0).sum() == 6
+
+
+def test_all_logits_tie_orders_by_beam_then_word():
+    cfg, gc = case("tiny")
+    Hz = np.zeros((4, cfg.d), dtype=np.float32)
+    gb, gw, gs, sp, ws = gc.step(Hz, np.zeros(4, np.float32), 1, 4)
+    cand = gc.index.candidates(Hz, gc.topfreq)
+    assert np.array_equal(gc.tables.debug_candidates(ws, sp, 0), cand)
+    assert gb[0].tolist() == [0, 0, 0, 0] and gw[0].tolist() == cand[:4].tolist()
+    np.testing.assert_allclose(gs[0], -np.log(len(cand)), rtol=1e-6)
+
+
+def test_topfreq_out_of_range_ids_and_duplicates_are_harmless():
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 1)[0]
+    tf = np.array([3, 3, -5, cfg.V, cfg.V + 100, 999, 0, 3], dtype=np.int32)
+    gb, gw, gs, sp, ws = gc.step(H, np.zeros(4, np.float32), 1, 4, T=len(tf), topfreq_dev=to_dev(tf))
+    want = gc.index.candidates(H, np.array([0, 3, 999], dtype=np.int32))
+    assert np.array_equal(gc.tables.debug_candidates(ws, sp, 0), want)
+
+
+def test_unaligned_hidden_size_uses_scalar_loads():
+    rng = np.random.default_rng(9)
+    for d, V, dt in [(50, 333, np.float32), (77, 200, np.float32), (52, 300, np.uint16)]:
+        E = rng.standard_normal((V, d)).astype(np.float32)
+        if dt == np.uint16:
+            E = workloads.f32_to_bf16_bits(E)
+        perms = np.stack([rng.permutation(d)[:8] for _ in range(8)]).astype(np.int32)
+        gc = GpuCase(E, perms, np.arange(20, dtype=np.int32), 2)
+        H = rng.standard_normal((2 * 5, d)).astype(np.float32)
+        run_and_check(None, gc, H, rng.standard_normal(10).astype(np.float32), 2, 5)
+        run_and_check(None, gc, H, np.zeros(10, np.float32), 2, 5, full_vocab=True)
+
+
+def test_step_is_deterministic():
+    cfg, gc = case("paper")
+    H = hidden(cfg, gc, 1)[0]
+    a = gc.step(H, np.zeros(cfg.R, np.float32), 1, cfg.B)
+    ca = gc.tables.debug_candidates(a[4], a[3], 0)
+    la = gc.tables.debug_logprobs(a[4], a[3], 0, cap=len(ca))
+    b = gc.step(H, np.zeros(cfg.R, np.float32), 1, cfg.B)
+    cb = gc.tables.debug_candidates(b[4], b[3], 0)
+    lb = gc.tables.debug_logprobs(b[4], b[3], 0, cap=len(cb))
+    assert np.array_equal(ca, cb) and np.array_equal(la, lb)
+    for x, y in zip(a[:3], b[:3]):
+        assert np.array_equal(x, y)
+
+
+def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
+    import torch
+    import paper_1806_00588_amd as lsh
+    from paper_1806_00588_amd import binding
+    cfg, gc = case("tiny")
+    H = to_dev(hidden(cfg, gc, 1)[0])
+    bs = torch.zeros(4, device="cuda")
+    ob = torch.full((1, 4), 42, dtype=torch.int32, device="cuda")
+    ow = ob.clone()
+    osc = torch.full((1, 4), 42.0, device="cuda")
+    sp = binding.step_params(1, 4, 50)
+    ws = torch.empty(lsh.step_workspace_bytes(gc.tables, sp), dtype=torch.uint8, device="cuda")
+    with pytest.raises(lsh.LshBeamError) as e:
+        lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, binding.step_params(1, 4, 50, threshold=2),
+                        ws, ob, ow, osc)
+    assert e.value.status == 2                                  # unsupported threshold
+    with pytest.raises(lsh.LshBeamError) as e:
+        lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, sp, ws[:1024], ob, ow, osc)
+    assert e.value.status == 6                                  # workspace too small
+    with pytest.raises(lsh.LshBeamError) as e:
+        lsh.decode_step(gc.tables, H, bs, None, sp, ws, ob, ow, osc)
+    assert e.value.status == 1                                  # T > 0 without a list
+    torch.cuda.synchronize()
+    assert torch.all(ob == 42) and torch.all(ow == 42) and torch.all(osc == 42.0)
+    assert lsh.step_workspace_bytes(gc.tables, binding.step_params(0, 4, 0)) == 0
+    assert lsh.step_workspace_bytes(gc.tables, binding.step_params(1, 257, 0)) == 0
+    # build-time validation
+    for K, W in [(1, 4), (8, 3), (8, 0), (8, 1)]:          # (8, 1): u * bits = 48 > 30
+        with pytest.raises(lsh.LshBeamError):
+            lsh.build_tables(gc.E_dev, gc.perms_dev[:, :K].contiguous(), K, W)
+    bad = gc.perms_dev.clone()
+    bad[0, 0] = cfg.d
+    with pytest.raises(lsh.LshBeamError):
+        lsh.build_tables(gc.E_dev, bad, cfg.K, cfg.W)
