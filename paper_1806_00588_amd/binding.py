@@ -271,3 +271,25 @@ def decode_step(tables: Tables, H, beam_scores, topfreq, sp: StepParams, workspa
         tables.handle, H.data_ptr(), beam_scores.data_ptr(), tf_ptr, ctypes.byref(sp),
         workspace.data_ptr(), workspace.numel() * workspace.element_size(), out_beam.data_ptr(),
         out_word.data_ptr(), out_score.data_ptr(), _stream_ptr(stream)), "lsh_decode_step")
+
+
+def make_step_caller(tables: Tables, sp: StepParams, workspace, topfreq):
+    """Pre-marshalled lsh_decode_step for tight loops: returns
+    f(H_ptr, beam_scores_ptr, out_beam_ptr, out_word_ptr, out_score_ptr, stream_ptr) -> None,
+    all arguments raw device addresses (ints).  Same entry point, same kernels; only the Python
+    argument checking is hoisted out of the loop."""
+    lib = load_library()
+    fn = lib.lsh_decode_step
+    h = ctypes.c_void_p(tables.handle)
+    spp = ctypes.pointer(sp)
+    ws = ctypes.c_void_p(workspace.data_ptr())
+    wsn = ctypes.c_size_t(workspace.numel() * workspace.element_size())
+    tf = ctypes.c_void_p(topfreq.data_ptr() if topfreq is not None else 0)
+    keep = (tables, sp, workspace, topfreq)
+
+    def call(H_ptr, bs_ptr, ob_ptr, ow_ptr, osc_ptr, stream_ptr, _keep=keep):
+        rc = fn(h, H_ptr, bs_ptr, tf, spp, ws, wsn, ob_ptr, ow_ptr, osc_ptr, stream_ptr)
+        if rc:
+            raise LshBeamError(rc, "lsh_decode_step")
+
+    return call
