@@ -190,7 +190,13 @@ def main():
         _, _, run_full = make_runner(True)
         kf = max(nst, min(K, 400) // nst * nst)
         fsecs, _ = time_region(run_full, kf, args.mode)
+        tables.profile_begin(kf)
+        run_full(0, kf, stream_ptr())
+        fprof = tables.profile_end()
+        for name, (ms, n) in fprof.items():
+            log(f"[bench]   full-vocab {name:14s} mean {ms*1e3:8.2f} us over {n} launches")
         full = {"steps": kf, "ms_per_step": round(fsecs / kf * 1e3, 5),
+                "kernels_us": {k: round(v[0] * 1e3, 3) for k, v in fprof.items() if v[1]},
                 "steps_per_s": round(kf / fsecs, 1),
                 "lsh_speedup": round((fsecs / kf) / (secs / K), 3),
                 "algorithmic_bytes_per_step": float(S) * cfg.V * cfg.d * e_bytes}

@@ -85,13 +85,25 @@ k_band_codes(const ET* __restrict__ X, int64_t ld, int64_t n, const int32_t* __r
 
 constexpr int kCandThreads = 1024;
 constexpr int kCandWaves = kCandThreads / kWave;
+constexpr int kCandStage = 12288;  // hidden values staged in LDS per chunk of rows (floats)
 
-// LDS words k_candidates needs for a vocabulary of V words.
-__host__ __device__ inline size_t candidates_lds_words(int V) {
-    const size_t nwords = ((size_t)V + 31) / 32;
-    return nwords + 3 * (size_t)kCandThreads + 64;
+// Rows of a sentence are processed in chunks small enough that the chunk's hidden rows fit the
+// LDS stage and its (row, band) pairs fit one workgroup-wide scan.
+__host__ __device__ inline int candidates_rows_per_chunk(int B, int d, int W) {
+    int rows = kCandStage / d;
+    if (rows > kCandThreads / W) rows = kCandThreads / W;
+    if (rows > B) rows = B;
+    return rows < 1 ? 1 : rows;
 }
 
+// LDS words k_candidates needs.  The stage always holds at least one hidden row.
+__host__ __device__ inline size_t candidates_lds_words(int V, int d, int P, int K) {
+    const size_t nwords = ((size_t)V + 31) / 32;
+    const size_t stage = (size_t)d > (size_t)kCandStage ? (size_t)d : (size_t)kCandStage;
+    return nwords + stage + (size_t)P * K + 3 * (size_t)kCandThreads + 64;
+}
+
+// One workgroup per sentence.  Requires W <= kCandThreads.
 __global__ void __launch_bounds__(kCandThreads)
 k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restrict__ perms, int P,
              int K, int W, int bits, const Slot* __restrict__ slots,
@@ -100,18 +112,28 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
              int32_t* __restrict__ count) {
     extern __shared__ uint32_t smem[];
     const int nwords = (V + 31) >> 5;
-    uint32_t* bm = smem;                         // presence bitmap, V bits
-    uint32_t* p_start = bm + nwords;             // span start of each pair in the chunk
-    uint32_t* p_band = p_start + kCandThreads;   // its band
-    uint32_t* p_pref = p_band + kCandThreads;    // exclusive prefix of span lengths
-    uint32_t* wsum = p_pref + kCandThreads;      // scan scratch (>= kCandWaves + 1)
+    const int stage_words = d > kCandStage ? d : kCandStage;
+    uint32_t* bm = smem;                                   // presence bitmap, V bits
+    float* stage = reinterpret_cast<float*>(bm + nwords);  // the chunk's hidden rows [rows][d]
+    int32_t* lperms = reinterpret_cast<int32_t*>(bm + nwords + stage_words);  // perms [P][K]
+    uint32_t* p_start = bm + nwords + stage_words + P * K; // span start of each pair in the chunk
+    uint32_t* p_band = p_start + kCandThreads;             // its band
+    uint32_t* p_pref = p_band + kCandThreads;              // exclusive prefix of span lengths
+    uint32_t* wsum = p_pref + kCandThreads;                // scan scratch (>= kCandWaves + 1)
 
     const int s = blockIdx.x;
     const int tid = threadIdx.x;
     const int u = P / W;
+    const int rows_per_chunk = candidates_rows_per_chunk(B, d, W);
+    // this thread's (row-in-chunk, band) pair is fixed: fetch its band's table description now
+    const uint32_t my_w = (uint32_t)(tid % W);
+    const BandMeta my_meta = bands[my_w];
 
+    LSH_TRACE(0, 0);
     for (int i = tid; i < nwords; i += kCandThreads) bm[i] = 0u;
+    for (int i = tid; i < P * K; i += kCandThreads) lperms[i] = perms[i];
     __syncthreads();
+    LSH_TRACE(0, 1);
 
     // Eq. 3: the top-frequent words are members of every candidate list.
     for (int i = tid; i < T; i += kCandThreads) {
@@ -119,41 +141,101 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
         if (id >= 0 && id < V) atomicOr(&bm[id >> 5], 1u << (id & 31));
     }
 
-    // Algorithm 1 for every (row, band) pair of the sentence, kCandThreads pairs at a time.
-    const int npairs = B * W;
-    for (int base = 0; base < npairs; base += kCandThreads) {
-        const int pair = base + tid;
-        uint32_t start = 0, len = 0, w = 0;
-        if (pair < npairs) {
-            const int i = pair / W;
-            w = pair - i * W;
-            const float* row = H + ((size_t)s * B + i) * d;
-            const int32_t code = band_code_of<float>(row, perms, (int)w, u, K, bits);
-            const BandMeta m = bands[w];
-            cuckoo_find(slots, m, code, &start, &len);
+    for (int row0 = 0; row0 < B; row0 += rows_per_chunk) {
+        const int rows = min(rows_per_chunk, B - row0);
+        // The chunk's hidden rows are contiguous: copy them to LDS with coalesced loads (a row's
+        // P*K permuted coordinates touch nearly every cache line of the row anyway), so that the
+        // permuted gathers of Eq. 5 are LDS reads and no global load depends on another.
+        const float* Hc = H + ((size_t)s * B + row0) * d;
+        const int nval = rows * d;
+        if (((uintptr_t)Hc & 15) == 0) {
+            const float4* H4 = reinterpret_cast<const float4*>(Hc);
+            float4* S4 = reinterpret_cast<float4*>(stage);
+            const int n4 = nval >> 2;
+            for (int e0 = tid; e0 < n4; e0 += 4 * kCandThreads) {  // 4 independent loads in flight
+                float4 r[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (e0 + q * kCandThreads < n4) r[q] = H4[e0 + q * kCandThreads];
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (e0 + q * kCandThreads < n4) S4[e0 + q * kCandThreads] = r[q];
+            }
+            for (int e = (nval & ~3) + tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
+        } else {
+            for (int e = tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
         }
+        __syncthreads();
+        LSH_TRACE(0, 2);
+
+        // Eq. 4-8 from the staged rows, then Algorithm 1 lines 1-2 for this thread's pair
+        const int npairs = rows * W;
+        uint32_t start = 0, len = 0, w = 0;
+        if (tid < npairs) {
+            const int i = tid / W;
+            w = my_w;
+            const float* sv = stage + (size_t)i * d;
+            const int32_t* pm = lperms + (size_t)w * u * K;
+            int32_t code = 0;
+            for (int q = 0; q < u; ++q) {
+                int best = 0;
+                float bv = -INFINITY;
+                bool first = true;
+                for (int k0 = 0; k0 < K; k0 += 8) {  // 8 windows entries per round of LDS reads
+                    int idx[8];
+                    float v[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) idx[j] = pm[q * K + min(k0 + j, K - 1)];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) v[j] = sv[idx[j]];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        // sequential scan semantics: the first entry seeds, later ones must be
+                        // strictly greater to win
+                        if (k0 + j < K && (first || v[j] > bv)) { bv = v[j]; best = k0 + j; }
+                        first = false;
+                    }
+                }
+                code = (code << bits) | best;
+            }
+            cuckoo_find(slots, my_meta, code, &start, &len);
+        }
+        LSH_TRACE(0, 3);
         uint32_t total;
         const uint32_t incl = block_incl_scan(len, wsum, &total);
+        LSH_TRACE(0, 4);
         p_start[tid] = start;
         p_band[tid] = w;
         p_pref[tid] = incl - len;
         __syncthreads();
-        // flat walk over all spans of the chunk: element e belongs to the last pair whose
-        // exclusive prefix is <= e
-        for (uint32_t e = tid; e < total; e += kCandThreads) {
-            int lo = 0, hi = kCandThreads;  // first index with p_pref > e, in (lo, hi]
-            while (hi - lo > 1) {
-                const int mid = (lo + hi) >> 1;
-                if (p_pref[mid] <= e) lo = mid; else hi = mid;
+        // Algorithm 1 lines 3-6 as a flat walk over all spans of the chunk: element e belongs
+        // to the last pair whose exclusive prefix is <= e
+        for (uint32_t e0 = tid; e0 < total; e0 += 4 * kCandThreads) {
+            int32_t id[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {  // 4 independent span reads in flight
+                const uint32_t e = e0 + q * kCandThreads;
+                id[q] = -1;
+                if (e < total) {
+                    int lo = 0, hi = kCandThreads;
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (p_pref[mid] <= e) lo = mid; else hi = mid;
+                    }
+                    id[q] = words[(size_t)p_band[lo] * V + p_start[lo] + (e - p_pref[lo])];
+                }
             }
-            const int32_t id =
-                words[(size_t)p_band[lo] * V + p_start[lo] + (e - p_pref[lo])];
-            atomicOr(&bm[id >> 5], 1u << (id & 31));
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                if (id[q] >= 0) atomicOr(&bm[id[q] >> 5], 1u << (id[q] & 31));
         }
         __syncthreads();
+        LSH_TRACE(0, 5);
     }
 
-    // Compaction: each wave owns a contiguous range of bitmap words (a multiple of 64 of them).
+    // Compaction (Eq. 10 with t = 1; the paper's Fig. 5 step): each wave owns a contiguous range
+    // of bitmap words (a multiple of 64 of them); popcount + wave prefix sum give every lane the
+    // output offset of its word's ids.
     const int wv = wave_id(), ln = lane_id();
     int per_wave = (nwords + kCandWaves - 1) / kCandWaves;
     per_wave = (per_wave + kWave - 1) / kWave * kWave;
@@ -182,9 +264,10 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
             out[off++] = (i << 5) + b;
             bitsw &= bitsw - 1;
         }
-        running += __shfl(incl, kWave - 1, kWave);
+        running += wave_read_lane(incl, kWave - 1);
     }
     if (tid == 0) count[s] = (int32_t)total;
+    LSH_TRACE(0, 6);
 }
 
 }  // namespace lshbeam

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "trace.h"
+
 namespace lshbeam {
 
 constexpr int kWave = 64;
@@ -10,20 +12,36 @@ constexpr int kWave = 64;
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 __device__ __forceinline__ int wave_id() { return threadIdx.x >> 6; }
 
-// Inclusive prefix sum over the 64 lanes of a wave.
+// DPP lane permutations (no LDS round trip, unlike ds_bpermute-based shuffles).
+//   0x110 + n : row_shr:n   -- shift right by n lanes inside each row of 16 lanes
+//   0x142     : row_bcast:15 -- lane 15 of each row to every lane of the next row
+//   0x143     : row_bcast:31 -- lane 31 to every lane of rows 2 and 3
+// Lanes that receive nothing (shifted in from outside the row, or rows disabled by row_mask)
+// read `old` = 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_or_zero(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, true);
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave: Hillis-Steele inside each row of 16 lanes,
+// then the row totals are carried across rows with the two broadcast steps.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        uint32_t n = __shfl_up(v, off, kWave);
-        if (lane_id() >= off) v += n;
-    }
+    v += dpp_or_zero<0x111, 0xf>(v);
+    v += dpp_or_zero<0x112, 0xf>(v);
+    v += dpp_or_zero<0x114, 0xf>(v);
+    v += dpp_or_zero<0x118, 0xf>(v);
+    v += dpp_or_zero<0x142, 0xa>(v);  // rows 1 and 3 add the total of rows 0 and 2
+    v += dpp_or_zero<0x143, 0xc>(v);  // rows 2 and 3 add the total of lanes 0..31
     return v;
 }
 
+// Value of lane `lane` (compile-time or wave-uniform) broadcast through a scalar register.
+__device__ __forceinline__ uint32_t wave_read_lane(uint32_t v, int lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
+    return wave_read_lane(wave_incl_scan(v), kWave - 1);
 }
 
 // Order-preserving map fp32 -> uint32 (larger float <=> larger integer; -0 is folded into +0 by

@@ -60,9 +60,26 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     const int MT = (B + kTileM - 1) / kTileM;
 
+    LSH_TRACE(1, 0);
     // The select kernel counts finished rows per sentence; its counters start from zero.
     if (blockIdx.x == 0)
         for (int i = tid; i < S; i += WAVES * kWave) tickets[i] = 0;
+
+    // Workgroups are dealt to the 8 XCDs round-robin by the dispatcher; renumber them so that
+    // consecutive logical ids (which take neighbouring tiles) share an XCD and its L2.
+    const uint32_t G = gridDim.x;
+    const uint32_t per_xcd = G >> 3;
+    const uint32_t logical = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    const int col = ln & 15, kq = ln >> 4;
+
+    // With a single sentence the first tile's candidate ids do not depend on the count: request
+    // them together with it instead of after it (one dependent memory round trip less).
+    const bool spec = (S == 1) && (cand != nullptr);
+    int32_t jspec = 0;
+    if (spec) {
+        const uint32_t c0 = (logical / (uint32_t)MT) * kTileN + col;
+        if (c0 < (uint32_t)V) jspec = cand[c0];
+    }
 
     // exclusive prefix of tiles per sentence (wave 0, 64 sentences at a time)
     if (wv == 0) {
@@ -76,20 +93,14 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
             }
             const uint32_t incl = wave_incl_scan(n);
             if (s < S) tile_pref[s] = carry + incl - n;
-            carry += __shfl(incl, kWave - 1, kWave);
+            carry += wave_read_lane(incl, kWave - 1);
         }
         if (ln == 0) tile_pref[S] = carry;
     }
     __syncthreads();
+    LSH_TRACE(1, 1);
     const uint32_t total_tiles = tile_pref[S];
 
-    // Workgroups are dealt to the 8 XCDs round-robin by the dispatcher; renumber them so that
-    // consecutive logical ids (which take neighbouring tiles) share an XCD and its L2.
-    const uint32_t G = gridDim.x;
-    const uint32_t per_xcd = G >> 3;
-    const uint32_t logical = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-
-    const int col = ln & 15, kq = ln >> 4;
     const int nks = (d + KSTEP - 1) / KSTEP;
 
     for (uint32_t t = logical; t < total_tiles; t += G) {
@@ -106,7 +117,12 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
 
         // out-of-range lanes are clamped onto a valid row; their results are never stored
         const int cidx = min(n0 + col, C - 1);
-        const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        int64_t j;
+        if (spec && t == logical)  // column 0 of a tile is always a real candidate
+            j = (n0 + col < C) ? jspec : __shfl(jspec, ln & ~15, kWave);
+        else
+            j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        LSH_TRACE(1, 2);
         const ET* erow = E + j * ld;
         const int hr = min(mt * kTileM + col, B - 1);
         const float* hrow = H + ((size_t)s * B + hr) * d;
@@ -146,6 +162,7 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
                     acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[uu][q], ev[uu][q], acc, 0, 0, 0);
         }
 
+        LSH_TRACE(1, 3);
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[r];
         __syncthreads();
@@ -159,6 +176,7 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
             if (row < B && c < C) logits[((size_t)s * B + row) * cpitch + c] = sum;
         }
         __syncthreads();
+        LSH_TRACE(1, 4);
     }
 }
 

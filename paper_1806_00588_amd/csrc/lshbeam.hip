@@ -284,7 +284,8 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (p->P < 1 || p->bands < 1 || p->P % p->bands != 0) return LSH_ERR_INVALID_ARG;
     const int bits = code_bits(p->K), u = p->P / p->bands;
     if ((int64_t)u * bits > 30) return LSH_ERR_INVALID_ARG;
-    if (candidates_lds_words(p->V) * 4 > kMaxDynLds) return LSH_ERR_UNSUPPORTED;
+    if (candidates_lds_words(p->V, p->d, p->P, p->K) * 4 > kMaxDynLds || p->bands > kCandThreads)
+        return LSH_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)hip_stream;
 
     lsh_tables* t = new (std::nothrow) lsh_tables();
@@ -355,7 +356,7 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     HIP_TRY(hipMemcpyAsync(t->bands_dev, metas.data(), W * sizeof(BandMeta), hipMemcpyHostToDevice, st));
     HIP_TRY(hipStreamSynchronize(st));
 
-    t->wg_candidates_lds = (int)(candidates_lds_words(t->V) * sizeof(uint32_t));
+    t->wg_candidates_lds = (int)(candidates_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
     if (t->wg_candidates_lds > 48 * 1024)
         HIP_TRY(hipFuncSetAttribute((const void*)k_candidates,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_candidates_lds));
@@ -555,5 +556,14 @@ lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
     }
     return LSH_OK;
 }
+
+#ifdef LSHBEAM_TRACE
+// Development builds only: copy the in-kernel phase timestamps (100 MHz ticks) to the host.
+int lsh_trace_read(unsigned long long* out_host) {
+    if (hipDeviceSynchronize() != hipSuccess) return 1;
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace),
+                               sizeof(unsigned long long) * kTraceKernels * kTraceSlots) != hipSuccess;
+}
+#endif
 
 }  // extern "C"

@@ -238,6 +238,13 @@ def test_all_logits_tie_orders_by_beam_then_word():
     assert np.array_equal(gc.tables.debug_candidates(ws, sp, 0), cand)
     assert gb[0].tolist() == [0, 0, 0, 0] and gw[0].tolist() == cand[:4].tolist()
     np.testing.assert_allclose(gs[0], -np.log(len(cand)), rtol=1e-6)
+    # all 1000 words tie in full-vocabulary mode: far more ties than the short list of the
+    # selection holds, so its exact radix fallback decides
+    gb, gw, gs, sp, ws = gc.step(Hz, np.array([0, 0, 1, 0], np.float32), 1, 4, full_vocab=True)
+    assert gb[0].tolist() == [2, 2, 2, 2] and gw[0].tolist() == [0, 1, 2, 3]
+    np.testing.assert_allclose(gs[0], 1 - np.log(cfg.V), rtol=1e-6)
+    gb, gw, gs, sp, ws = gc.step(Hz, np.zeros(4, np.float32), 1, 4, full_vocab=True)
+    assert gb[0].tolist() == [0, 0, 0, 0] and gw[0].tolist() == [0, 1, 2, 3]
 
 
 def test_topfreq_out_of_range_ids_and_duplicates_are_harmless():
