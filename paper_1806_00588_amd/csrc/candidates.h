@@ -135,10 +135,29 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
     __syncthreads();
     LSH_TRACE(0, 1);
 
-    // Eq. 3: the top-frequent words are members of every candidate list.
-    for (int i = tid; i < T; i += kCandThreads) {
-        const int32_t id = topfreq[i];
-        if (id >= 0 && id < V) atomicOr(&bm[id >> 5], 1u << (id & 31));
+    // Eq. 3: the top-frequent words are members of every candidate list.  Frequent-word ids
+    // tend to be consecutive, i.e. many lanes of a wave set bits of the SAME bitmap word, and
+    // same-address LDS atomics serialise; so lanes that share a word first OR their bits
+    // together and one of them issues the atomic.
+    for (int i0 = 0; i0 < T; i0 += kCandThreads) {
+        const int i = i0 + tid;
+        const int32_t id = (i < T) ? topfreq[i] : -1;
+        const bool ok = id >= 0 && id < V;
+        const uint32_t word = ok ? (uint32_t)(id >> 5) : 0xFFFFFFFFu;
+        const uint32_t bit = ok ? (1u << (id & 31)) : 0u;
+        uint64_t todo = __ballot(ok);
+        bool grouped = true;
+        while (todo && grouped) {
+            const int leader = __ffsll((unsigned long long)todo) - 1;
+            const uint32_t w0 = wave_read_lane(word, leader);
+            const bool mine = ok && word == w0;
+            const uint64_t grp = __ballot(mine);
+            const uint32_t ored = wave_or(mine ? bit : 0u);
+            if (lane_id() == leader) atomicOr(&bm[w0], ored);
+            todo &= ~grp;
+            grouped = __popcll(grp) > 1;  // scattered ids: stop grouping, plain atomics below
+        }
+        if (ok && ((todo >> lane_id()) & 1ull)) atomicOr(&bm[word], bit);
     }
 
     for (int row0 = 0; row0 < B; row0 += rows_per_chunk) {
@@ -153,13 +172,14 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
             float4* S4 = reinterpret_cast<float4*>(stage);
             const int n4 = nval >> 2;
             for (int e0 = tid; e0 < n4; e0 += 4 * kCandThreads) {  // 4 independent loads in flight
-                float4 r[4];
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (e0 + q * kCandThreads < n4) r[q] = H4[e0 + q * kCandThreads];
-#pragma unroll
-                for (int q = 0; q < 4; ++q)
-                    if (e0 + q * kCandThreads < n4) S4[e0 + q * kCandThreads] = r[q];
+                const float4 r0 = H4[min(e0, n4 - 1)];
+                const float4 r1 = H4[min(e0 + kCandThreads, n4 - 1)];
+                const float4 r2 = H4[min(e0 + 2 * kCandThreads, n4 - 1)];
+                const float4 r3 = H4[min(e0 + 3 * kCandThreads, n4 - 1)];
+                S4[e0] = r0;
+                if (e0 + kCandThreads < n4) S4[e0 + kCandThreads] = r1;
+                if (e0 + 2 * kCandThreads < n4) S4[e0 + 2 * kCandThreads] = r2;
+                if (e0 + 3 * kCandThreads < n4) S4[e0 + 3 * kCandThreads] = r3;
             }
             for (int e = (nval & ~3) + tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
         } else {
@@ -210,24 +230,22 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
         __syncthreads();
         // Algorithm 1 lines 3-6 as a flat walk over all spans of the chunk: element e belongs
         // to the last pair whose exclusive prefix is <= e
-        for (uint32_t e0 = tid; e0 < total; e0 += 4 * kCandThreads) {
-            int32_t id[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {  // 4 independent span reads in flight
-                const uint32_t e = e0 + q * kCandThreads;
-                id[q] = -1;
-                if (e < total) {
-                    int lo = 0, hi = kCandThreads;
-                    while (hi - lo > 1) {
-                        const int mid = (lo + hi) >> 1;
-                        if (p_pref[mid] <= e) lo = mid; else hi = mid;
-                    }
-                    id[q] = words[(size_t)p_band[lo] * V + p_start[lo] + (e - p_pref[lo])];
-                }
+        for (uint32_t e0 = tid; e0 < total; e0 += 2 * kCandThreads) {
+            // two independent span reads in flight per thread
+            const uint32_t ea = e0, eb = min(e0 + (uint32_t)kCandThreads, total - 1);
+            int la = 0, ha = kCandThreads, lb = 0, hb = kCandThreads;
+            while (ha - la > 1) {
+                const int mid = (la + ha) >> 1;
+                if (p_pref[mid] <= ea) la = mid; else ha = mid;
             }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                if (id[q] >= 0) atomicOr(&bm[id[q] >> 5], 1u << (id[q] & 31));
+            while (hb - lb > 1) {
+                const int mid = (lb + hb) >> 1;
+                if (p_pref[mid] <= eb) lb = mid; else hb = mid;
+            }
+            const int32_t ida = words[(size_t)p_band[la] * V + p_start[la] + (ea - p_pref[la])];
+            const int32_t idb = words[(size_t)p_band[lb] * V + p_start[lb] + (eb - p_pref[lb])];
+            atomicOr(&bm[ida >> 5], 1u << (ida & 31));
+            atomicOr(&bm[idb >> 5], 1u << (idb & 31));  // a clamped duplicate sets a set bit again
         }
         __syncthreads();
         LSH_TRACE(0, 5);

@@ -35,6 +35,9 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
     return v;
 }
 
+// OR of v over the 64 lanes (same data movement as the scan; valid in lane 63, returned uniform).
+__device__ __forceinline__ uint32_t wave_or(uint32_t v);
+
 // Value of lane `lane` (compile-time or wave-uniform) broadcast through a scalar register.
 __device__ __forceinline__ uint32_t wave_read_lane(uint32_t v, int lane) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
@@ -42,6 +45,37 @@ __device__ __forceinline__ uint32_t wave_read_lane(uint32_t v, int lane) {
 
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return wave_read_lane(wave_incl_scan(v), kWave - 1);
+}
+
+__device__ __forceinline__ uint32_t wave_or(uint32_t v) {
+    v |= dpp_or_zero<0x111, 0xf>(v);
+    v |= dpp_or_zero<0x112, 0xf>(v);
+    v |= dpp_or_zero<0x114, 0xf>(v);
+    v |= dpp_or_zero<0x118, 0xf>(v);
+    v |= dpp_or_zero<0x142, 0xa>(v);
+    v |= dpp_or_zero<0x143, 0xc>(v);
+    return wave_read_lane(v, kWave - 1);
+}
+
+// All-reduce inside each group of 16 consecutive lanes (a DPP "row"): xor-1 and xor-2 inside
+// quads, then the half-row and full-row mirrors.  Every lane of the group ends with the result.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, dpp_f32<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_f32<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_f32<0x141>(v));  // row_half_mirror
+    v = fmaxf(v, dpp_f32<0x140>(v));  // row_mirror
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_f32<0xB1>(v);
+    v += dpp_f32<0x4E>(v);
+    v += dpp_f32<0x141>(v);
+    v += dpp_f32<0x140>(v);
+    return v;
 }
 
 // Order-preserving map fp32 -> uint32 (larger float <=> larger integer; -0 is folded into +0 by

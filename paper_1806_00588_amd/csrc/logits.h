@@ -2,6 +2,10 @@
 // the candidate list; the paper's separate "construct E_LSH" copy is fused away: candidate rows
 // of E are gathered straight into the matrix-core operands).
 //
+// Besides the logits every tile leaves, per hidden row, the pair (max, sum exp(logit - max)) over
+// its 16 candidates: the selection kernel combines these into the row's log-sum-exp without
+// touching the exponential of every logit again.
+//
 // Work unit ("tile"): one sentence s, one group of 16 hidden rows (M-tile) and 16 candidates.
 // A workgroup of WAVES waves splits the hidden dimension between its waves; every wave issues
 // v_mfma_f32_16x16x4_f32 over its share of k and the partial 16x16 tiles are summed through LDS
@@ -51,7 +55,8 @@ template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(WAVES * kWave)
 k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
          const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-         float* __restrict__ logits, int64_t cpitch, int32_t* __restrict__ tickets) {
+         float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
+         int64_t ppitch) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
     __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
@@ -61,15 +66,14 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
     const int MT = (B + kTileM - 1) / kTileM;
 
     LSH_TRACE(1, 0);
-    // The select kernel counts finished rows per sentence; its counters start from zero.
-    if (blockIdx.x == 0)
-        for (int i = tid; i < S; i += WAVES * kWave) tickets[i] = 0;
-
     // Workgroups are dealt to the 8 XCDs round-robin by the dispatcher; renumber them so that
     // consecutive logical ids (which take neighbouring tiles) share an XCD and its L2.
     const uint32_t G = gridDim.x;
     const uint32_t per_xcd = G >> 3;
-    const uint32_t logical = (G & 7u) ? blockIdx.x : (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+    // (Only worth it when several M-tiles re-read the same candidate rows; with one M-tile the
+    // plain order lets the first workgroups dispatched be the ones that have work.)
+    const uint32_t logical = ((G & 7u) || MT == 1) ? blockIdx.x
+                                                   : (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
     const int col = ln & 15, kq = ln >> 4;
 
     // With a single sentence the first tile's candidate ids do not depend on the count: request
@@ -173,7 +177,14 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
             const int row = mt * kTileM + i, c = n0 + jc;
-            if (row < B && c < C) logits[((size_t)s * B + row) * cpitch + c] = sum;
+            const bool valid = row < B && c < C;
+            if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
+            // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
+            // tile's 16 candidates; the 16 lanes that share a row are one DPP row
+            const float mx = row16_max(valid ? sum : -INFINITY);
+            const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
+            if (jc == 0 && row < B)
+                partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
         }
         __syncthreads();
         LSH_TRACE(1, 4);

@@ -151,12 +151,10 @@ void launch(lsh_tables* t, int which, void (*kernel)(KArgs...), dim3 grid, dim3 
 struct Workspace {
     int32_t* cand;       // [S, V]
     int32_t* count;      // [S]
-    int32_t* tickets;    // [S]
     float* logits;       // [R, cpitch]
-    uint64_t* part;      // [R, B]
-    int32_t* part_n;     // [R]
+    float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max))
     float* lse;          // [R]
-    uint64_t* merge;     // [S, B*B]
+    int64_t ppitch;
     int64_t cpitch;
     size_t bytes;
 };
@@ -169,12 +167,10 @@ Workspace carve(const lsh_tables* t, const lsh_step_params* sp, void* base) {
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return (char*)base + o; };
     w.cand = (int32_t*)take(sp->full_vocab ? 0 : S * V * sizeof(int32_t));
     w.count = (int32_t*)take(S * sizeof(int32_t));
-    w.tickets = (int32_t*)take(S * sizeof(int32_t));
+    w.ppitch = w.cpitch / kTileN;
     w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
-    w.part = (uint64_t*)take(R * B * sizeof(uint64_t));
-    w.part_n = (int32_t*)take(R * sizeof(int32_t));
+    w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(float2));
     w.lse = (float*)take(R * sizeof(float));
-    w.merge = (uint64_t*)take(S * B * B * sizeof(uint64_t));
     w.bytes = off;
     return w;
 }
@@ -197,10 +193,12 @@ void launch_logits_w(lsh_tables* t, hipStream_t st, int grid, bool aligned, cons
     const ET* E = (const ET*)t->E;
     if (aligned)
         launch(t, 1, k_logits<ET, WAVES, UNROLL, true>, dim3(grid), dim3(WAVES * kWave), 0, st, E,
-               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.tickets);
+               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials,
+               w.ppitch);
     else
         launch(t, 1, k_logits<ET, WAVES, UNROLL, false>, dim3(grid), dim3(WAVES * kWave), 0, st, E,
-               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.tickets);
+               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials,
+               w.ppitch);
 }
 
 template <typename ET>
@@ -216,7 +214,7 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     int waves = (sp->S * MT <= 8) ? 16 : 4;
     waves = env_int("LSHBEAM_LOGITS_WAVES", waves);
     if (waves >= 16) {
-        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 512));
+        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 256));
         launch_logits_w<ET, 16>(t, st, grid, aligned, H, sp, cand, count, w);
     } else if (waves >= 8) {
         const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 1024));
@@ -385,8 +383,6 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     const Workspace w = carve(t, sp, workspace_dev);
     if (workspace_bytes < w.bytes) return LSH_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)hip_stream;
-    const int R = sp->S * sp->B;
-
     const int32_t* cand = nullptr;
     const int32_t* count = nullptr;
     if (!sp->full_vocab) {
@@ -399,8 +395,8 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     }
     if (t->dtype == LSH_F32) launch_logits<float>(t, st, H_dev, sp, cand, count, w);
     else launch_logits<uint16_t>(t, st, H_dev, sp, cand, count, w);
-    launch(t, 2, k_select, dim3(R), dim3(kSelThreads), 0, st, (const float*)w.logits, w.cpitch, cand,
-           count, t->V, sp->B, beam_scores_dev, w.part, w.part_n, w.lse, w.merge, w.tickets,
+    launch(t, 2, k_select, dim3(sp->S), dim3(kSelThreads), 0, st, (const float*)w.logits, w.cpitch,
+           (const float2*)w.partials, w.ppitch, cand, count, t->V, sp->B, beam_scores_dev, w.lse,
            out_beam_dev, out_word_dev, out_score_dev);
     HIP_TRY(hipGetLastError());
     return LSH_OK;
