@@ -52,6 +52,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE readings to bytes)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-GPU kernel "
@@ -82,6 +85,14 @@ def main():
     tables = lsh.build_tables(E_dev, perms_dev, cfg.K, cfg.W, seed=0)
     torch.cuda.synchronize()
     log(f"[bench] lsh_build_tables: {time.time()-t0:.2f}s")
+
+    if args.calibration_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     R, S, B, nst = cfg.R, cfg.S, cfg.B, cfg.steps
     zero = torch.zeros(R, dtype=torch.float32, device="cuda")
