@@ -103,14 +103,41 @@ __host__ __device__ inline size_t candidates_lds_words(int V, int d, int P, int 
     return nwords + stage + (size_t)P * K + 3 * (size_t)kCandThreads + 64;
 }
 
-// One workgroup per sentence.  Requires W <= kCandThreads.
-__global__ void __launch_bounds__(kCandThreads)
-k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restrict__ perms, int P,
-             int K, int W, int bits, const Slot* __restrict__ slots,
-             const BandMeta* __restrict__ bands, const int32_t* __restrict__ words, int V,
-             const int32_t* __restrict__ topfreq, int T, int32_t* __restrict__ cand,
-             int32_t* __restrict__ count) {
-    extern __shared__ uint32_t smem[];
+// Branch-free search in an ascending LDS array of kCandThreads entries whose first entry is 0:
+// the last index whose value is <= e.  Always ten steps, so two searches interleave well.
+__device__ __forceinline__ int last_not_above(const uint32_t* pref, uint32_t e) {
+    int lo = 0;
+#pragma unroll
+    for (int step = kCandThreads / 2; step >= 1; step >>= 1)
+        if (pref[lo + step] <= e) lo += step;
+    return lo;
+}
+
+// Arguments of candidate generation (everything k_candidates takes except its outputs).
+struct CandArgs {
+    const float* H;          // [S*B, d] hidden rows
+    int B, d;
+    const int32_t* perms;    // [P, K]
+    int P, K, W, bits;
+    const Slot* slots;
+    const BandMeta* bands;   // [W]
+    const int32_t* words;    // [W, V]
+    int V;
+    const int32_t* topfreq;  // [T]
+    int T;
+};
+
+// Builds sentence s's presence bitmap (V bits, at smem[0 .. ceil(V/32))) in LDS: hashing, cuckoo
+// probes, bucket walk and the top-frequent words.  Called by all kCandThreads threads of a
+// workgroup with candidates_lds_words() words of LDS; ends with a workgroup barrier.
+__device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, uint32_t* smem) {
+    const float* __restrict__ H = a.H;
+    const int B = a.B, d = a.d, P = a.P, K = a.K, W = a.W, bits = a.bits, V = a.V, T = a.T;
+    const int32_t* __restrict__ perms = a.perms;
+    const Slot* __restrict__ slots = a.slots;
+    const BandMeta* __restrict__ bands = a.bands;
+    const int32_t* __restrict__ words = a.words;
+    const int32_t* __restrict__ topfreq = a.topfreq;
     const int nwords = (V + 31) >> 5;
     const int stage_words = d > kCandStage ? d : kCandStage;
     uint32_t* bm = smem;                                   // presence bitmap, V bits
@@ -121,17 +148,32 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
     uint32_t* p_pref = p_band + kCandThreads;              // exclusive prefix of span lengths
     uint32_t* wsum = p_pref + kCandThreads;                // scan scratch (>= kCandWaves + 1)
 
-    const int s = blockIdx.x;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, ln = lane_id();
     const int u = P / W;
     const int rows_per_chunk = candidates_rows_per_chunk(B, d, W);
-    // this thread's (row-in-chunk, band) pair is fixed: fetch its band's table description now
+    LSH_TRACE(0, 0);
+
+    // Everything whose address is known up front is requested before anything is waited for:
+    // this thread's band descriptor (its (row-in-chunk, band) pair is fixed), its first
+    // top-frequent id, and its share of the first chunk of hidden rows.
     const uint32_t my_w = (uint32_t)(tid % W);
     const BandMeta my_meta = bands[my_w];
-
-    LSH_TRACE(0, 0);
-    for (int i = tid; i < nwords; i += kCandThreads) bm[i] = 0u;
+    int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
+    const float* H0 = H + (size_t)s * B * d;
+    const bool vec_ok = (((uintptr_t)H0 | ((uintptr_t)d * 4)) & 15) == 0;
+    float4 r0 = {}, r1 = {}, r2 = {}, r3 = {};
+    {
+        const int n4 = (min(rows_per_chunk, B) * d) >> 2;
+        if (vec_ok && n4 > 0) {
+            const float4* H4 = reinterpret_cast<const float4*>(H0);
+            r0 = H4[min(tid, n4 - 1)];
+            r1 = H4[min(tid + kCandThreads, n4 - 1)];
+            r2 = H4[min(tid + 2 * kCandThreads, n4 - 1)];
+            r3 = H4[min(tid + 3 * kCandThreads, n4 - 1)];
+        }
+    }
     for (int i = tid; i < P * K; i += kCandThreads) lperms[i] = perms[i];
+    for (int i = tid; i < nwords; i += kCandThreads) bm[i] = 0u;
     __syncthreads();
     LSH_TRACE(0, 1);
 
@@ -141,7 +183,7 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
     // together and one of them issues the atomic.
     for (int i0 = 0; i0 < T; i0 += kCandThreads) {
         const int i = i0 + tid;
-        const int32_t id = (i < T) ? topfreq[i] : -1;
+        const int32_t id = (i0 == 0) ? tf_first : ((i < T) ? topfreq[i] : -1);
         const bool ok = id >= 0 && id < V;
         const uint32_t word = ok ? (uint32_t)(id >> 5) : 0xFFFFFFFFu;
         const uint32_t bit = ok ? (1u << (id & 31)) : 0u;
@@ -153,11 +195,11 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
             const bool mine = ok && word == w0;
             const uint64_t grp = __ballot(mine);
             const uint32_t ored = wave_or(mine ? bit : 0u);
-            if (lane_id() == leader) atomicOr(&bm[w0], ored);
+            if (ln == leader) atomicOr(&bm[w0], ored);
             todo &= ~grp;
             grouped = __popcll(grp) > 1;  // scattered ids: stop grouping, plain atomics below
         }
-        if (ok && ((todo >> lane_id()) & 1ull)) atomicOr(&bm[word], bit);
+        if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
     }
 
     for (int row0 = 0; row0 < B; row0 += rows_per_chunk) {
@@ -165,61 +207,77 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
         // The chunk's hidden rows are contiguous: copy them to LDS with coalesced loads (a row's
         // P*K permuted coordinates touch nearly every cache line of the row anyway), so that the
         // permuted gathers of Eq. 5 are LDS reads and no global load depends on another.
-        const float* Hc = H + ((size_t)s * B + row0) * d;
+        const float* Hc = H0 + (size_t)row0 * d;
         const int nval = rows * d;
-        if (((uintptr_t)Hc & 15) == 0) {
+        if (vec_ok) {
             const float4* H4 = reinterpret_cast<const float4*>(Hc);
             float4* S4 = reinterpret_cast<float4*>(stage);
             const int n4 = nval >> 2;
             for (int e0 = tid; e0 < n4; e0 += 4 * kCandThreads) {  // 4 independent loads in flight
-                const float4 r0 = H4[min(e0, n4 - 1)];
-                const float4 r1 = H4[min(e0 + kCandThreads, n4 - 1)];
-                const float4 r2 = H4[min(e0 + 2 * kCandThreads, n4 - 1)];
-                const float4 r3 = H4[min(e0 + 3 * kCandThreads, n4 - 1)];
+                if (row0 != 0 || e0 != tid) {  // the very first batch is already in registers
+                    r0 = H4[min(e0, n4 - 1)];
+                    r1 = H4[min(e0 + kCandThreads, n4 - 1)];
+                    r2 = H4[min(e0 + 2 * kCandThreads, n4 - 1)];
+                    r3 = H4[min(e0 + 3 * kCandThreads, n4 - 1)];
+                }
                 S4[e0] = r0;
                 if (e0 + kCandThreads < n4) S4[e0 + kCandThreads] = r1;
                 if (e0 + 2 * kCandThreads < n4) S4[e0 + 2 * kCandThreads] = r2;
                 if (e0 + 3 * kCandThreads < n4) S4[e0 + 3 * kCandThreads] = r3;
             }
-            for (int e = (nval & ~3) + tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
         } else {
             for (int e = tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
         }
         __syncthreads();
         LSH_TRACE(0, 2);
 
-        // Eq. 4-8 from the staged rows, then Algorithm 1 lines 1-2 for this thread's pair
+        // Eq. 4-5: one thread per (row, permutation) takes the windowed argmax from the staged
+        // row (strict '>' in window order, so the lowest k wins a tie); codes go to LDS.  When
+        // the chunk has more codes than threads, each pair's thread computes its own u codes.
         const int npairs = rows * W;
+        const bool par_codes = rows * P <= kCandThreads;
+        uint32_t* codes = p_pref;  // free until the scan below
+        auto wta = [&](const float* sv, const int32_t* pm) {
+            int best = 0;
+            float bv = -INFINITY;
+            bool first = true;
+            for (int k0 = 0; k0 < K; k0 += 8) {  // 8 window entries per round of LDS reads
+                int idx[8];
+                float v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) idx[j] = pm[min(k0 + j, K - 1)];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = sv[idx[j]];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (k0 + j < K && (first || v[j] > bv)) { bv = v[j]; best = k0 + j; }
+                    first = false;
+                }
+            }
+            return best;
+        };
+        if (par_codes) {
+            if (tid < rows * P) {
+                const int i = tid / P, p = tid - i * P;
+                codes[tid] = (uint32_t)wta(stage + (size_t)i * d, lperms + (size_t)p * K);
+            }
+            __syncthreads();
+        }
+        // Eq. 6-8 (first code most significant), then Algorithm 1 lines 1-2 for this pair
         uint32_t start = 0, len = 0, w = 0;
         if (tid < npairs) {
             const int i = tid / W;
             w = my_w;
-            const float* sv = stage + (size_t)i * d;
-            const int32_t* pm = lperms + (size_t)w * u * K;
             int32_t code = 0;
             for (int q = 0; q < u; ++q) {
-                int best = 0;
-                float bv = -INFINITY;
-                bool first = true;
-                for (int k0 = 0; k0 < K; k0 += 8) {  // 8 windows entries per round of LDS reads
-                    int idx[8];
-                    float v[8];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) idx[j] = pm[q * K + min(k0 + j, K - 1)];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) v[j] = sv[idx[j]];
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        // sequential scan semantics: the first entry seeds, later ones must be
-                        // strictly greater to win
-                        if (k0 + j < K && (first || v[j] > bv)) { bv = v[j]; best = k0 + j; }
-                        first = false;
-                    }
-                }
+                const int best = par_codes
+                    ? (int)codes[i * P + (int)w * u + q]
+                    : wta(stage + (size_t)i * d, lperms + ((size_t)w * u + q) * K);
                 code = (code << bits) | best;
             }
             cuckoo_find(slots, my_meta, code, &start, &len);
         }
+        __syncthreads();  // codes[] aliases p_pref
         LSH_TRACE(0, 3);
         uint32_t total;
         const uint32_t incl = block_incl_scan(len, wsum, &total);
@@ -229,19 +287,10 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
         p_pref[tid] = incl - len;
         __syncthreads();
         // Algorithm 1 lines 3-6 as a flat walk over all spans of the chunk: element e belongs
-        // to the last pair whose exclusive prefix is <= e
+        // to the last pair whose exclusive prefix is <= e.  Two span reads in flight per thread.
         for (uint32_t e0 = tid; e0 < total; e0 += 2 * kCandThreads) {
-            // two independent span reads in flight per thread
             const uint32_t ea = e0, eb = min(e0 + (uint32_t)kCandThreads, total - 1);
-            int la = 0, ha = kCandThreads, lb = 0, hb = kCandThreads;
-            while (ha - la > 1) {
-                const int mid = (la + ha) >> 1;
-                if (p_pref[mid] <= ea) la = mid; else ha = mid;
-            }
-            while (hb - lb > 1) {
-                const int mid = (lb + hb) >> 1;
-                if (p_pref[mid] <= eb) lb = mid; else hb = mid;
-            }
+            const int la = last_not_above(p_pref, ea), lb = last_not_above(p_pref, eb);
             const int32_t ida = words[(size_t)p_band[la] * V + p_start[la] + (ea - p_pref[la])];
             const int32_t idb = words[(size_t)p_band[lb] * V + p_start[lb] + (eb - p_pref[lb])];
             atomicOr(&bm[ida >> 5], 1u << (ida & 31));
@@ -251,36 +300,79 @@ k_candidates(const float* __restrict__ H, int B, int d, const int32_t* __restric
         LSH_TRACE(0, 5);
     }
 
+}
+
+// One workgroup per sentence.  Requires W <= kCandThreads.
+__global__ void __launch_bounds__(kCandThreads)
+k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count) {
+    extern __shared__ uint32_t smem[];
+    const int s = blockIdx.x;
+    const int tid = threadIdx.x, wv = wave_id(), ln = lane_id();
+    const int V = a.V;
+    const int nwords = (V + 31) >> 5;
+    uint32_t* bm = smem;
+    uint32_t* wsum = smem + candidates_lds_words(a.V, a.d, a.P, a.K) - 64;
+    build_presence_bitmap(a, s, smem);
+
     // Compaction (Eq. 10 with t = 1; the paper's Fig. 5 step): each wave owns a contiguous range
     // of bitmap words (a multiple of 64 of them); popcount + wave prefix sum give every lane the
-    // output offset of its word's ids.
-    const int wv = wave_id(), ln = lane_id();
+    // output offset of its word's ids.  A sparse word is expanded by its own lane (neighbouring
+    // lanes write neighbouring addresses).  Dense words -- the top-frequent ids usually fill
+    // whole words -- would make each lane write a long private run, 128 bytes apart from its
+    // neighbour's; they are expanded two at a time by 32 lanes each, one lane per bit, so that
+    // their stores are contiguous.
     int per_wave = (nwords + kCandWaves - 1) / kCandWaves;
     per_wave = (per_wave + kWave - 1) / kWave * kWave;
     const int wbeg = wv * per_wave;
     const int wend = min(nwords, wbeg + per_wave);
     uint32_t cnt = 0;
     for (int i = wbeg + ln; i < wend; i += kWave) cnt += __popc(bm[i]);
+    LSH_TRACE(0, 7);
     cnt = wave_sum(cnt);
     if (ln == 0) wsum[wv] = cnt;
+    LSH_TRACE(0, 8);
     __syncthreads();
+    LSH_TRACE(0, 9);
     uint32_t running = 0, total = 0;
     for (int i = 0; i < kCandWaves; ++i) {
         const uint32_t x = wsum[i];
         if (i < wv) running += x;
         total += x;
     }
+    LSH_TRACE(0, 10);
     int32_t* out = cand + (size_t)s * V;
+    const int half = ln >> 5, hbit = ln & 31;
     for (int i0 = wbeg; i0 < wend; i0 += kWave) {
         const int i = i0 + ln;
-        uint32_t bitsw = (i < wend) ? bm[i] : 0u;
+        const uint32_t bitsw = (i < wend) ? bm[i] : 0u;
         const uint32_t c = __popc(bitsw);
         const uint32_t incl = wave_incl_scan(c);
-        uint32_t off = running + incl - c;
-        while (bitsw) {
-            const int b = __ffs(bitsw) - 1;
-            out[off++] = (i << 5) + b;
-            bitsw &= bitsw - 1;
+        const uint32_t off = running + incl - c;
+        const bool dense = c >= 12;
+        uint64_t dmask = __ballot(dense);
+        if (!dense) {
+            uint32_t b = bitsw, o = off;
+            while (b) {
+                out[o++] = (i << 5) + (__ffs(b) - 1);
+                b &= b - 1;
+            }
+        }
+        while (dmask) {  // wave-uniform
+            const int la = __ffsll((unsigned long long)dmask) - 1;
+            dmask &= dmask - 1;
+            const int lb = dmask ? __ffsll((unsigned long long)dmask) - 1 : la;
+            const bool have_b = dmask != 0;
+            dmask &= dmask - 1;  // no-op on zero
+            const uint32_t wa = wave_read_lane(bitsw, la), wb = wave_read_lane(bitsw, lb);
+            const uint32_t oa = wave_read_lane(off, la), ob = wave_read_lane(off, lb);
+            const uint32_t wbits = half ? wb : wa;
+            const uint32_t woff = half ? ob : oa;
+            const int wlane = half ? lb : la;
+            const bool set = ((wbits >> hbit) & 1u) && (half == 0 || have_b);
+            const uint64_t bal = __ballot(set);
+            const uint32_t hm = half ? (uint32_t)(bal >> 32) : (uint32_t)bal;
+            const uint32_t pos = __popc(hm & ((1u << hbit) - 1u));
+            if (set) out[woff + pos] = ((i0 + wlane) << 5) + hbit;
         }
         running += wave_read_lane(incl, kWave - 1);
     }

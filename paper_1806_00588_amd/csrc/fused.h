@@ -1,0 +1,105 @@
+// Candidate generation fused into the logits kernel, for steps with little work (few sentences).
+//
+// With one sentence of a dozen beams the whole step moves ~9 MB: it is bound by its chain of
+// dependent memory round trips and by kernel boundaries, not by bandwidth.  Here every workgroup
+// of the logits grid rebuilds the sentence's presence bitmap for itself in LDS (hashing, cuckoo
+// probes, bucket walk: ~70 KB of cache-resident reads), prefix-sums the bitmap words' popcounts,
+// and finds the 16 candidates of each of its tiles by rank: a branch-free search of the prefix
+// array for the word that holds the wanted output position, then the bit of that rank inside
+// the word.  The candidate list is never needed before the contraction starts, so the separate
+// candidates kernel, its compaction stores, and the count/list loads of the logits kernel all
+// disappear; the dense ascending list is still emitted (each tile stores its 16 ids), because
+// the selection kernel and the inspection calls read it.  The work is redundant across the
+// workgroups on purpose: it runs concurrently on otherwise idle CUs and shortens the critical
+// path.  Steps with many sentences keep the three-kernel path (there the candidates kernel is
+// amortised and throughput matters, not latency).
+#pragma once
+#include "candidates.h"
+#include "logits.h"
+
+namespace lshbeam {
+
+constexpr int kFusedWaves = kCandThreads / kWave;  // 16: the split-k width of the contraction
+
+__host__ __device__ inline uint32_t pow2_at_least(uint32_t x) {
+    uint32_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// LDS words: candidate generation + prefix array (padded to a power of two, plus one) + the
+// cross-wave reduction buffer of the contraction.
+__host__ __device__ inline size_t fused_lds_words(int V, int d, int P, int K) {
+    const uint32_t nwords = (uint32_t)(((size_t)V + 31) / 32);
+    return candidates_lds_words(V, d, P, K) + pow2_at_least(nwords) + 1 +
+           (size_t)kFusedWaves * 4 * kWave;
+}
+
+// grid = S * G workgroups: workgroup b works for sentence b % S and takes that sentence's tiles
+// (b / S), (b / S) + G, ...
+template <typename ET, bool ALIGNED>
+__global__ void __launch_bounds__(kCandThreads)
+k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* __restrict__ cand,
+              int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
+              float2* __restrict__ partials, int64_t ppitch) {
+    extern __shared__ uint32_t smem[];
+    const int tid = threadIdx.x, ln = lane_id();
+    const int s = blockIdx.x % S;
+    const int g = blockIdx.x / S, G = gridDim.x / S;
+    const int V = a.V, B = a.B;
+    const int nwords = (V + 31) >> 5;
+    const uint32_t npow = pow2_at_least((uint32_t)nwords);
+    uint32_t* bm = smem;
+    uint32_t* wsum = smem + candidates_lds_words(V, a.d, a.P, a.K) - 64;
+    uint32_t* wpref = smem + candidates_lds_words(V, a.d, a.P, a.K);
+    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + npow + 1);
+
+    build_presence_bitmap(a, s, smem);
+
+    // exclusive prefix of the bitmap words' popcounts; entries past the last word hold the total
+    const int per_thread = (int)((npow + kCandThreads - 1) / kCandThreads);
+    const int wbeg = tid * per_thread;
+    uint32_t mine = 0;
+    for (int i = wbeg; i < wbeg + per_thread; ++i) mine += (i < nwords) ? __popc(bm[i]) : 0u;
+    uint32_t total;
+    uint32_t run = block_incl_scan(mine, wsum, &total) - mine;
+    for (int i = wbeg; i < wbeg + per_thread; ++i) {
+        if (i < (int)npow) wpref[i] = run;
+        run += (i < nwords) ? __popc(bm[i]) : 0u;
+    }
+    if (tid == 0) wpref[npow] = total;
+    __syncthreads();
+    LSH_TRACE(0, 6);
+    const int C = (int)total;
+    if (g == 0 && tid == 0) count[s] = C;
+
+    const int MT = (B + kTileM - 1) / kTileM;
+    const int ntiles = (C + kTileN - 1) / kTileN;
+    const int col = ln & 15;
+    for (int nt = g; nt < ntiles; nt += G) {
+        // this lane's candidate: output position 16 nt + col of the ascending list (clamped onto
+        // the last one past the end; such columns are never stored)
+        const uint32_t jpos = (uint32_t)min(nt * kTileN + col, C - 1);
+        uint32_t lo = 0;
+        for (uint32_t step = npow >> 1; step >= 1; step >>= 1)
+            if (wpref[lo + step] <= jpos) lo += step;  // last word whose prefix is <= jpos
+        uint32_t wbits = bm[lo];
+        uint32_t nth = jpos - wpref[lo];  // rank of the wanted bit inside the word
+        int pos = 0;
+#pragma unroll
+        for (int width = 16; width >= 1; width >>= 1) {
+            const uint32_t low = wbits & ((1u << width) - 1u);
+            const uint32_t c = __popc(low);
+            if (nth >= c) { nth -= c; wbits >>= width; pos += width; }
+            else wbits = low;
+        }
+        const int32_t id = (int32_t)((lo << 5) + pos);
+        if (tid < kTileN && nt * kTileN + col < C) cand[(size_t)s * V + nt * kTileN + col] = id;
+        LSH_TRACE(1, 2);
+        for (int mt = 0; mt < MT; ++mt)
+            logits_tile<ET, kFusedWaves, 4, ALIGNED>(E, ld, a.d, a.H, B, s, mt, nt, C, (int64_t)id,
+                                                     logits, cpitch, partials, ppitch, red);
+    }
+}
+
+}  // namespace lshbeam

@@ -49,32 +49,110 @@ constexpr int kTileN = 16;  // candidates per tile
 constexpr int kTileM = 16;  // hidden rows per tile
 constexpr int kMaxSentencesLogits = 4096;
 
+// One tile: logits of hidden rows [16 mt, 16 mt + 16) of sentence s against 16 candidates, this
+// lane's candidate being row j of E (lanes beyond the list hold any valid row; their results are
+// dropped).  Called by all WAVES*64 threads of the workgroup; contains two workgroup barriers.
+//
 // ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
 // d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
+__device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld, int d,
+                                            const float* __restrict__ H, int B, int s, int mt,
+                                            int nt, int C, int64_t j, float* __restrict__ logits,
+                                            int64_t cpitch, float2* __restrict__ partials,
+                                            int64_t ppitch, float (*red)[4][kWave]) {
+    constexpr int VEC = ElemTraits<ET>::VEC;
+    constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
+    const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    const int col = ln & 15, kq = ln >> 4;
+    const int nks = (d + KSTEP - 1) / KSTEP;
+    const int n0 = nt * kTileN;
+    const ET* erow = E + j * ld;
+    const int hr = min(mt * kTileM + col, B - 1);  // clamped like the candidate: never stored
+    const float* hrow = H + ((size_t)s * B + hr) * d;
+
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int ks0 = wv; ks0 < nks; ks0 += WAVES * UNROLL) {
+        float ev[UNROLL][VEC], hv[UNROLL][VEC];
+#pragma unroll
+        for (int uu = 0; uu < UNROLL; ++uu) {
+            const int k = (ks0 + uu * WAVES) * KSTEP + kq * VEC;
+            if (ALIGNED) {
+                if (k < d) {
+                    ElemTraits<ET>::load16(erow + k, ev[uu]);
+#pragma unroll
+                    for (int q = 0; q < VEC; q += 4) {
+                        const float4 h4 = *reinterpret_cast<const float4*>(hrow + k + q);
+                        hv[uu][q] = h4.x; hv[uu][q + 1] = h4.y;
+                        hv[uu][q + 2] = h4.z; hv[uu][q + 3] = h4.w;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) { ev[uu][q] = 0.f; hv[uu][q] = 0.f; }
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < VEC; ++q) {
+                    const bool in = (k + q) < d;
+                    ev[uu][q] = in ? elem_f32(erow + k + q) : 0.f;
+                    hv[uu][q] = in ? hrow[k + q] : 0.f;
+                }
+            }
+        }
+#pragma unroll
+        for (int uu = 0; uu < UNROLL; ++uu)
+#pragma unroll
+            for (int q = 0; q < VEC; ++q)
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[uu][q], ev[uu][q], acc, 0, 0, 0);
+    }
+
+    LSH_TRACE(1, 3);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[r];
+    __syncthreads();
+    if (tid < kTileM * kTileN) {
+        const int i = tid >> 4, jc = tid & 15;
+        const int src = (i >> 2) * 16 + jc, r = i & 3;
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
+        const int row = mt * kTileM + i, c = n0 + jc;
+        const bool valid = row < B && c < C;
+        if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
+        // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
+        // tile's 16 candidates; the 16 lanes that share a row are one DPP row
+        const float mx = row16_max(valid ? sum : -INFINITY);
+        const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
+        if (jc == 0 && row < B)
+            partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+    }
+    __syncthreads();
+    LSH_TRACE(1, 4);
+}
+
 template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(WAVES * kWave)
 k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
          const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
          float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
          int64_t ppitch) {
-    constexpr int VEC = ElemTraits<ET>::VEC;
-    constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
     __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
     __shared__ float red[WAVES][4][kWave];
 
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    (void)tid;
     const int MT = (B + kTileM - 1) / kTileM;
 
     LSH_TRACE(1, 0);
     // Workgroups are dealt to the 8 XCDs round-robin by the dispatcher; renumber them so that
     // consecutive logical ids (which take neighbouring tiles) share an XCD and its L2.
-    const uint32_t G = gridDim.x;
-    const uint32_t per_xcd = G >> 3;
     // (Only worth it when several M-tiles re-read the same candidate rows; with one M-tile the
     // plain order lets the first workgroups dispatched be the ones that have work.)
+    const uint32_t G = gridDim.x;
+    const uint32_t per_xcd = G >> 3;
     const uint32_t logical = ((G & 7u) || MT == 1) ? blockIdx.x
                                                    : (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
-    const int col = ln & 15, kq = ln >> 4;
+    const int col = ln & 15;
 
     // With a single sentence the first tile's candidate ids do not depend on the count: request
     // them together with it instead of after it (one dependent memory round trip less).
@@ -105,8 +183,6 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
     LSH_TRACE(1, 1);
     const uint32_t total_tiles = tile_pref[S];
 
-    const int nks = (d + KSTEP - 1) / KSTEP;
-
     for (uint32_t t = logical; t < total_tiles; t += G) {
         int lo = 0, hi = S;  // sentence: last s with tile_pref[s] <= t
         while (hi - lo > 1) {
@@ -127,67 +203,8 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
         else
             j = cand ? cand[(size_t)s * V + cidx] : cidx;
         LSH_TRACE(1, 2);
-        const ET* erow = E + j * ld;
-        const int hr = min(mt * kTileM + col, B - 1);
-        const float* hrow = H + ((size_t)s * B + hr) * d;
-
-        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
-        for (int ks0 = wv; ks0 < nks; ks0 += WAVES * UNROLL) {
-            float ev[UNROLL][VEC], hv[UNROLL][VEC];
-#pragma unroll
-            for (int uu = 0; uu < UNROLL; ++uu) {
-                const int k = (ks0 + uu * WAVES) * KSTEP + kq * VEC;
-                if (ALIGNED) {
-                    if (k < d) {
-                        ElemTraits<ET>::load16(erow + k, ev[uu]);
-#pragma unroll
-                        for (int q = 0; q < VEC; q += 4) {
-                            const float4 h4 = *reinterpret_cast<const float4*>(hrow + k + q);
-                            hv[uu][q] = h4.x; hv[uu][q + 1] = h4.y;
-                            hv[uu][q + 2] = h4.z; hv[uu][q + 3] = h4.w;
-                        }
-                    } else {
-#pragma unroll
-                        for (int q = 0; q < VEC; ++q) { ev[uu][q] = 0.f; hv[uu][q] = 0.f; }
-                    }
-                } else {
-#pragma unroll
-                    for (int q = 0; q < VEC; ++q) {
-                        const bool in = (k + q) < d;
-                        ev[uu][q] = in ? elem_f32(erow + k + q) : 0.f;
-                        hv[uu][q] = in ? hrow[k + q] : 0.f;
-                    }
-                }
-            }
-#pragma unroll
-            for (int uu = 0; uu < UNROLL; ++uu)
-#pragma unroll
-                for (int q = 0; q < VEC; ++q)
-                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[uu][q], ev[uu][q], acc, 0, 0, 0);
-        }
-
-        LSH_TRACE(1, 3);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[r];
-        __syncthreads();
-        if (tid < kTileM * kTileN) {
-            const int i = tid >> 4, jc = tid & 15;
-            const int src = (i >> 2) * 16 + jc, r = i & 3;
-            float sum = 0.f;
-#pragma unroll
-            for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
-            const int row = mt * kTileM + i, c = n0 + jc;
-            const bool valid = row < B && c < C;
-            if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
-            // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
-            // tile's 16 candidates; the 16 lanes that share a row are one DPP row
-            const float mx = row16_max(valid ? sum : -INFINITY);
-            const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
-            if (jc == 0 && row < B)
-                partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
-        }
-        __syncthreads();
-        LSH_TRACE(1, 4);
+        logits_tile<ET, WAVES, UNROLL, ALIGNED>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
+                                                partials, ppitch, red);
     }
 }
 

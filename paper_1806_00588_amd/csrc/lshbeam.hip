@@ -15,6 +15,7 @@
 #include <vector>
 
 #include "candidates.h"
+#include "fused.h"
 #include "logits.h"
 #include "select.h"
 
@@ -58,6 +59,7 @@ struct lsh_tables {
     std::vector<HostBand> bands;
     std::vector<Slot> slots_host;
     int wg_candidates_lds = 0;
+    int wg_fused_lds = 0;
     Profiler prof;
 };
 
@@ -358,6 +360,14 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (t->wg_candidates_lds > 48 * 1024)
         HIP_TRY(hipFuncSetAttribute((const void*)k_candidates,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_candidates_lds));
+    t->wg_fused_lds = (int)(fused_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
+    if ((size_t)t->wg_fused_lds <= kMaxDynLds) {
+        const void* fused[4] = {(const void*)k_cand_logits<float, true>, (const void*)k_cand_logits<float, false>,
+                                (const void*)k_cand_logits<uint16_t, true>,
+                                (const void*)k_cand_logits<uint16_t, false>};
+        for (const void* f : fused)
+            HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_fused_lds));
+    }
     guard.t = nullptr;
     *out = t;
     return LSH_OK;
@@ -385,16 +395,43 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     hipStream_t st = (hipStream_t)hip_stream;
     const int32_t* cand = nullptr;
     const int32_t* count = nullptr;
-    if (!sp->full_vocab) {
-        launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads), (size_t)t->wg_candidates_lds, st,
-               H_dev, sp->B, t->d, (const int32_t*)t->perms_dev, t->P, t->K, t->W, t->bits,
-               (const Slot*)t->slots_dev, (const BandMeta*)t->bands_dev, (const int32_t*)t->words_dev,
-               t->V, topfreq_dev, sp->T, w.cand, w.count);
+    const CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
+                      t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T};
+    const int MT = (sp->B + kTileM - 1) / kTileM;
+    // Little work per step (few sentences): every workgroup of the logits grid regenerates the
+    // candidates itself; otherwise one candidates workgroup per sentence, then the logits grid.
+    bool fused = !sp->full_vocab && sp->S * MT <= 8 && (size_t)t->wg_fused_lds <= kMaxDynLds;
+    fused = env_int("LSHBEAM_FUSED", fused ? 1 : 0) != 0 && !sp->full_vocab &&
+            (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
+    if (fused) {
+        const int per_sentence = std::max(1, env_int("LSHBEAM_FUSED_GRID", 256) / sp->S);
+        const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
+        const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
+        if (t->dtype == LSH_F32) {
+            const bool al = aligned16 && t->ld % 4 == 0;
+            if (al) launch(t, 1, k_cand_logits<float, true>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+                           (const float*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
+            else launch(t, 1, k_cand_logits<float, false>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+                        (const float*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
+        } else {
+            const bool al = aligned16 && t->ld % 8 == 0 && t->d % 8 == 0;
+            if (al) launch(t, 1, k_cand_logits<uint16_t, true>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+                           (const uint16_t*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
+            else launch(t, 1, k_cand_logits<uint16_t, false>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+                        (const uint16_t*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
+        }
         cand = w.cand;
         count = w.count;
+    } else {
+        if (!sp->full_vocab) {
+            launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads), (size_t)t->wg_candidates_lds, st,
+                   ca, w.cand, w.count);
+            cand = w.cand;
+            count = w.count;
+        }
+        if (t->dtype == LSH_F32) launch_logits<float>(t, st, H_dev, sp, cand, count, w);
+        else launch_logits<uint16_t>(t, st, H_dev, sp, cand, count, w);
     }
-    if (t->dtype == LSH_F32) launch_logits<float>(t, st, H_dev, sp, cand, count, w);
-    else launch_logits<uint16_t>(t, st, H_dev, sp, cand, count, w);
     launch(t, 2, k_select, dim3(sp->S), dim3(kSelThreads), 0, st, (const float*)w.logits, w.cpitch,
            (const float2*)w.partials, w.ppitch, cand, count, t->V, sp->B, beam_scores_dev, w.lse,
            out_beam_dev, out_word_dev, out_score_dev);
