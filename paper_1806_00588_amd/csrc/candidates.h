@@ -172,8 +172,11 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
             r3 = H4[min(tid + 3 * kCandThreads, n4 - 1)];
         }
     }
-    for (int i = tid; i < P * K; i += kCandThreads) lperms[i] = perms[i];
+    const int32_t perm_first = (tid < P * K) ? perms[tid] : 0;
+    __builtin_amdgcn_sched_barrier(0);  // keep the loads above where they are: issued first
     for (int i = tid; i < nwords; i += kCandThreads) bm[i] = 0u;
+    if (tid < P * K) lperms[tid] = perm_first;
+    for (int i = tid + kCandThreads; i < P * K; i += kCandThreads) lperms[i] = perms[i];
     __syncthreads();
     LSH_TRACE(0, 1);
 
@@ -201,6 +204,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         }
         if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
     }
+    LSH_TRACE(0, 11);
 
     for (int row0 = 0; row0 < B; row0 += rows_per_chunk) {
         const int rows = min(rows_per_chunk, B - row0);
@@ -228,6 +232,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         } else {
             for (int e = tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
         }
+        LSH_TRACE(0, 12);
         __syncthreads();
         LSH_TRACE(0, 2);
 

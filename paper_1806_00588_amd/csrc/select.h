@@ -8,10 +8,9 @@
 //      combined from those pairs, so no exponential is taken per logit here -- and the tile
 //      maxima are all this kernel needs to read of most of the logits:
 //   2. score = beam_score + (logit - lse).  Every lane keeps the best tile-maximum score it
-//      strides over; per wave the B-th largest of the 64 lane values (bitwise descent on wave
-//      ballots, scalar registers) is a lower bound on the B-th largest score overall, because B
-//      distinct scores (the maxima of B different tiles) are >= it; tau = the largest such bound
-//      over the waves.
+//      strides over; per wave the k-th largest of the 64 lane values (bitwise descent on wave
+//      ballots, scalar registers) gives lower bounds tau on the B-th largest score overall,
+//      because B distinct scores (the maxima of B different tiles) are >= tau.
 //   3. Only tiles whose maximum reaches tau can hold a winner: their 16 logits are read and the
 //      scores >= tau -- a few B on unordered data -- are appended to a short LDS list, which is
 //      ranked by counting: that sorts it and the first B are the answer.
@@ -29,8 +28,10 @@ namespace lshbeam {
 
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / kWave;
-constexpr int kSelListCap = 1024;    // short list of keys >= tau (== kSelThreads)
-constexpr int kSelBatch = 8;         // tile partials in flight per lane
+constexpr int kSelListCap = 4096;    // short list of keys >= tau
+constexpr int kSelRankCap = 1024;    // keys ranked directly (== kSelThreads)
+constexpr int kSelRefineAbove = 256; // longer lists are thinned once more before ranking
+constexpr int kSelBatch = 4;         // tile partials in flight per lane
 
 __device__ __forceinline__ uint64_t make_key(float v, uint32_t index) {
     return ((uint64_t)f32_sortable(v + 0.0f) << 32) | (uint64_t)(~index);
@@ -38,14 +39,16 @@ __device__ __forceinline__ uint64_t make_key(float v, uint32_t index) {
 __device__ __forceinline__ float key_value(uint64_t k) { return sortable_f32((uint32_t)(k >> 32)); }
 __device__ __forceinline__ uint32_t key_index(uint64_t k) { return ~(uint32_t)k; }
 
-// Lower bound (bits 11..0 left at zero) of the k-th largest, k in 1..64, of the 64 lanes' values.
-// Wave-uniform result; everything lives in scalar registers.
+// The k-th largest, k in 1..64, of the 64 lanes' values (0 if fewer than k lanes are non-zero).
+// Wave-uniform result; everything lives in scalar registers.  All 32 bits are resolved: scores
+// accumulate over the steps of a sentence, and at |score| ~ 300 the low 12 bits of an fp32 span
+// 0.1 -- a threshold that coarse would let thousands of scores through.
 __device__ __forceinline__ uint32_t wave_kth_largest_lb(uint32_t v, int k) {
     uint64_t active = ~0ull;
     uint32_t kth = 0;
     int need = k;
 #pragma unroll 4
-    for (int bit = 31; bit >= 12; --bit) {
+    for (int bit = 31; bit >= 0; --bit) {
         const uint64_t ones = __ballot((v >> bit) & 1u) & active;
         const int c = __popcll(ones);
         if (c >= need) { active = ones; kth |= 1u << bit; }
@@ -69,13 +72,36 @@ __device__ __forceinline__ void wave_lds_sync() {
 struct SelShared {
     int32_t open_tiles[kSelWaves][kSelBatch * kWave];  // per wave: tiles to open in this batch
     uint64_t list[kSelListCap];
-    uint32_t rank[kSelListCap];
+    uint32_t rank[kSelRankCap];
     uint32_t hist[256];
     float lse[256];
     float bs[256];
     uint32_t wtau[kSelWaves];
+    uint32_t bitcnt[2][kSelWaves];
     uint32_t misc[8];
 };
+
+// The k-th largest of the workgroup's 1024 thread values, k in 1..1024: the same bitwise descent
+// as wave_kth_largest_lb, with the per-bit population summed over the waves through LDS (one
+// barrier per bit; the counters are double-buffered).
+__device__ __forceinline__ uint32_t block_kth_largest_lb(uint32_t v, int k, SelShared* sh) {
+    const int wv = wave_id();
+    uint64_t active = ~0ull;
+    uint32_t kth = 0;
+    int need = k;
+    for (int bit = 31; bit >= 0; --bit) {
+        const uint64_t ones = __ballot((v >> bit) & 1u) & active;
+        uint32_t* cnt = sh->bitcnt[bit & 1];
+        if (lane_id() == 0) cnt[wv] = (uint32_t)__popcll(ones);
+        __syncthreads();
+        int c = 0;
+#pragma unroll
+        for (int w = 0; w < kSelWaves; ++w) c += (int)cnt[w];
+        if (c >= need) { active = ones; kth |= 1u << bit; }
+        else { need -= c; active &= ~ones; }
+    }
+    return kth;
+}
 
 // Everything a sweep over the sentence's scores needs.
 struct ScoreSrc {
@@ -92,7 +118,7 @@ struct ScoreSrc {
 
 // Exact B largest keys by the whole workgroup: radix select, 8-bit digits, most significant
 // first.  Writes them to list[] in any order.  Needs B*C > B.  Out of line: it only runs when
-// more than kSelListCap scores tie at the threshold.
+// more than kSelRankCap scores are left after thinning (heavy ties).
 __device__ __noinline__ void block_radix_select(ScoreSrc src, int k, SelShared* sh) {
     // arguments of an out-of-line call arrive in vector registers: mark the uniform ones
     src.B = __builtin_amdgcn_readfirstlane(src.B);
@@ -205,18 +231,22 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     }
     LSH_TRACE(2, 1);
 
-    // ---- threshold: per wave the kw-th largest lane value.  B <= 64: kw = B and tau is the
-    //      largest over the waves (that wave alone holds B scores >= tau).  More beams:
-    //      kw = ceil(B/16) and tau is the smallest over the waves (16 * kw >= B scores). ----
-    const int kw = (B <= kWave) ? B : (B + kSelWaves - 1) / kSelWaves;
-    const uint32_t kth = wave_kth_largest_lb(lmax, kw);
-    if (ln == 0) sh.wtau[wv] = kth;
-    __syncthreads();
-    uint32_t tau = sh.wtau[0];
+    // ---- threshold tau: a lower bound of the B-th best score from the 16 x 64 lane values
+    //      (B distinct tile maxima are >= it).  Up to 16 beams every row has its own wave, and
+    //      the largest over the waves of "B-th largest lane value in the wave" costs no barrier
+    //      per bit; with more beams the B-th largest of all 1024 lane values is much tighter. ----
+    uint32_t tau;
+    if (B <= kSelWaves) {
+        const uint32_t kth = wave_kth_largest_lb(lmax, B);
+        if (ln == 0) sh.wtau[wv] = kth;
+        __syncthreads();
+        tau = 0;
 #pragma unroll
-    for (int w = 1; w < kSelWaves; ++w)
-        tau = (B <= kWave) ? max(tau, sh.wtau[w]) : min(tau, sh.wtau[w]);
-    if ((size_t)B * C <= (size_t)kSelListCap) tau = 0;  // everything fits the list: take it all
+        for (int w = 0; w < kSelWaves; ++w) tau = max(tau, sh.wtau[w]);
+    } else {
+        tau = block_kth_largest_lb(lmax, B, &sh);
+    }
+    if ((size_t)B * C <= (size_t)kSelRankCap) tau = 0;  // few scores: take them all
     LSH_TRACE(2, 2);
 
     // ---- second pass: tiles whose maximum reaches tau are opened, 16 lanes per tile ----
@@ -276,7 +306,32 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     __syncthreads();
     int m = (int)sh.misc[4];
     LSH_TRACE(2, 3);
-    if (m > kSelListCap) {
+    // A long list (many near-equal tile maxima, e.g. many beams) is thinned once more with the
+    // same argument applied to the list itself: thread t owns keys t, t+1024, ...; the B-th
+    // largest thread maximum bounds the B-th largest key from below.
+    if (m > kSelRefineAbove && m <= kSelListCap && m > B) {
+        uint64_t mine[kSelListCap / kSelThreads];
+        uint32_t tm = 0;
+#pragma unroll
+        for (int q = 0; q < kSelListCap / kSelThreads; ++q) {
+            const int e = tid + q * kSelThreads;
+            mine[q] = (e < m) ? sh.list[e] : 0ull;
+            tm = max(tm, (uint32_t)(mine[q] >> 32));
+        }
+        const uint32_t tau2 = block_kth_largest_lb(tm, B, &sh);  // m > 256 >= B keys exist
+        if (tid == 0) sh.misc[4] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < kSelListCap / kSelThreads; ++q) {
+            if (tid + q * kSelThreads < m && (uint32_t)(mine[q] >> 32) >= tau2) {
+                const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
+                sh.list[pos] = mine[q];  // pos < m <= kSelListCap; every old key is in registers
+            }
+        }
+        __syncthreads();
+        m = (int)sh.misc[4];
+    }
+    if (m > kSelRankCap) {
         __syncthreads();
         block_radix_select(src, B, &sh);
         m = B;
