@@ -208,4 +208,120 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
     }
 }
 
+// Throughput variant for steps with many tiles (many sentences): ONE WAVE per tile of 16
+// candidates, all k and all MT groups of 16 hidden rows in that wave.  No LDS, no barrier: the
+// accumulators go straight from the matrix core to the stores, and a candidate row is read once
+// however many beams there are.  Waves of a workgroup take consecutive tiles; the grid is
+// persistent.
+template <typename ET, int MT, int UNROLL, bool ALIGNED>
+__global__ void __launch_bounds__(256)
+k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
+              const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
+              float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
+              int64_t ppitch) {
+    constexpr int VEC = ElemTraits<ET>::VEC;
+    constexpr int KSTEP = 4 * VEC;
+    __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
+    const int ln = lane_id(), wv = wave_id();
+    LSH_TRACE(1, 0);
+    if (wv == 0) {
+        uint32_t carry = 0;
+        for (int base = 0; base < S; base += kWave) {
+            const int s = base + ln;
+            uint32_t n = 0;
+            if (s < S) n = (uint32_t)(((count ? count[s] : V) + kTileN - 1) / kTileN);
+            const uint32_t incl = wave_incl_scan(n);
+            if (s < S) tile_pref[s] = carry + incl - n;
+            carry += wave_read_lane(incl, kWave - 1);
+        }
+        if (ln == 0) tile_pref[S] = carry;
+    }
+    __syncthreads();
+    LSH_TRACE(1, 1);
+    const uint32_t total_tiles = tile_pref[S];
+    const uint32_t nwaves = gridDim.x * 4u;
+    const int col = ln & 15, kq = ln >> 4;
+    const int nks = (d + KSTEP - 1) / KSTEP;
+
+    for (uint32_t t = blockIdx.x * 4u + wv; t < total_tiles; t += nwaves) {
+        int lo = 0, hi = S;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tile_pref[mid] <= t) lo = mid; else hi = mid;
+        }
+        const int s = lo;
+        const int nt = (int)(t - tile_pref[s]);
+        const int C = count ? count[s] : V;
+        const int n0 = nt * kTileN;
+        const int cidx = min(n0 + col, C - 1);  // clamped lanes are never stored
+        const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        const ET* erow = E + j * ld;
+        const float* hrow[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+            hrow[mt] = H + ((size_t)s * B + min(mt * kTileM + col, B - 1)) * d;
+
+        floatx4 acc[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+        for (int ks0 = 0; ks0 < nks; ks0 += UNROLL) {
+            float ev[UNROLL][VEC], hv[MT][UNROLL][VEC];
+#pragma unroll
+            for (int uu = 0; uu < UNROLL; ++uu) {
+                const int k = (ks0 + uu) * KSTEP + kq * VEC;
+                if (ALIGNED) {
+                    if (k < d) {
+                        ElemTraits<ET>::load16(erow + k, ev[uu]);
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int q = 0; q < VEC; q += 4) {
+                                const float4 h4 = *reinterpret_cast<const float4*>(hrow[mt] + k + q);
+                                hv[mt][uu][q] = h4.x; hv[mt][uu][q + 1] = h4.y;
+                                hv[mt][uu][q + 2] = h4.z; hv[mt][uu][q + 3] = h4.w;
+                            }
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) {
+                            ev[uu][q] = 0.f;
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt) hv[mt][uu][q] = 0.f;
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) {
+                        const bool in = (k + q) < d;
+                        ev[uu][q] = in ? elem_f32(erow + k + q) : 0.f;
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) hv[mt][uu][q] = in ? hrow[mt][k + q] : 0.f;
+                    }
+                }
+            }
+#pragma unroll
+            for (int uu = 0; uu < UNROLL; ++uu)
+#pragma unroll
+                for (int q = 0; q < VEC; ++q)
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+                        acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[mt][uu][q], ev[uu][q],
+                                                                       acc[mt], 0, 0, 0);
+        }
+        // lane (col, kq) holds rows 16 mt + 4 kq + r of column n0 + col: 16 lanes per row
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int row = mt * kTileM + 4 * kq + r, c = n0 + col;
+                const bool valid = row < B && c < C;
+                const float x = acc[mt][r];
+                if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
+                const float mx = row16_max(valid ? x : -INFINITY);
+                const float se = row16_sum(valid ? expf(x - mx) : 0.f);
+                if (col == 0 && row < B)
+                    partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+            }
+    }
+}
+
 }  // namespace lshbeam

@@ -203,6 +203,21 @@ void launch_logits_w(lsh_tables* t, hipStream_t st, int grid, bool aligned, cons
                w.ppitch);
 }
 
+template <typename ET, int MT>
+void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
+                        const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
+                        const Workspace& w) {
+    // loads in flight per lane: 32 (fp32) / 64 (bf16) bytes of E per step, plus MT times that of H
+    constexpr int UNROLL = ((MT == 1) ? 8 : 4) / (ElemTraits<ET>::VEC / 4);
+    const ET* E = (const ET*)t->E;
+    if (aligned)
+        launch(t, 1, k_logits_wave<ET, MT, UNROLL, true>, dim3(grid), dim3(256), 0, st, E, t->ld, t->d,
+               H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
+    else
+        launch(t, 1, k_logits_wave<ET, MT, UNROLL, false>, dim3(grid), dim3(256), 0, st, E, t->ld, t->d,
+               H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
+}
+
 template <typename ET>
 void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
                    const int32_t* cand, const int32_t* count, const Workspace& w) {
@@ -210,15 +225,25 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     const bool aligned = (t->d % VEC == 0) && (t->ld % VEC == 0) && ((uintptr_t)t->E % 16 == 0) &&
                          (t->d % 4 == 0) && ((uintptr_t)H % 16 == 0);
     const int MT = (sp->B + kTileM - 1) / kTileM;
-    const int64_t max_tiles = (int64_t)sp->S * MT * ((t->V + kTileN - 1) / kTileN);
-    // few (sentence, M-tile) groups: little work per step, split k across many waves so that
-    // enough loads are in flight; otherwise 4 waves per tile
-    int waves = (sp->S * MT <= 8) ? 16 : 4;
-    waves = env_int("LSHBEAM_LOGITS_WAVES", waves);
-    if (waves >= 16) {
+    const int64_t tiles_n = (int64_t)sp->S * ((t->V + kTileN - 1) / kTileN);  // upper bound
+    const int64_t max_tiles = tiles_n * MT;
+    // Few (sentence, M-tile) groups: little work per step and it is latency that counts, so k is
+    // split across the 16 waves of a workgroup and the partial tiles are summed through LDS.
+    // Otherwise one wave per 16-candidate tile, no LDS and no barrier (up to 4 M-tiles per wave).
+    const bool few = sp->S * MT <= 8;
+    const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : (MT <= 4 ? 1 : 4));
+    if (mode == 1 && MT <= 4) {
+        const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, env_int("LSHBEAM_LOGITS_GRID", 1024));
+        switch (MT) {
+            case 1: launch_logits_wave<ET, 1>(t, st, grid, aligned, H, sp, cand, count, w); break;
+            case 2: launch_logits_wave<ET, 2>(t, st, grid, aligned, H, sp, cand, count, w); break;
+            case 3: launch_logits_wave<ET, 3>(t, st, grid, aligned, H, sp, cand, count, w); break;
+            default: launch_logits_wave<ET, 4>(t, st, grid, aligned, H, sp, cand, count, w); break;
+        }
+    } else if (mode >= 16) {
         const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 256));
         launch_logits_w<ET, 16>(t, st, grid, aligned, H, sp, cand, count, w);
-    } else if (waves >= 8) {
+    } else if (mode >= 8) {
         const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 1024));
         launch_logits_w<ET, 8>(t, st, grid, aligned, H, sp, cand, count, w);
     } else {
