@@ -97,8 +97,11 @@ __host__ __device__ inline int candidates_rows_per_chunk(int B, int d, int W) {
 }
 
 // LDS words k_candidates needs.  The stage always holds at least one hidden row.
+// Words reserved for the V-bit bitmap: rounded to 4 so that what follows is 16-byte aligned.
+__host__ __device__ inline int bitmap_words_padded(int V) { return (((V + 31) >> 5) + 3) & ~3; }
+
 __host__ __device__ inline size_t candidates_lds_words(int V, int d, int P, int K) {
-    const size_t nwords = ((size_t)V + 31) / 32;
+    const size_t nwords = (size_t)bitmap_words_padded(V);
     const size_t stage = (size_t)d > (size_t)kCandStage ? (size_t)d : (size_t)kCandStage;
     return nwords + stage + (size_t)P * K + 3 * (size_t)kCandThreads + 64;
 }
@@ -141,9 +144,10 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     const int nwords = (V + 31) >> 5;
     const int stage_words = d > kCandStage ? d : kCandStage;
     uint32_t* bm = smem;                                   // presence bitmap, V bits
-    float* stage = reinterpret_cast<float*>(bm + nwords);  // the chunk's hidden rows [rows][d]
-    int32_t* lperms = reinterpret_cast<int32_t*>(bm + nwords + stage_words);  // perms [P][K]
-    uint32_t* p_start = bm + nwords + stage_words + P * K; // span start of each pair in the chunk
+    const int bmw = bitmap_words_padded(V);
+    float* stage = reinterpret_cast<float*>(bm + bmw);     // the chunk's hidden rows [rows][d]
+    int32_t* lperms = reinterpret_cast<int32_t*>(bm + bmw + stage_words);  // perms [P][K]
+    uint32_t* p_start = bm + bmw + stage_words + P * K;    // span start of each pair in the chunk
     uint32_t* p_band = p_start + kCandThreads;             // its band
     uint32_t* p_pref = p_band + kCandThreads;              // exclusive prefix of span lengths
     uint32_t* wsum = p_pref + kCandThreads;                // scan scratch (>= kCandWaves + 1)

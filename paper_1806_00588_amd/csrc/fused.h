@@ -75,6 +75,11 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
 
     const int MT = (B + kTileM - 1) / kTileM;
     const int ntiles = (C + kTileN - 1) / kTileN;
+    // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
+    // the contraction takes its A operands from there instead of reading H again
+    const float* h_lds = nullptr;
+    if (candidates_rows_per_chunk(B, a.d, a.W) >= B && (a.d & 3) == 0)
+        h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
     const int col = ln & 15;
     for (int nt = g; nt < ntiles; nt += G) {
         // this lane's candidate: output position 16 nt + col of the ascending list (clamped onto
@@ -98,7 +103,7 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
         LSH_TRACE(1, 2);
         for (int mt = 0; mt < MT; ++mt)
             logits_tile<ET, kFusedWaves, 4, ALIGNED>(E, ld, a.d, a.H, B, s, mt, nt, C, (int64_t)id,
-                                                     logits, cpitch, partials, ppitch, red);
+                                                     logits, cpitch, partials, ppitch, red, h_lds);
     }
 }
 

@@ -52,6 +52,7 @@ constexpr int kMaxSentencesLogits = 4096;
 // One tile: logits of hidden rows [16 mt, 16 mt + 16) of sentence s against 16 candidates, this
 // lane's candidate being row j of E (lanes beyond the list hold any valid row; their results are
 // dropped).  Called by all WAVES*64 threads of the workgroup; contains two workgroup barriers.
+// h_lds, if given, is an LDS copy of the sentence's B hidden rows (16-byte aligned, pitch d).
 //
 // ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
 // d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
@@ -60,7 +61,8 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
                                             const float* __restrict__ H, int B, int s, int mt,
                                             int nt, int C, int64_t j, float* __restrict__ logits,
                                             int64_t cpitch, float2* __restrict__ partials,
-                                            int64_t ppitch, float (*red)[4][kWave]) {
+                                            int64_t ppitch, float (*red)[4][kWave],
+                                            const float* h_lds = nullptr) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
@@ -69,7 +71,8 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
     const int n0 = nt * kTileN;
     const ET* erow = E + j * ld;
     const int hr = min(mt * kTileM + col, B - 1);  // clamped like the candidate: never stored
-    const float* hrow = H + ((size_t)s * B + hr) * d;
+    // the sentence's hidden rows, from LDS when the caller has them staged there ([B][d])
+    const float* hrow = h_lds ? h_lds + (size_t)hr * d : H + ((size_t)s * B + hr) * d;
 
     floatx4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int ks0 = wv; ks0 < nks; ks0 += WAVES * UNROLL) {
