@@ -243,9 +243,6 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     } else if (mode >= 16) {
         const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 256));
         launch_logits_w<ET, 16>(t, st, grid, aligned, H, sp, cand, count, w);
-    } else if (mode >= 8) {
-        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 1024));
-        launch_logits_w<ET, 8>(t, st, grid, aligned, H, sp, cand, count, w);
     } else {
         const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 2048));
         launch_logits_w<ET, 4>(t, st, grid, aligned, H, sp, cand, count, w);

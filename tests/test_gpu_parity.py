@@ -131,10 +131,14 @@ def test_tiny_many_sentences_and_other_beam_counts():
     cfg, gc = case("tiny")
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)          # 80 rows
     rng = np.random.default_rng(2)
-    for S, B in [(5, 16), (2, 17), (80, 1), (3, 20), (1, 33)]:
+    # few (sentence, 16-row group) pairs -> fused kernel; many -> one wave per tile with 1..4
+    # row groups; more than 64 beams -> split-k kernel with several row groups
+    H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)      # 160 rows
+    for S, B in [(5, 16), (2, 17), (80, 1), (3, 20), (1, 33), (9, 17), (4, 40), (3, 50), (2, 70)]:
         bs = (rng.standard_normal(S * B) * 2).astype(np.float32)
         run_and_check(cfg, gc, H[:S * B], bs, S, B)
     run_and_check(cfg, gc, H[:34], np.zeros(34, np.float32), 2, 17, full_vocab=True)
+    run_and_check(cfg, gc, H[:153], np.zeros(153, np.float32), 9, 17, full_vocab=True)
 
 
 def test_paper_shape_steps():
