@@ -29,8 +29,8 @@ def log(*a):
 
 
 def measured_traffic(workload: str):
-    """HBM bytes per k_logits launch from the committed rocprofv3 --pmc summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"k_logits_{workload}_pmc.md")
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
+    path = os.path.join(ROOT, "profiles", f"k_cand_logits_{workload}_pmc.md")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -51,6 +51,9 @@ def main():
                          "stream: launch every step from the host")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
+    ap.add_argument("--no-regime", action="store_true",
+                    help="skip the extra bandwidth-regime measurement (the logits kernel on the "
+                         "32-sentence 'batched' shape, same embeddings and tables)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling rocprofv3 --pmc "
@@ -189,7 +192,10 @@ def main():
     k_ms = prof["k_logits"][0]
     achieved = alg_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
     flops = 2.0 * B * mean_rows * cfg.d
-    roofline = {"kernel": "k_logits", "bound": "hbm", "achieved": round(achieved, 1),
+    fused = binding.step_is_fused(tables, sp)
+    dominant = "k_cand_logits (candidate generation fused into the logits kernel)" if fused \
+        else "k_logits"
+    roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": measured_traffic(cfg.name),
                 "algorithmic_bytes_per_launch": alg_bytes, "kernel_us": round(k_ms * 1e3, 3),
@@ -213,6 +219,41 @@ def main():
                 "algorithmic_bytes_per_step": float(S) * cfg.V * cfg.d * e_bytes}
         log(f"[bench] {cfg.name} full-vocab: {fsecs/kf*1e6:.2f} us/step -> LSH speedup "
             f"{full['lsh_speedup']}x")
+
+    # ---- the gathered contraction where bandwidth, not latency, limits it: 32 sentences on the
+    #      same embeddings and tables (the 'batched' shape), three-kernel path -------------------
+    regime = None
+    if not args.no_regime and cfg.name == "paper":
+        bcfg = workloads.CONFIGS["batched"]
+        Hb = torch.from_numpy(workloads.make_hidden(bcfg, E, seed=0, steps=8)).cuda()
+        bsp = binding.step_params(bcfg.S, bcfg.B, bcfg.T, 1, False)
+        bws = torch.empty(lsh.step_workspace_bytes(tables, bsp), dtype=torch.uint8, device="cuda")
+        bz = torch.zeros(bcfg.R, dtype=torch.float32, device="cuda")
+        bo = [torch.empty(bcfg.R, dtype=torch.int32, device="cuda") for _ in range(2)]
+        bsc = torch.empty(bcfg.R, dtype=torch.float32, device="cuda")
+        rows = []
+        for i in range(8):
+            lsh.decode_step(tables, Hb[i], bz, tf_dev, bsp, bws, bo[0], bo[1], bsc)
+            torch.cuda.synchronize()
+            rows.append(sum(len(tables.debug_candidates(bws, bsp, s)) for s in range(bcfg.S)))
+        for i in range(16):
+            lsh.decode_step(tables, Hb[i % 8], bz, tf_dev, bsp, bws, bo[0], bo[1], bsc)
+        torch.cuda.synchronize()
+        tables.profile_begin(64)
+        for i in range(64):
+            lsh.decode_step(tables, Hb[i % 8], bz, tf_dev, bsp, bws, bo[0], bo[1], bsc)
+        bprof = tables.profile_end()
+        bbytes = float(np.mean(rows)) * bcfg.d * e_bytes
+        bms = bprof["k_logits"][0]
+        regime = {"workload": f"batched: S={bcfg.S} B={bcfg.B}, same E and tables",
+                  "kernel": "k_logits_wave", "kernel_us": round(bms * 1e3, 2),
+                  "algorithmic_bytes_per_launch": bbytes,
+                  "achieved_GBps": round(bbytes / (bms * 1e-3) / 1e9, 1),
+                  "frac_of_hbm_peak": round(bbytes / (bms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "kernels_us": {k: round(v[0] * 1e3, 2) for k, v in bprof.items()}}
+        log(f"[bench] bandwidth regime ({regime['workload']}): k_logits {bms*1e3:.1f} us, "
+            f"{regime['achieved_GBps']} GB/s = {regime['frac_of_hbm_peak']*100:.1f}% of HBM peak")
+        del Hb, bws
 
     # ---- the oracle on the host cores, bounded sample -----------------------------------------
     cpu = None
@@ -247,8 +288,11 @@ def main():
                                f"W={cfg.W} T={cfg.T}, {nst}-step sentences, seed 0",
                    "mode": args.mode, "mean_candidates_per_sentence": round(mean_rows / S, 1)},
         "roofline": roofline,
-        "kernels_us": {k: round(v[0] * 1e3, 3) for k, v in prof.items()},
+        "kernels_us": {("k_cand_logits" if (fused and k == "k_logits") else k): round(v[0] * 1e3, 3)
+                       for k, v in prof.items() if v[1]},
         "full_vocab": full,
+        "bandwidth_regime": regime,
+        "step_bytes_over_step_time_GBps": round(alg_bytes / secs * K / 1e9, 1),
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -138,6 +138,12 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
 
 #define LSH_NUM_KERNELS 3 /* 0 candidates (hash+probe+merge), 1 gathered logits, 2 select */
 
+/* 1 if a step with these parameters runs candidate generation inside the logits kernel (steps
+ * with little work: few sentences; the timing slot 0 then stays empty and slot 1 covers the
+ * fused kernel `k_cand_logits`), 0 if it runs the three kernels separately. */
+int32_t lsh_step_is_fused(const lsh_tables* t, const lsh_step_params* sp);
+
+
 /* Start recording the device start/stop time of every kernel of the next steps (at most
  * max_steps of them) on this handle; lsh_profile_end synchronises the device, writes the mean
  * duration in milliseconds of each kernel and the number of recorded launches, and stops. */

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = (
     "lsh_build_tables", "lsh_free_tables", "lsh_step_workspace_bytes", "lsh_decode_step",
     "lsh_debug_codes", "lsh_debug_embedding_codes", "lsh_debug_bucket", "lsh_debug_csr",
     "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profile_begin",
-    "lsh_profile_end", "lsh_kernel_name", "lsh_status_string",
+    "lsh_profile_end", "lsh_kernel_name", "lsh_status_string", "lsh_step_is_fused",
 )
 
 
@@ -74,6 +74,7 @@ def load_library():
                                        ctypes.POINTER(ctypes.c_float), i32, i32p]
     lib.lsh_profile_begin.argtypes = [vp, i32]
     lib.lsh_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_double), i32p]
+    lib.lsh_step_is_fused.argtypes = [vp, ctypes.POINTER(StepParams)]
     lib.lsh_kernel_name.argtypes = [i32]
     lib.lsh_kernel_name.restype = ctypes.c_char_p
     lib.lsh_status_string.argtypes = [ctypes.c_int]
@@ -241,6 +242,10 @@ def build_tables(E, perms, K: int, bands: int, seed: int = 0, stream=None) -> Ta
 
 def step_params(S: int, B: int, T: int, threshold: int = 1, full_vocab: bool = False) -> StepParams:
     return StepParams(S, B, T, threshold, 1 if full_vocab else 0)
+
+
+def step_is_fused(tables: Tables, sp: StepParams) -> bool:
+    return bool(load_library().lsh_step_is_fused(tables.handle, ctypes.byref(sp)))
 
 
 def step_workspace_bytes(tables: Tables, sp: StepParams) -> int:

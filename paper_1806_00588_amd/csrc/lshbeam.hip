@@ -187,6 +187,17 @@ int env_int(const char* name, int dflt) {
     return (v && *v) ? std::atoi(v) : dflt;
 }
 
+// Little work per step (few sentences x 16-row groups): every workgroup of the logits grid
+// regenerates the candidates itself (k_cand_logits); otherwise one candidates workgroup per
+// sentence, then the logits grid.  LSHBEAM_FUSED=0/1 overrides the size rule (for tests and
+// measurements), never the hard limits.
+bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
+    const int MT = (sp->B + kTileM - 1) / kTileM;
+    const bool possible = !sp->full_vocab && (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
+    const bool wanted = env_int("LSHBEAM_FUSED", sp->S * MT <= 8 ? 1 : 0) != 0;
+    return possible && wanted;
+}
+
 template <typename ET, int WAVES>
 void launch_logits_w(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
                      const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
@@ -273,6 +284,10 @@ const char* lsh_status_string(lsh_status s) {
         case LSH_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
     }
     return "unknown status";
+}
+
+int32_t lsh_step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
+    return (step_params_ok(t, sp) && step_is_fused(t, sp)) ? 1 : 0;
 }
 
 const char* lsh_kernel_name(int32_t which) {
@@ -419,12 +434,7 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     const int32_t* count = nullptr;
     const CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
                       t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T};
-    const int MT = (sp->B + kTileM - 1) / kTileM;
-    // Little work per step (few sentences): every workgroup of the logits grid regenerates the
-    // candidates itself; otherwise one candidates workgroup per sentence, then the logits grid.
-    bool fused = !sp->full_vocab && sp->S * MT <= 8 && (size_t)t->wg_fused_lds <= kMaxDynLds;
-    fused = env_int("LSHBEAM_FUSED", fused ? 1 : 0) != 0 && !sp->full_vocab &&
-            (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
+    const bool fused = step_is_fused(t, sp);
     if (fused) {
         const int per_sentence = std::max(1, env_int("LSHBEAM_FUSED_GRID", 256) / sp->S);
         const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
