@@ -105,7 +105,7 @@ def main():
     h_ptrs = [H_dev[i].data_ptr() for i in range(nst)]
 
     def make_runner(full_vocab: bool):
-        sp = binding.step_params(S, B, cfg.T, 1, full_vocab)
+        sp = binding.step_params(S, B, cfg.T, cfg.threshold, full_vocab)
         ws = torch.empty(lsh.step_workspace_bytes(tables, sp), dtype=torch.uint8, device="cuda")
         call = binding.make_step_caller(tables, sp, ws, tf_dev)
         zp, sps = zero.data_ptr(), [score[0].data_ptr(), score[1].data_ptr()]
@@ -266,7 +266,7 @@ def main():
             st = n_done % nst
             if st == 0:
                 bs[:] = 0
-            _, _, osc, _ = ix.decode_step(H[st], bs, topfreq, S, B)
+            _, _, osc, _ = ix.decode_step(H[st], bs, topfreq, S, B, t=cfg.threshold)
             bs = osc.reshape(-1).astype(np.float32)
             n_done += 1
             el = time.perf_counter() - t0
@@ -285,7 +285,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16xf32" if cfg.e_dtype == workloads.BF16 else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg.name}: d={cfg.d} V={cfg.V} S={S} B={B} K={cfg.K} P={cfg.P} "
-                               f"W={cfg.W} T={cfg.T}, {nst}-step sentences, seed 0",
+                               f"W={cfg.W} T={cfg.T} t={cfg.threshold}, {nst}-step sentences, seed 0",
                    "mode": args.mode, "mean_candidates_per_sentence": round(mean_rows / S, 1)},
         "roofline": roofline,
         "kernels_us": {("k_cand_logits" if (fused and k == "k_logits") else k): round(v[0] * 1e3, 3)

@@ -74,7 +74,9 @@ typedef struct {
     int32_t S;          /* sentences in the call; hidden rows R = S * B                          */
     int32_t B;          /* beams per sentence, 1 .. 256; also the number of results per sentence */
     int32_t T;          /* length of the top-frequent word list (may be 0)                       */
-    int32_t threshold;  /* t of Eq. 10; only t = 1 is implemented (else LSH_ERR_UNSUPPORTED)     */
+    int32_t threshold;  /* t of Eq. 10, >= 1: a word is a candidate iff some row of the sentence
+                           shares at least t band codes with it.  t > 1 keeps a row of 16-bit
+                           hit counters in LDS: LSH_ERR_UNSUPPORTED if V is too large for that */
     int32_t full_vocab; /* 1: skip hashing, the candidate list is all of V (Eq. 1-2 as printed)  */
 } lsh_step_params;
 
@@ -136,7 +138,8 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
 
 /* ---- per-kernel timing -------------------------------------------------------------------- */
 
-#define LSH_NUM_KERNELS 3 /* 0 candidates (hash+probe+merge), 1 gathered logits, 2 select */
+#define LSH_NUM_KERNELS 4 /* 0 candidates (hash+probe+merge; t > 1: union + compaction),
+                             1 gathered logits, 2 select, 3 per-row hit counts (t > 1 only) */
 
 /* 1 if a step with these parameters runs candidate generation inside the logits kernel (steps
  * with little work: few sentences; the timing slot 0 then stays empty and slot 1 covers the

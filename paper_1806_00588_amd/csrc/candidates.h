@@ -116,6 +116,35 @@ __device__ __forceinline__ int last_not_above(const uint32_t* pref, uint32_t e) 
     return lo;
 }
 
+// Marks the ids of a list in an LDS bitmap.  Ids that fall into the same bitmap word are OR-ed
+// inside the wave first and one lane issues the atomic: same-address LDS atomics serialise, and
+// frequent-word ids tend to be consecutive.  `first` is this thread's already loaded list[tid]
+// (or -1).  Called by all kCandThreads threads.
+__device__ __forceinline__ void mark_id_list(uint32_t* bm, int V, const int32_t* __restrict__ list,
+                                             int T, int32_t first) {
+    const int tid = threadIdx.x, ln = lane_id();
+    for (int i0 = 0; i0 < T; i0 += kCandThreads) {
+        const int i = i0 + tid;
+        const int32_t id = (i0 == 0) ? first : ((i < T) ? list[i] : -1);
+        const bool ok = id >= 0 && id < V;
+        const uint32_t word = ok ? (uint32_t)(id >> 5) : 0xFFFFFFFFu;
+        const uint32_t bit = ok ? (1u << (id & 31)) : 0u;
+        uint64_t todo = __ballot(ok);
+        bool grouped = true;
+        while (todo && grouped) {
+            const int leader = __ffsll((unsigned long long)todo) - 1;
+            const uint32_t w0 = wave_read_lane(word, leader);
+            const bool mine = ok && word == w0;
+            const uint64_t grp = __ballot(mine);
+            const uint32_t ored = wave_or(mine ? bit : 0u);
+            if (ln == leader) atomicOr(&bm[w0], ored);
+            todo &= ~grp;
+            grouped = __popcll(grp) > 1;  // scattered ids: stop grouping, plain atomics below
+        }
+        if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
+    }
+}
+
 // Arguments of candidate generation (everything k_candidates takes except its outputs).
 struct CandArgs {
     const float* H;          // [S*B, d] hidden rows
@@ -152,7 +181,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     uint32_t* p_pref = p_band + kCandThreads;              // exclusive prefix of span lengths
     uint32_t* wsum = p_pref + kCandThreads;                // scan scratch (>= kCandWaves + 1)
 
-    const int tid = threadIdx.x, ln = lane_id();
+    const int tid = threadIdx.x;
     const int u = P / W;
     const int rows_per_chunk = candidates_rows_per_chunk(B, d, W);
     LSH_TRACE(0, 0);
@@ -184,30 +213,8 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     __syncthreads();
     LSH_TRACE(0, 1);
 
-    // Eq. 3: the top-frequent words are members of every candidate list.  Frequent-word ids
-    // tend to be consecutive, i.e. many lanes of a wave set bits of the SAME bitmap word, and
-    // same-address LDS atomics serialise; so lanes that share a word first OR their bits
-    // together and one of them issues the atomic.
-    for (int i0 = 0; i0 < T; i0 += kCandThreads) {
-        const int i = i0 + tid;
-        const int32_t id = (i0 == 0) ? tf_first : ((i < T) ? topfreq[i] : -1);
-        const bool ok = id >= 0 && id < V;
-        const uint32_t word = ok ? (uint32_t)(id >> 5) : 0xFFFFFFFFu;
-        const uint32_t bit = ok ? (1u << (id & 31)) : 0u;
-        uint64_t todo = __ballot(ok);
-        bool grouped = true;
-        while (todo && grouped) {
-            const int leader = __ffsll((unsigned long long)todo) - 1;
-            const uint32_t w0 = wave_read_lane(word, leader);
-            const bool mine = ok && word == w0;
-            const uint64_t grp = __ballot(mine);
-            const uint32_t ored = wave_or(mine ? bit : 0u);
-            if (ln == leader) atomicOr(&bm[w0], ored);
-            todo &= ~grp;
-            grouped = __popcll(grp) > 1;  // scattered ids: stop grouping, plain atomics below
-        }
-        if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
-    }
+    // Eq. 3: the top-frequent words are members of every candidate list.
+    mark_id_list(bm, V, topfreq, T, tf_first);
     LSH_TRACE(0, 11);
 
     for (int row0 = 0; row0 < B; row0 += rows_per_chunk) {
@@ -311,45 +318,33 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
 
 }
 
-// One workgroup per sentence.  Requires W <= kCandThreads.
-__global__ void __launch_bounds__(kCandThreads)
-k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count) {
-    extern __shared__ uint32_t smem[];
-    const int s = blockIdx.x;
+// Compaction of a V-bit LDS bitmap into the ascending id list out[0..count) (Eq. 10's selection
+// made dense; the paper's Fig. 5 step).  Each wave owns a contiguous range of bitmap words (a
+// multiple of 64 of them); popcount + wave prefix sum give every lane the output offset of its
+// word's ids.  A sparse word is expanded by its own lane (neighbouring lanes write neighbouring
+// addresses).  Dense words -- the top-frequent ids usually fill whole words -- would make each
+// lane write a long private run, 128 bytes apart from its neighbour's; they are expanded two at
+// a time by 32 lanes each, one lane per bit, so that their stores are contiguous.
+// Called by all kCandThreads threads; wsum is LDS scratch of >= kCandWaves words.
+__device__ __forceinline__ void compact_bitmap(const uint32_t* bm, int nwords, uint32_t* wsum,
+                                               int32_t* __restrict__ out,
+                                               int32_t* __restrict__ count_out) {
     const int tid = threadIdx.x, wv = wave_id(), ln = lane_id();
-    const int V = a.V;
-    const int nwords = (V + 31) >> 5;
-    uint32_t* bm = smem;
-    uint32_t* wsum = smem + candidates_lds_words(a.V, a.d, a.P, a.K) - 64;
-    build_presence_bitmap(a, s, smem);
-
-    // Compaction (Eq. 10 with t = 1; the paper's Fig. 5 step): each wave owns a contiguous range
-    // of bitmap words (a multiple of 64 of them); popcount + wave prefix sum give every lane the
-    // output offset of its word's ids.  A sparse word is expanded by its own lane (neighbouring
-    // lanes write neighbouring addresses).  Dense words -- the top-frequent ids usually fill
-    // whole words -- would make each lane write a long private run, 128 bytes apart from its
-    // neighbour's; they are expanded two at a time by 32 lanes each, one lane per bit, so that
-    // their stores are contiguous.
     int per_wave = (nwords + kCandWaves - 1) / kCandWaves;
     per_wave = (per_wave + kWave - 1) / kWave * kWave;
     const int wbeg = wv * per_wave;
     const int wend = min(nwords, wbeg + per_wave);
     uint32_t cnt = 0;
     for (int i = wbeg + ln; i < wend; i += kWave) cnt += __popc(bm[i]);
-    LSH_TRACE(0, 7);
     cnt = wave_sum(cnt);
     if (ln == 0) wsum[wv] = cnt;
-    LSH_TRACE(0, 8);
     __syncthreads();
-    LSH_TRACE(0, 9);
     uint32_t running = 0, total = 0;
     for (int i = 0; i < kCandWaves; ++i) {
         const uint32_t x = wsum[i];
         if (i < wv) running += x;
         total += x;
     }
-    LSH_TRACE(0, 10);
-    int32_t* out = cand + (size_t)s * V;
     const int half = ln >> 5, hbit = ln & 31;
     for (int i0 = wbeg; i0 < wend; i0 += kWave) {
         const int i = i0 + ln;
@@ -385,8 +380,137 @@ k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count
         }
         running += wave_read_lane(incl, kWave - 1);
     }
-    if (tid == 0) count[s] = (int32_t)total;
+    if (tid == 0) *count_out = (int32_t)total;
+}
+
+// One workgroup per sentence.  Requires W <= kCandThreads.
+__global__ void __launch_bounds__(kCandThreads)
+k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count) {
+    extern __shared__ uint32_t smem[];
+    const int s = blockIdx.x;
+    const int nwords = (a.V + 31) >> 5;
+    uint32_t* wsum = smem + candidates_lds_words(a.V, a.d, a.P, a.K) - 64;
+    build_presence_bitmap(a, s, smem);
+    compact_bitmap(smem, nwords, wsum, cand + (size_t)s * a.V, count + s);
     LSH_TRACE(0, 6);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Threshold t > 1 (Eq. 9-10 in full): the hit matrix L[i, j] counts in how many bands row i and
+// word j collide, and a word is a candidate iff some row reaches t.  One workgroup per hidden
+// row keeps that row of L in LDS as 16-bit counters (the paper keeps L in global memory), walks
+// the row's W spans with one wave per span (Algorithm 1; spans are long here -- ~V / 2^(u bits)
+// words -- so a wave per span is load-balanced enough and needs no search), and leaves the
+// row's thresholded bits as a V-bit bitmap in global memory.  A second kernel ORs the sentence's
+// row bitmaps with the top-frequent words (Eq. 3) and compacts.
+// ---------------------------------------------------------------------------------------------
+
+// LDS words of k_hit_rows: counters (2 per word), the hidden row, codes (2 per word), spans.
+__host__ __device__ inline size_t hit_rows_lds_words(int V, int d, int P, int W) {
+    return ((size_t)V + 1) / 2 + (size_t)((d + 3) & ~3) + ((size_t)P + 1) / 2 + 2 * (size_t)W + 8;
+}
+
+// grid = S*B workgroups (one per hidden row).  Requires W < 65536 (16-bit counters).
+__global__ void __launch_bounds__(kCandThreads)
+k_hit_rows(CandArgs a, int t, uint32_t* __restrict__ row_bitmaps /*[S*B, nwords]*/) {
+    extern __shared__ uint32_t smem[];
+    const int V = a.V, d = a.d, P = a.P, K = a.K, W = a.W, bits = a.bits;
+    const int u = P / W;
+    const int nwords = (V + 31) >> 5;
+    uint32_t* cnt32 = smem;                                            // V 16-bit counters
+    float* rowv = reinterpret_cast<float*>(cnt32 + (V + 1) / 2);       // the hidden row
+    uint16_t* codes = reinterpret_cast<uint16_t*>(rowv + ((d + 3) & ~3));
+    uint32_t* sp_start = reinterpret_cast<uint32_t*>(codes) + (P + 1) / 2;
+    uint32_t* sp_len = sp_start + W;
+    const int r = blockIdx.x;
+    const int tid = threadIdx.x, wv = wave_id(), ln = lane_id();
+    const float* hrow = a.H + (size_t)r * d;
+
+    for (int i = tid; i < d; i += kCandThreads) rowv[i] = hrow[i];
+    for (int i = tid; i < (V + 1) / 2; i += kCandThreads) cnt32[i] = 0u;
+    __syncthreads();
+
+    // Eq. 4-5: one windowed argmax per permutation (strict '>' in window order)
+    for (int p = tid; p < P; p += kCandThreads) {
+        const int32_t* pm = a.perms + (size_t)p * K;
+        int best = 0;
+        float bv = -INFINITY;
+        bool first = true;
+        for (int k0 = 0; k0 < K; k0 += 8) {  // 8 window entries per round of loads
+            int idx[8];
+            float v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) idx[j] = pm[min(k0 + j, K - 1)];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = rowv[idx[j]];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                if (k0 + j < K && (first || v[j] > bv)) { bv = v[j]; best = k0 + j; }
+                first = false;
+            }
+        }
+        codes[p] = (uint16_t)best;
+    }
+    __syncthreads();
+    // Eq. 6-8 and Algorithm 1 lines 1-2: one band per thread
+    for (int w = tid; w < W; w += kCandThreads) {
+        int32_t code = 0;
+        for (int q = 0; q < u; ++q) code = (code << bits) | codes[w * u + q];
+        uint32_t start, len;
+        cuckoo_find(a.slots, a.bands[w], code, &start, &len);
+        sp_start[w] = start;
+        sp_len[w] = len;
+    }
+    __syncthreads();
+    // Algorithm 1 lines 3-6: L[i, word] += 1, one wave per span, two spans in flight
+    for (int w0 = wv; w0 < W; w0 += 2 * kCandWaves) {
+        const int w1 = w0 + kCandWaves;
+        const uint32_t s0 = sp_start[w0], l0 = sp_len[w0];
+        const uint32_t s1 = (w1 < W) ? sp_start[w1] : 0u, l1 = (w1 < W) ? sp_len[w1] : 0u;
+        const int32_t* span0 = a.words + (size_t)w0 * V + s0;
+        const int32_t* span1 = a.words + (size_t)min(w1, W - 1) * V + s1;
+        for (uint32_t i = ln; i < max(l0, l1); i += kWave) {
+            const int32_t id0 = (i < l0) ? span0[i] : -1;
+            const int32_t id1 = (i < l1) ? span1[i] : -1;
+            if (id0 >= 0) atomicAdd(&cnt32[id0 >> 1], 1u << (16 * (id0 & 1)));
+            if (id1 >= 0) atomicAdd(&cnt32[id1 >> 1], 1u << (16 * (id1 & 1)));
+        }
+    }
+    __syncthreads();
+    // Eq. 10 for this row: bit j = (L[i, j] >= t); lane l of a wave looks at counter base + l
+    const uint16_t* cnt16 = reinterpret_cast<const uint16_t*>(cnt32);
+    uint32_t* out = row_bitmaps + (size_t)r * nwords;
+    const int nchunks = (V + kWave - 1) / kWave;  // 64 words of the vocabulary = 2 bitmap words
+    for (int c = wv; c < nchunks; c += kCandWaves) {
+        const int j = c * kWave + ln;
+        const bool hit = j < V && (int)cnt16[j] >= t;
+        const uint64_t bal = __ballot(hit);
+        if (ln == 0) out[2 * c] = (uint32_t)bal;
+        if (ln == 32 && 2 * c + 1 < nwords) out[2 * c + 1] = (uint32_t)(bal >> 32);
+    }
+}
+
+// grid = S workgroups: OR of the sentence's B row bitmaps and the top-frequent words, compacted.
+__global__ void __launch_bounds__(kCandThreads)
+k_union_compact(const uint32_t* __restrict__ row_bitmaps, int B, int V,
+                const int32_t* __restrict__ topfreq, int T, int32_t* __restrict__ cand,
+                int32_t* __restrict__ count) {
+    extern __shared__ uint32_t smem[];  // nwords + 64 words
+    const int s = blockIdx.x, tid = threadIdx.x;
+    const int nwords = (V + 31) >> 5;
+    uint32_t* bm = smem;
+    uint32_t* wsum = smem + nwords;
+    const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
+    const uint32_t* rb = row_bitmaps + (size_t)s * B * nwords;
+    for (int i = tid; i < nwords; i += kCandThreads) {
+        uint32_t x = 0;
+        for (int b = 0; b < B; ++b) x |= rb[(size_t)b * nwords + i];
+        bm[i] = x;
+    }
+    __syncthreads();
+    mark_id_list(bm, V, topfreq, T, tf_first);
+    __syncthreads();
+    compact_bitmap(bm, nwords, wsum, cand + (size_t)s * V, count + s);
 }
 
 }  // namespace lshbeam

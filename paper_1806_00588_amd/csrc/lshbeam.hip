@@ -41,7 +41,7 @@ struct Profiler {
     bool on = false;
     int max_steps = 0;
     std::vector<hipEvent_t> ev[LSH_NUM_KERNELS];  // start/stop pairs
-    int used[LSH_NUM_KERNELS] = {0, 0, 0};
+    int used[LSH_NUM_KERNELS] = {0, 0, 0, 0};
 };
 
 }  // namespace
@@ -60,6 +60,7 @@ struct lsh_tables {
     std::vector<Slot> slots_host;
     int wg_candidates_lds = 0;
     int wg_fused_lds = 0;
+    int wg_hit_rows_lds = 0;
     Profiler prof;
 };
 
@@ -155,6 +156,7 @@ struct Workspace {
     int32_t* count;      // [S]
     float* logits;       // [R, cpitch]
     float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max))
+    uint32_t* row_bitmaps;  // [R, ceil(V/32)]  thresholded hit rows (t > 1 only)
     float* lse;          // [R]
     int64_t ppitch;
     int64_t cpitch;
@@ -173,6 +175,7 @@ Workspace carve(const lsh_tables* t, const lsh_step_params* sp, void* base) {
     w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
     w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(float2));
     w.lse = (float*)take(R * sizeof(float));
+    w.row_bitmaps = (uint32_t*)take(sp->threshold > 1 && !sp->full_vocab ? R * ((V + 31) / 32) * sizeof(uint32_t) : 0);
     w.bytes = off;
     return w;
 }
@@ -193,7 +196,8 @@ int env_int(const char* name, int dflt) {
 // measurements), never the hard limits.
 bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
     const int MT = (sp->B + kTileM - 1) / kTileM;
-    const bool possible = !sp->full_vocab && (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
+    const bool possible = !sp->full_vocab && sp->threshold == 1 &&
+                          (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
     const bool wanted = env_int("LSHBEAM_FUSED", sp->S * MT <= 8 ? 1 : 0) != 0;
     return possible && wanted;
 }
@@ -295,6 +299,7 @@ const char* lsh_kernel_name(int32_t which) {
         case 0: return "k_candidates";
         case 1: return "k_logits";
         case 2: return "k_select";
+        case 3: return "k_hit_rows";
     }
     return "";
 }
@@ -397,6 +402,12 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (t->wg_candidates_lds > 48 * 1024)
         HIP_TRY(hipFuncSetAttribute((const void*)k_candidates,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_candidates_lds));
+    t->wg_hit_rows_lds = (int)(hit_rows_lds_words(t->V, t->d, t->P, t->W) * sizeof(uint32_t));
+    if ((size_t)t->wg_hit_rows_lds <= kMaxDynLds)
+        HIP_TRY(hipFuncSetAttribute((const void*)k_hit_rows, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    t->wg_hit_rows_lds));
+    HIP_TRY(hipFuncSetAttribute((const void*)k_union_compact, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)(((t->V + 31) / 32 + 64) * sizeof(uint32_t))));
     t->wg_fused_lds = (int)(fused_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
     if ((size_t)t->wg_fused_lds <= kMaxDynLds) {
         const void* fused[4] = {(const void*)k_cand_logits<float, true>, (const void*)k_cand_logits<float, false>,
@@ -424,7 +435,10 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
         return LSH_ERR_INVALID_ARG;
     if (!step_params_ok(tc, sp)) return LSH_ERR_INVALID_ARG;
     if (!sp->full_vocab && sp->T > 0 && !topfreq_dev) return LSH_ERR_INVALID_ARG;
-    if (!sp->full_vocab && sp->threshold != 1) return LSH_ERR_UNSUPPORTED;
+    if (!sp->full_vocab && sp->threshold < 1) return LSH_ERR_INVALID_ARG;
+    if (!sp->full_vocab && sp->threshold > 1 &&
+        ((size_t)tc->wg_hit_rows_lds > kMaxDynLds || tc->W >= 65536))
+        return LSH_ERR_UNSUPPORTED;
     if ((uintptr_t)workspace_dev % kAlign) return LSH_ERR_INVALID_ARG;
     lsh_tables* t = const_cast<lsh_tables*>(tc);  // only the profiler state is touched
     const Workspace w = carve(t, sp, workspace_dev);
@@ -455,7 +469,16 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
         cand = w.cand;
         count = w.count;
     } else {
-        if (!sp->full_vocab) {
+        if (!sp->full_vocab && sp->threshold > 1) {
+            // Eq. 9-10 with t > 1: per-row hit counts, then union + top-frequent + compaction
+            launch(t, 3, k_hit_rows, dim3(sp->S * sp->B), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds,
+                   st, ca, (int)sp->threshold, w.row_bitmaps);
+            launch(t, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
+                   (size_t)(((t->V + 31) / 32 + 64) * sizeof(uint32_t)), st,
+                   (const uint32_t*)w.row_bitmaps, sp->B, t->V, topfreq_dev, sp->T, w.cand, w.count);
+            cand = w.cand;
+            count = w.count;
+        } else if (!sp->full_vocab) {
             launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads), (size_t)t->wg_candidates_lds, st,
                    ca, w.cand, w.count);
             cand = w.cand;

@@ -49,15 +49,15 @@ class GpuCase:
                    workloads.make_topfreq(cfg), cfg.W, seed)
 
     def step(self, H: np.ndarray, beam_scores: np.ndarray, S: int, B: int, full_vocab=False,
-             T=None, topfreq_dev=None):
+             T=None, topfreq_dev=None, threshold=1):
         """One lsh_decode_step; returns (beam, word, score) numpy [S,B] plus (sp, workspace)."""
         from paper_1806_00588_amd import binding
         torch = self.torch
         T = self.topfreq.size if T is None else T
-        sp = binding.step_params(S, B, T, 1, full_vocab)
+        sp = binding.step_params(S, B, T, threshold, full_vocab)
         nbytes = self.lsh.step_workspace_bytes(self.tables, sp)
         assert nbytes > 0
-        key = (S, B, bool(full_vocab))
+        key = (S, B, bool(full_vocab), threshold > 1)
         if key not in self._ws or self._ws[key].numel() < nbytes:
             self._ws[key] = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         ws = self._ws[key]
@@ -71,10 +71,10 @@ class GpuCase:
         torch.cuda.synchronize()
         return ob.cpu().numpy(), ow.cpu().numpy(), osc.cpu().numpy(), sp, ws
 
-    def oracle_sentence(self, Hs, bs, B, full_vocab=False, topfreq=None):
+    def oracle_sentence(self, Hs, bs, B, full_vocab=False, topfreq=None, threshold=1):
         """Oracle for one sentence: Ref(cand, lp fp64 [B,C], logits fp64 [B,C], beam, word, score)."""
         tf = self.topfreq if topfreq is None else topfreq
-        cand = np.arange(self.V, dtype=np.int32) if full_vocab else self.index.candidates(Hs, tf)
+        cand = np.arange(self.V, dtype=np.int32) if full_vocab else self.index.candidates(Hs, tf, threshold)
         lp, lg = self.index.logprobs(Hs, cand, want_logits=True)
         ob, ow, osc = oracle.topb(np.asarray(bs, dtype=np.float64), lp, cand, B)
         return Ref(cand, lp, lg, ob, ow, osc)

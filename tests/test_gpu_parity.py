@@ -94,12 +94,12 @@ def test_cuckoo_with_wide_band_codes():
 # decode step
 # ---------------------------------------------------------------------------------------------
 
-def run_and_check(cfg, gc, H, bs, S, B, full_vocab=False, check_lp=True):
-    gb, gw, gs, sp, ws = gc.step(H, bs, S, B, full_vocab=full_vocab)
+def run_and_check(cfg, gc, H, bs, S, B, full_vocab=False, check_lp=True, threshold=1):
+    gb, gw, gs, sp, ws = gc.step(H, bs, S, B, full_vocab=full_vocab, threshold=threshold)
     swaps = 0
     for s in range(S):
         Hs, bss = H[s * B:(s + 1) * B], bs[s * B:(s + 1) * B]
-        ref = gc.oracle_sentence(Hs, bss, B, full_vocab=full_vocab)
+        ref = gc.oracle_sentence(Hs, bss, B, full_vocab=full_vocab, threshold=threshold)
         if not full_vocab:
             assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), ref.cand)   # bit-exact list
         if check_lp:
@@ -155,6 +155,44 @@ def test_paper_shape_full_vocab():
     H = hidden(cfg, gc, 1)
     run_and_check(cfg, gc, H[0], np.linspace(-3, 0, cfg.R).astype(np.float32), 1, cfg.B,
                   full_vocab=True)
+
+
+def test_tiny_hit_thresholds():
+    """Eq. 10 with t > 1: a word needs t colliding bands with one row; t > W leaves V_T only."""
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    rng = np.random.default_rng(5)
+    sizes = {}
+    for t in [2, 3, 4, 5]:
+        for S, B in [(1, 4), (3, 7), (2, 20)]:
+            bs = rng.standard_normal(S * B).astype(np.float32)
+            run_and_check(cfg, gc, H[:S * B], bs, S, B, threshold=t)
+        sizes[t] = len(gc.index.candidates(H[:4], gc.topfreq, t))
+    assert sizes[2] >= sizes[3] >= sizes[4] >= sizes[5]
+    assert sizes[5] == len(np.unique(gc.topfreq))          # cfg.W == 4 bands: nothing reaches 5
+    # without top-frequent words and out of reach: an empty list, all outputs padded
+    gb, gw, gs, sp, ws = gc.step(H[:4], np.zeros(4, np.float32), 1, 4, T=0, threshold=5)
+    assert len(gc.tables.debug_candidates(ws, sp, 0)) == 0
+    assert np.all(gb == -1) and np.all(gw == -1) and np.all(np.isneginf(gs))
+
+
+def test_paper_banding_with_hit_threshold():
+    """{K, u, W} = {8, 3, 500} on the Table 1 shape: thousands of hits per row, t selects."""
+    cfg, gc = case("paperscale")
+    H = hidden(cfg, gc, 3)
+    bs = np.zeros(cfg.R, dtype=np.float32)
+    for step in range(3):
+        run_and_check(cfg, gc, H[step], bs, cfg.S, cfg.B, threshold=cfg.threshold)
+        bs = gc.oracle_sentence(H[step], bs, cfg.B, threshold=cfg.threshold).score.astype(np.float32)
+    n5 = len(gc.index.candidates(H[0], gc.topfreq, cfg.threshold))
+    assert cfg.T < n5 < cfg.V // 4
+    run_and_check(cfg, gc, H[1], bs, cfg.S, cfg.B, threshold=2, check_lp=False)
+    run_and_check(cfg, gc, H[2], bs, cfg.S, cfg.B, threshold=40)
+    # the same tables with t = 1 (500 probes per row through the one-kernel candidate path)
+    run_and_check(cfg, gc, H[0], bs, cfg.S, cfg.B, check_lp=False)
+    # several sentences
+    H3 = np.concatenate([H[0], H[1], H[2]])[:30]
+    run_and_check(cfg, gc, H3, np.zeros(30, np.float32), 3, 10, threshold=cfg.threshold, check_lp=False)
 
 
 def test_batched_shape():
@@ -324,7 +362,11 @@ def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
     with pytest.raises(lsh.LshBeamError) as e:
         lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, binding.step_params(1, 4, 50, threshold=2),
                         ws, ob, ow, osc)
-    assert e.value.status == 2                                  # unsupported threshold
+    assert e.value.status == 6                                  # t > 1 needs a larger workspace
+    with pytest.raises(lsh.LshBeamError) as e:
+        lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, binding.step_params(1, 4, 50, threshold=0),
+                        ws, ob, ow, osc)
+    assert e.value.status == 1                                  # t < 1
     with pytest.raises(lsh.LshBeamError) as e:
         lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, sp, ws[:1024], ob, ow, osc)
     assert e.value.status == 6                                  # workspace too small
@@ -335,6 +377,17 @@ def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
     assert torch.all(ob == 42) and torch.all(ow == 42) and torch.all(osc == 42.0)
     assert lsh.step_workspace_bytes(gc.tables, binding.step_params(0, 4, 0)) == 0
     assert lsh.step_workspace_bytes(gc.tables, binding.step_params(1, 257, 0)) == 0
+    # t > 1 keeps V 16-bit hit counters in LDS: 200000 words do not fit
+    _, big = case("largevocab")
+    Hb = torch.zeros(10, 1024, device="cuda")
+    spb = binding.step_params(1, 10, 0, threshold=2)
+    wsb = torch.empty(lsh.step_workspace_bytes(big.tables, spb), dtype=torch.uint8, device="cuda")
+    with pytest.raises(lsh.LshBeamError) as e:
+        lsh.decode_step(big.tables, Hb, torch.zeros(10, device="cuda"), None, spb, wsb,
+                        torch.zeros(1, 10, dtype=torch.int32, device="cuda"),
+                        torch.zeros(1, 10, dtype=torch.int32, device="cuda"),
+                        torch.zeros(1, 10, device="cuda"))
+    assert e.value.status == 2
     # build-time validation
     for K, W in [(1, 4), (8, 3), (8, 0), (8, 1)]:          # (8, 1): u * bits = 48 > 30
         with pytest.raises(lsh.LshBeamError):

@@ -51,4 +51,6 @@ def test_config_table_matches_the_benchmark_definitions():
     assert (c["widebeam"].V, c["widebeam"].B, c["widebeam"].S, c["widebeam"].K) == (100000, 50, 4, 16)
     assert (c["largevocab"].d, c["largevocab"].V, c["largevocab"].R) == (1024, 200000, 640)
     assert c["largevocab"].e_dtype == workloads.BF16
-    assert all(v.u == 4 for v in c.values())
+    assert all(v.u == 4 and v.threshold == 1 for n, v in c.items() if n != "paperscale")
+    ps = c["paperscale"]                      # the paper's {K, u, W} = {8, 3, 500} with a hit threshold
+    assert (ps.d, ps.V, ps.B, ps.K, ps.u, ps.W, ps.threshold) == (1000, 40000, 12, 8, 3, 500, 5)

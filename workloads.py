@@ -2,7 +2,7 @@
 
 This module only *draws numbers*: embedding matrices, permutation windows, top-frequent word
 lists and per-step hidden states, with the shapes and distributions of the five benchmark
-configurations.  It holds none of the method's arithmetic (no hashing, no tables, no softmax),
+configurations (plus the paper-scale banding).  It holds none of the method's arithmetic (no hashing, no tables, no softmax),
 so both the CPU oracle's tests and the HIP path's tests can consume the same bytes without
 sharing any code of the method itself.
 
@@ -44,6 +44,7 @@ class Config:
     e_dtype: int = F32
     uniform_row_frac: float = 0.0   # fraction of H rows drawn iid uniform (low-overlap buckets)
     zipf_s: float = 1.1
+    threshold: int = 1              # t of Eq. 10
 
     @property
     def R(self) -> int:
@@ -54,12 +55,14 @@ class Config:
         return self.P // self.W
 
 
-def _cfg(name, d, V, S, B, K, P, W, T, nc, steps, h_scale, *, tiny=False, e_dtype=F32, uni=0.0):
+def _cfg(name, d, V, S, B, K, P, W, T, nc, steps, h_scale, *, tiny=False, e_dtype=F32, uni=0.0,
+         t=1):
     if tiny:
-        return Config(name, d, V, S, B, K, P, W, T, nc, 1.0, 0.3, 1.0, 0.2, steps, e_dtype, uni)
+        return Config(name, d, V, S, B, K, P, W, T, nc, 1.0, 0.3, 1.0, 0.2, steps, e_dtype, uni,
+                      threshold=t)
     sd = 1.0 / np.sqrt(d)
     return Config(name, d, V, S, B, K, P, W, T, nc, sd, 0.3 * sd, h_scale, 0.3 * sd, steps,
-                  e_dtype, uni)
+                  e_dtype, uni, threshold=t)
 
 
 CONFIGS = {
@@ -69,6 +72,8 @@ CONFIGS = {
     "widebeam": _cfg("widebeam", 1000, 100000, 4, 50, 16, 48, 12, 2000, 2000, 40, 0.7),
     "largevocab": _cfg("largevocab", 1024, 200000, 64, 10, 8, 64, 16, 2000, 4000, 30, 0.8,
                        e_dtype=BF16, uni=0.10),
+    # the paper's own banding {K, u, W} = {8, 3, 500} (Table 1's setting) with a hit threshold
+    "paperscale": _cfg("paperscale", 1000, 40000, 1, 12, 8, 1500, 500, 1000, 1000, 20, 0.8, t=5),
 }
 
 _STREAMS = {"centres": 1, "noise": 2, "perms": 3, "targets": 4, "hnoise": 5, "uniform": 6,
