@@ -405,42 +405,63 @@ k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count
 // row bitmaps with the top-frequent words (Eq. 3) and compacts.
 // ---------------------------------------------------------------------------------------------
 
-// LDS words of k_hit_rows: counters (2 per word), the hidden row, codes (2 per word), spans.
-__host__ __device__ inline size_t hit_rows_lds_words(int V, int d, int P, int W) {
-    return ((size_t)V + 1) / 2 + (size_t)((d + 3) & ~3) + ((size_t)P + 1) / 2 + 2 * (size_t)W + 8;
+// LDS words of k_hit_rows without its load list: counters (2 per word, in blocks of 64 ids), the
+// hidden row, codes (2 per word), scan scratch, three per-span arrays.
+__host__ __device__ inline size_t hit_rows_fixed_lds_words(int V, int d, int P) {
+    return ((size_t)V + 63) / 64 * 32 + (size_t)((d + 3) & ~3) + ((size_t)P + 1) / 2 + 32 +
+           3 * (size_t)kCandThreads + 64;
 }
+constexpr int kHitListMin = 2048, kHitListMax = 16384;  // load-list entries per pass
 
-// grid = S*B workgroups (one per hidden row).  Requires W < 65536 (16-bit counters).
+// grid = S*B workgroups (one per hidden row).  Requires W <= kCandThreads (one span per thread),
+// W * V < 2^30 (a 16-byte group index and a 4-bit mask share a word) and list_cap >= kHitListMin.
 __global__ void __launch_bounds__(kCandThreads)
-k_hit_rows(CandArgs a, int t, uint32_t* __restrict__ row_bitmaps /*[S*B, nwords]*/) {
+k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /*[S*B, nwords]*/) {
     extern __shared__ uint32_t smem[];
     const int V = a.V, d = a.d, P = a.P, K = a.K, W = a.W, bits = a.bits;
     const int u = P / W;
     const int nwords = (V + 31) >> 5;
     uint32_t* cnt32 = smem;                                            // V 16-bit counters
-    float* rowv = reinterpret_cast<float*>(cnt32 + (V + 1) / 2);       // the hidden row
+    const int ncnt = (V + 63) / 64 * 32;                               // counter words
+    float* rowv = reinterpret_cast<float*>(cnt32 + ncnt);              // the hidden row
     uint16_t* codes = reinterpret_cast<uint16_t*>(rowv + ((d + 3) & ~3));
-    uint32_t* sp_start = reinterpret_cast<uint32_t*>(codes) + (P + 1) / 2;
-    uint32_t* sp_len = sp_start + W;
+    uint32_t* wsum = reinterpret_cast<uint32_t*>(codes) + (P + 1) / 2;  // scan scratch
+    uint32_t* sp_pref = wsum + 32;                 // first list entry of each span (+ the total)
+    uint32_t* sp_where = sp_pref + kCandThreads + 64;  // first 16-byte group << 2 | misalignment
+    uint32_t* sp_len = sp_where + kCandThreads;
+    uint32_t* list = sp_len + kCandThreads;        // load list [list_cap]
     const int r = blockIdx.x;
     const int tid = threadIdx.x, wv = wave_id(), ln = lane_id();
     const float* hrow = a.H + (size_t)r * d;
 
+    LSH_TRACE(3, 0);
+    // this thread's band descriptor is needed only after the codes: request it now
+    const BandMeta my_meta = a.bands[min(tid, W - 1)];
     for (int i = tid; i < d; i += kCandThreads) rowv[i] = hrow[i];
-    for (int i = tid; i < (V + 1) / 2; i += kCandThreads) cnt32[i] = 0u;
+    for (int i = tid; i < ncnt; i += kCandThreads) cnt32[i] = 0u;
     __syncthreads();
+    LSH_TRACE(3, 1);
 
-    // Eq. 4-5: one windowed argmax per permutation (strict '>' in window order)
+    // Eq. 4-5: one windowed argmax per permutation (strict '>' in window order, so the lowest k
+    // wins a tie); window entries are fetched eight at a time, as 16-byte loads when K allows
+    const bool pvec = (K & 3) == 0 && ((uintptr_t)a.perms & 15) == 0;
     for (int p = tid; p < P; p += kCandThreads) {
         const int32_t* pm = a.perms + (size_t)p * K;
         int best = 0;
         float bv = -INFINITY;
         bool first = true;
-        for (int k0 = 0; k0 < K; k0 += 8) {  // 8 window entries per round of loads
+        for (int k0 = 0; k0 < K; k0 += 8) {
             int idx[8];
             float v[8];
+            if (pvec) {
+                const int4 q0 = *reinterpret_cast<const int4*>(pm + k0);
+                const int4 q1 = *reinterpret_cast<const int4*>(pm + min(k0 + 4, K - 4));
+                idx[0] = q0.x; idx[1] = q0.y; idx[2] = q0.z; idx[3] = q0.w;
+                idx[4] = q1.x; idx[5] = q1.y; idx[6] = q1.z; idx[7] = q1.w;
+            } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) idx[j] = pm[min(k0 + j, K - 1)];
+                for (int j = 0; j < 8; ++j) idx[j] = pm[min(k0 + j, K - 1)];
+            }
 #pragma unroll
             for (int j = 0; j < 8; ++j) v[j] = rowv[idx[j]];
 #pragma unroll
@@ -452,41 +473,140 @@ k_hit_rows(CandArgs a, int t, uint32_t* __restrict__ row_bitmaps /*[S*B, nwords]
         codes[p] = (uint16_t)best;
     }
     __syncthreads();
-    // Eq. 6-8 and Algorithm 1 lines 1-2: one band per thread
-    for (int w = tid; w < W; w += kCandThreads) {
+    LSH_TRACE(3, 2);
+
+    // Eq. 6-8 and Algorithm 1 lines 1-2: thread w packs band w's code and probes its table.
+    // Span ids are read in aligned groups of four (one 16-byte load): the span covers
+    // `ngroups` of them starting at group `grp0` of the flat word array, its first id sitting
+    // at position `mis` of the first group.
+    uint32_t grp0 = 0, mis = 0, len = 0, ngroups = 0;
+    if (tid < W) {
         int32_t code = 0;
-        for (int q = 0; q < u; ++q) code = (code << bits) | codes[w * u + q];
-        uint32_t start, len;
-        cuckoo_find(a.slots, a.bands[w], code, &start, &len);
-        sp_start[w] = start;
-        sp_len[w] = len;
-    }
-    __syncthreads();
-    // Algorithm 1 lines 3-6: L[i, word] += 1, one wave per span, two spans in flight
-    for (int w0 = wv; w0 < W; w0 += 2 * kCandWaves) {
-        const int w1 = w0 + kCandWaves;
-        const uint32_t s0 = sp_start[w0], l0 = sp_len[w0];
-        const uint32_t s1 = (w1 < W) ? sp_start[w1] : 0u, l1 = (w1 < W) ? sp_len[w1] : 0u;
-        const int32_t* span0 = a.words + (size_t)w0 * V + s0;
-        const int32_t* span1 = a.words + (size_t)min(w1, W - 1) * V + s1;
-        for (uint32_t i = ln; i < max(l0, l1); i += kWave) {
-            const int32_t id0 = (i < l0) ? span0[i] : -1;
-            const int32_t id1 = (i < l1) ? span1[i] : -1;
-            if (id0 >= 0) atomicAdd(&cnt32[id0 >> 1], 1u << (16 * (id0 & 1)));
-            if (id1 >= 0) atomicAdd(&cnt32[id1 >> 1], 1u << (16 * (id1 & 1)));
+        for (int q = 0; q < u; ++q) code = (code << bits) | codes[tid * u + q];
+        uint32_t start;
+        cuckoo_find(a.slots, my_meta, code, &start, &len);
+        if (len) {
+            const size_t g0 = (size_t)tid * V + start;
+            grp0 = (uint32_t)(g0 >> 2);
+            mis = (uint32_t)(g0 & 3);
+            ngroups = (mis + len + 3) >> 2;
         }
     }
+    uint32_t total;
+    const uint32_t first_entry = block_incl_scan(ngroups, wsum, &total) - ngroups;
+    sp_pref[tid] = (tid < W) ? first_entry : total;
+    if (tid == 0) sp_pref[kCandThreads] = total;
+    sp_where[tid] = (grp0 << 2) | mis;
+    sp_len[tid] = len;
     __syncthreads();
-    // Eq. 10 for this row: bit j = (L[i, j] >= t); lane l of a wave looks at counter base + l
-    const uint16_t* cnt16 = reinterpret_cast<const uint16_t*>(cnt32);
+    LSH_TRACE(3, 3);
+
+    // Algorithm 1 lines 3-6: L[i, word] += 1 for every id of every hit span.  Spans have unequal
+    // lengths (the source of the paper's divergence problem): they are flattened into a list of
+    // 16-byte loads in LDS -- entry = group index << 4 | which of its four ids belong to the
+    // span.  Every thread writes an equal, contiguous share of the list (it finds the span of
+    // its first entry by search and walks on from there), and the workgroup then consumes the
+    // list interleaved, kHitInFlight loads per thread in flight.  Lists longer than list_cap
+    // are handled in passes.
+    const int4* words4 = reinterpret_cast<const int4*>(a.words);
+    constexpr int kHitInFlight = 8;
+    // Counter of word id: 64 consecutive ids share 32 LDS words, id & 31 picks the word and bit 5
+    // of the id its half, so that the thresholding pass below gets whole bitmap words from a
+    // ballot over the low halves and one over the high halves.
+    auto bump = [&](int32_t id, uint32_t ok) {
+        if (ok) atomicAdd(&cnt32[((id >> 6) << 5) | (id & 31)], (id & 32) ? 0x10000u : 1u);
+    };
+    for (uint32_t pass0 = 0; pass0 < total; pass0 += (uint32_t)list_cap) {
+        const uint32_t pass1 = min(total, pass0 + (uint32_t)list_cap);
+        // an odd share keeps the threads' writes on different LDS banks
+        const uint32_t share = ((pass1 - pass0 + kCandThreads - 1) / kCandThreads) | 1u;
+        const uint32_t f_lo = pass0 + (uint32_t)tid * share;
+        const uint32_t f_hi = min(pass1, f_lo + share);
+        if (f_lo < f_hi) {
+            int w = last_not_above(sp_pref, f_lo);  // the non-empty span that holds entry f_lo
+            uint32_t base = sp_pref[w], ng = sp_pref[w + 1] - base;
+            uint32_t where = sp_where[w], slen = sp_len[w];
+            uint32_t k = f_lo - base;
+            for (uint32_t f = f_lo; f < f_hi; ++f) {
+                while (k >= ng) {  // next non-empty span (there is one: f < total)
+                    ++w;
+                    base = sp_pref[w];
+                    ng = sp_pref[w + 1] - base;
+                    where = sp_where[w];
+                    slen = sp_len[w];
+                    k = 0;
+                }
+                const int m = (int)(where & 3u);
+                const int lo = max(m - (int)(4 * k), 0);
+                const int hi = min(m + (int)slen - (int)(4 * k), 4);
+                const uint32_t mask = ((1u << hi) - 1u) & ~((1u << lo) - 1u);
+                list[f - pass0] = (((where >> 2) + k) << 4) | mask;
+                ++k;
+            }
+        }
+        __syncthreads();
+        LSH_TRACE(3, 7);
+        const int n = (int)(pass1 - pass0);
+        for (int f0 = tid; f0 < n; f0 += kHitInFlight * kCandThreads) {
+            uint32_t e[kHitInFlight];
+            int4 x[kHitInFlight];
+#pragma unroll
+            for (int j = 0; j < kHitInFlight; ++j) {
+                const int f = f0 + j * kCandThreads;
+                e[j] = (f < n) ? list[f] : 0u;  // entry 0: group 0, nothing valid
+            }
+#pragma unroll
+            for (int j = 0; j < kHitInFlight; ++j) x[j] = words4[e[j] >> 4];
+#pragma unroll
+            for (int j = 0; j < kHitInFlight; ++j) {
+                bump(x[j].x, e[j] & 1u); bump(x[j].y, e[j] & 2u);
+                bump(x[j].z, e[j] & 4u); bump(x[j].w, e[j] & 8u);
+            }
+        }
+        LSH_TRACE(3, 4);
+        __syncthreads();
+    }
+    LSH_TRACE(3, 5);
+    // Eq. 10 for this row: bit j = (L[i, j] >= t).  Lane l of a wave reads counter word
+    // 64 * c + l: its low half belongs to id 128 * c + 64 * (l / 32) + l % 32, its high half to
+    // that id + 32, so the two ballots are four consecutive bitmap words (in the order
+    // lo[31:0], hi[31:0], lo[63:32], hi[63:32]); lanes 0..3 store them.
     uint32_t* out = row_bitmaps + (size_t)r * nwords;
-    const int nchunks = (V + kWave - 1) / kWave;  // 64 words of the vocabulary = 2 bitmap words
-    for (int c = wv; c < nchunks; c += kCandWaves) {
-        const int j = c * kWave + ln;
-        const bool hit = j < V && (int)cnt16[j] >= t;
-        const uint64_t bal = __ballot(hit);
-        if (ln == 0) out[2 * c] = (uint32_t)bal;
-        if (ln == 32 && 2 * c + 1 < nwords) out[2 * c + 1] = (uint32_t)(bal >> 32);
+    const int nchunks = (ncnt + kWave - 1) / kWave;   // counters of ids beyond V stay zero
+    for (int c0 = wv; c0 < nchunks; c0 += 4 * kCandWaves) {  // four LDS reads in flight
+        uint32_t x[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = (c0 + q * kCandWaves) * kWave + ln;
+            x[q] = (i < ncnt) ? cnt32[i] : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int c = c0 + q * kCandWaves;
+            const uint64_t lo = __ballot((int)(x[q] & 0xFFFFu) >= t);
+            const uint64_t hi = __ballot((int)(x[q] >> 16) >= t);
+            const uint32_t mine = (ln == 0) ? (uint32_t)lo : (ln == 1) ? (uint32_t)hi
+                                : (ln == 2) ? (uint32_t)(lo >> 32) : (uint32_t)(hi >> 32);
+            if (ln < 4 && 4 * c + ln < nwords) out[4 * c + ln] = mine;
+        }
+    }
+    LSH_TRACE(3, 6);
+}
+
+// OR of B row bitmaps of nwords words each (rows nwords apart) into the LDS bitmap bm; called by
+// all kCandThreads threads, no barrier inside.
+__device__ __forceinline__ void union_row_bitmaps(const uint32_t* __restrict__ rb, int B, int nwords,
+                                                  uint32_t* bm) {
+    for (int i = threadIdx.x; i < nwords; i += kCandThreads) {
+        uint32_t x = 0;
+        int b = 0;
+        for (; b + 4 <= B; b += 4) {  // four independent loads in flight
+            const uint32_t x0 = rb[(size_t)b * nwords + i], x1 = rb[(size_t)(b + 1) * nwords + i];
+            const uint32_t x2 = rb[(size_t)(b + 2) * nwords + i], x3 = rb[(size_t)(b + 3) * nwords + i];
+            x |= (x0 | x1) | (x2 | x3);
+        }
+        for (; b < B; ++b) x |= rb[(size_t)b * nwords + i];
+        bm[i] = x;
     }
 }
 
@@ -501,12 +621,7 @@ k_union_compact(const uint32_t* __restrict__ row_bitmaps, int B, int V,
     uint32_t* bm = smem;
     uint32_t* wsum = smem + nwords;
     const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
-    const uint32_t* rb = row_bitmaps + (size_t)s * B * nwords;
-    for (int i = tid; i < nwords; i += kCandThreads) {
-        uint32_t x = 0;
-        for (int b = 0; b < B; ++b) x |= rb[(size_t)b * nwords + i];
-        bm[i] = x;
-    }
+    union_row_bitmaps(row_bitmaps + (size_t)s * B * nwords, B, nwords, bm);
     __syncthreads();
     mark_id_list(bm, V, topfreq, T, tf_first);
     __syncthreads();

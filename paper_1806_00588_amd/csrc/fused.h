@@ -12,7 +12,9 @@
 // the selection kernel and the inspection calls read it.  The work is redundant across the
 // workgroups on purpose: it runs concurrently on otherwise idle CUs and shortens the critical
 // path.  Steps with many sentences keep the three-kernel path (there the candidates kernel is
-// amortised and throughput matters, not latency).
+// amortised and throughput matters, not latency).  With a hit threshold above 1 the per-row hit
+// counting stays a kernel of its own (k_hit_rows) and "rebuilding the bitmap" is the OR of the
+// sentence's row bitmaps.
 #pragma once
 #include "candidates.h"
 #include "logits.h"
@@ -39,7 +41,8 @@ __host__ __device__ inline size_t fused_lds_words(int V, int d, int P, int K) {
 // (b / S), (b / S) + G, ...
 template <typename ET, bool ALIGNED>
 __global__ void __launch_bounds__(kCandThreads)
-k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* __restrict__ cand,
+k_cand_logits(CandArgs a, const uint32_t* __restrict__ row_bitmaps, const ET* __restrict__ E,
+              int64_t ld, int S, int32_t* __restrict__ cand,
               int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
               float2* __restrict__ partials, int64_t ppitch) {
     extern __shared__ uint32_t smem[];
@@ -54,7 +57,17 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
     uint32_t* wpref = smem + candidates_lds_words(V, a.d, a.P, a.K);
     float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + npow + 1);
 
-    build_presence_bitmap(a, s, smem);
+    if (row_bitmaps) {
+        // hit threshold above 1: the rows' thresholded hit bitmaps were left by k_hit_rows; the
+        // sentence's bitmap is their union with the top-frequent words (Eq. 3, Eq. 10)
+        const int32_t tf_first = (tid < a.T) ? a.topfreq[tid] : -1;
+        union_row_bitmaps(row_bitmaps + (size_t)s * B * nwords, B, nwords, bm);
+        __syncthreads();
+        mark_id_list(bm, V, a.topfreq, a.T, tf_first);
+        __syncthreads();
+    } else {
+        build_presence_bitmap(a, s, smem);
+    }
 
     // exclusive prefix of the bitmap words' popcounts; entries past the last word hold the total
     const int per_thread = (int)((npow + kCandThreads - 1) / kCandThreads);
@@ -78,7 +91,7 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
     // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
     // the contraction takes its A operands from there instead of reading H again
     const float* h_lds = nullptr;
-    if (candidates_rows_per_chunk(B, a.d, a.W) >= B && (a.d & 3) == 0)
+    if (!row_bitmaps && candidates_rows_per_chunk(B, a.d, a.W) >= B && (a.d & 3) == 0)
         h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
     const int col = ln & 15;
     for (int nt = g; nt < ntiles; nt += G) {

@@ -60,7 +60,8 @@ struct lsh_tables {
     std::vector<Slot> slots_host;
     int wg_candidates_lds = 0;
     int wg_fused_lds = 0;
-    int wg_hit_rows_lds = 0;
+    int wg_hit_rows_lds = 0;   // 0: the hit-count kernel cannot run on these tables (t > 1 unsupported)
+    int hit_list_cap = 0;
     Profiler prof;
 };
 
@@ -196,8 +197,7 @@ int env_int(const char* name, int dflt) {
 // measurements), never the hard limits.
 bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
     const int MT = (sp->B + kTileM - 1) / kTileM;
-    const bool possible = !sp->full_vocab && sp->threshold == 1 &&
-                          (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
+    const bool possible = !sp->full_vocab && (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
     const bool wanted = env_int("LSHBEAM_FUSED", sp->S * MT <= 8 ? 1 : 0) != 0;
     return possible && wanted;
 }
@@ -389,7 +389,8 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     std::vector<BandMeta> metas(W);
     for (size_t w = 0; w < W; ++w) metas[w] = t->bands[w].meta;
 
-    HIP_TRY(hipMalloc((void**)&t->words_dev, V * W * sizeof(int32_t)));
+    // 16 bytes of slack: k_hit_rows reads ids with 16-byte loads that may straddle the end
+    HIP_TRY(hipMalloc((void**)&t->words_dev, V * W * sizeof(int32_t) + 16));
     HIP_TRY(hipMalloc((void**)&t->slots_dev, t->slots_host.size() * sizeof(Slot)));
     HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
     HIP_TRY(hipMemcpyAsync(t->words_dev, words.data(), V * W * sizeof(int32_t), hipMemcpyHostToDevice, st));
@@ -402,10 +403,18 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (t->wg_candidates_lds > 48 * 1024)
         HIP_TRY(hipFuncSetAttribute((const void*)k_candidates,
                                     hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_candidates_lds));
-    t->wg_hit_rows_lds = (int)(hit_rows_lds_words(t->V, t->d, t->P, t->W) * sizeof(uint32_t));
-    if ((size_t)t->wg_hit_rows_lds <= kMaxDynLds)
-        HIP_TRY(hipFuncSetAttribute((const void*)k_hit_rows, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    t->wg_hit_rows_lds));
+    {   // LDS plan of k_hit_rows: whatever the counters leave goes to the load list
+        const size_t fixed = hit_rows_fixed_lds_words(t->V, t->d, t->P);
+        const size_t room = kMaxDynLds / sizeof(uint32_t);
+        size_t cap = room > fixed ? (room - fixed) / 1024 * 1024 : 0;
+        if (cap > (size_t)kHitListMax) cap = kHitListMax;
+        if (cap >= (size_t)kHitListMin && (uint64_t)t->W * (uint64_t)t->V < (1ull << 30)) {
+            t->hit_list_cap = (int)cap;
+            t->wg_hit_rows_lds = (int)((fixed + cap) * sizeof(uint32_t));
+            HIP_TRY(hipFuncSetAttribute((const void*)k_hit_rows,
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_hit_rows_lds));
+        }
+    }
     HIP_TRY(hipFuncSetAttribute((const void*)k_union_compact, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(((t->V + 31) / 32 + 64) * sizeof(uint32_t))));
     t->wg_fused_lds = (int)(fused_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
@@ -436,9 +445,7 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     if (!step_params_ok(tc, sp)) return LSH_ERR_INVALID_ARG;
     if (!sp->full_vocab && sp->T > 0 && !topfreq_dev) return LSH_ERR_INVALID_ARG;
     if (!sp->full_vocab && sp->threshold < 1) return LSH_ERR_INVALID_ARG;
-    if (!sp->full_vocab && sp->threshold > 1 &&
-        ((size_t)tc->wg_hit_rows_lds > kMaxDynLds || tc->W >= 65536))
-        return LSH_ERR_UNSUPPORTED;
+    if (!sp->full_vocab && sp->threshold > 1 && tc->wg_hit_rows_lds == 0) return LSH_ERR_UNSUPPORTED;
     if ((uintptr_t)workspace_dev % kAlign) return LSH_ERR_INVALID_ARG;
     lsh_tables* t = const_cast<lsh_tables*>(tc);  // only the profiler state is touched
     const Workspace w = carve(t, sp, workspace_dev);
@@ -449,30 +456,35 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     const CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
                       t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T};
     const bool fused = step_is_fused(t, sp);
+    const uint32_t* rbm = nullptr;
+    if (!sp->full_vocab && sp->threshold > 1) {
+        // Eq. 9-10 with t > 1: per-row hit counts, thresholded into one bitmap per row
+        launch(t, 3, k_hit_rows, dim3(sp->S * sp->B), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds, st,
+               ca, (int)sp->threshold, t->hit_list_cap, w.row_bitmaps);
+        rbm = w.row_bitmaps;
+    }
     if (fused) {
         const int per_sentence = std::max(1, env_int("LSHBEAM_FUSED_GRID", 256) / sp->S);
         const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
         const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
         if (t->dtype == LSH_F32) {
             const bool al = aligned16 && t->ld % 4 == 0;
-            if (al) launch(t, 1, k_cand_logits<float, true>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+            if (al) launch(t, 1, k_cand_logits<float, true>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
                            (const float*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
-            else launch(t, 1, k_cand_logits<float, false>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+            else launch(t, 1, k_cand_logits<float, false>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
                         (const float*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
         } else {
             const bool al = aligned16 && t->ld % 8 == 0 && t->d % 8 == 0;
-            if (al) launch(t, 1, k_cand_logits<uint16_t, true>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+            if (al) launch(t, 1, k_cand_logits<uint16_t, true>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
                            (const uint16_t*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
-            else launch(t, 1, k_cand_logits<uint16_t, false>, grid, block, (size_t)t->wg_fused_lds, st, ca,
+            else launch(t, 1, k_cand_logits<uint16_t, false>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
                         (const uint16_t*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
         }
         cand = w.cand;
         count = w.count;
     } else {
-        if (!sp->full_vocab && sp->threshold > 1) {
-            // Eq. 9-10 with t > 1: per-row hit counts, then union + top-frequent + compaction
-            launch(t, 3, k_hit_rows, dim3(sp->S * sp->B), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds,
-                   st, ca, (int)sp->threshold, w.row_bitmaps);
+        if (rbm) {
+            // union of the sentence's rows + top-frequent words + compaction
             launch(t, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
                    (size_t)(((t->V + 31) / 32 + 64) * sizeof(uint32_t)), st,
                    (const uint32_t*)w.row_bitmaps, sp->B, t->V, topfreq_dev, sp->T, w.cand, w.count);

@@ -6,7 +6,7 @@
 
 #ifdef LSHBEAM_TRACE
 namespace lshbeam {
-constexpr int kTraceKernels = 3, kTraceSlots = 16;
+constexpr int kTraceKernels = 4, kTraceSlots = 16;
 __device__ unsigned long long g_trace[kTraceKernels][kTraceSlots];
 }
 #define LSH_TRACE(kernel, slot)                                                   \

@@ -325,17 +325,20 @@ def test_step_is_deterministic():
         assert np.array_equal(x, y)
 
 
-@pytest.mark.parametrize("name,S,B", [("paper", 1, 12), ("tiny", 2, 4), ("tiny", 1, 20)])
-def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, monkeypatch):
+@pytest.mark.parametrize("name,S,B,t", [("paper", 1, 12, 1), ("tiny", 2, 4, 1), ("tiny", 1, 20, 1),
+                                        ("tiny", 2, 4, 2), ("paperscale", 1, 12, 5)])
+def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypatch):
     # few sentences: candidates are regenerated inside the logits kernel; LSHBEAM_FUSED=0 forces
     # the general three-kernel path.  Same arithmetic, same order: every output must be identical.
+    from paper_1806_00588_amd import binding
     cfg, gc = case(name)
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)[:S * B]
     bs = np.linspace(-1, 0, S * B).astype(np.float32)
     res = {}
     for mode in ("1", "0"):
         monkeypatch.setenv("LSHBEAM_FUSED", mode)
-        gb, gw, gs, sp, ws = gc.step(H, bs, S, B)
+        gb, gw, gs, sp, ws = gc.step(H, bs, S, B, threshold=t)
+        assert binding.step_is_fused(gc.tables, sp) == (mode == "1")
         cands = [gc.tables.debug_candidates(ws, sp, s) for s in range(S)]
         lps = [gc.tables.debug_logprobs(ws, sp, s, cap=len(cands[s])) for s in range(S)]
         res[mode] = (gb, gw, gs, cands, lps)
@@ -344,7 +347,7 @@ def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, monkeypatch)
     for s in range(S):
         assert np.array_equal(res["1"][3][s], res["0"][3][s])
         assert np.array_equal(res["1"][4][s], res["0"][4][s])
-        assert np.array_equal(res["1"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq))
+        assert np.array_equal(res["1"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq, t))
 
 
 def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
