@@ -216,6 +216,13 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
 // accumulators go straight from the matrix core to the stores, and a candidate row is read once
 // however many beams there are.  Waves of a workgroup take consecutive tiles; the grid is
 // persistent.
+//
+// Whole rounds (every wave of the grid one tile) run this way.  A last round that would occupy
+// fewer than half of the waves is different: while all waves stream, the kernel runs at the
+// memory system's rate, but a few hundred waves left alone with a 64 KB tile each run at one
+// wave's latency-bound rate, and that tail was a sixth of the kernel.  Such a remainder is
+// therefore dealt to whole workgroups, whose four waves split k and sum their partial tiles
+// through LDS in wave order (logits_tile): four times as many waves share the same bytes.
 template <typename ET, int MT, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(256)
 k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
@@ -225,6 +232,7 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;
     __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
+    __shared__ float red[4][4][kWave];
     const int ln = lane_id(), wv = wave_id();
     LSH_TRACE(1, 0);
     if (wv == 0) {
@@ -245,14 +253,21 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     const uint32_t nwaves = gridDim.x * 4u;
     const int col = ln & 15, kq = ln >> 4;
     const int nks = (d + KSTEP - 1) / KSTEP;
-
-    for (uint32_t t = blockIdx.x * 4u + wv; t < total_tiles; t += nwaves) {
-        int lo = 0, hi = S;
+    // tiles [0, wave_tiles) one wave each; the rest one workgroup each
+    const uint32_t whole = total_tiles / nwaves * nwaves;
+    const uint32_t wave_tiles =
+        (whole == 0 || (total_tiles - whole) * 2u > nwaves) ? total_tiles : whole;
+    auto sentence_of = [&](uint32_t t) {
+        int lo = 0, hi = S;  // last s with tile_pref[s] <= t
         while (hi - lo > 1) {
             const int mid = (lo + hi) >> 1;
             if (tile_pref[mid] <= t) lo = mid; else hi = mid;
         }
-        const int s = lo;
+        return lo;
+    };
+
+    for (uint32_t t = blockIdx.x * 4u + wv; t < wave_tiles; t += nwaves) {
+        const int s = sentence_of(t);
         const int nt = (int)(t - tile_pref[s]);
         const int C = count ? count[s] : V;
         const int n0 = nt * kTileN;
@@ -324,6 +339,19 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
                 if (col == 0 && row < B)
                     partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
             }
+    }
+
+    // the remainder: one workgroup per tile, k split over its four waves (uniform per workgroup)
+    for (uint32_t t = wave_tiles + blockIdx.x; t < total_tiles; t += gridDim.x) {
+        const int s = sentence_of(t);
+        const int nt = (int)(t - tile_pref[s]);
+        const int C = count ? count[s] : V;
+        const int cidx = min(nt * kTileN + col, C - 1);
+        const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        for (int mt = 0; mt < MT; ++mt)
+            logits_tile<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED>(E, ld, d, H, B, s, mt, nt, C, j,
+                                                                   logits, cpitch, partials, ppitch,
+                                                                   red);
     }
 }
 

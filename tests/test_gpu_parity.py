@@ -350,6 +350,22 @@ def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypat
         assert np.array_equal(res["1"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq, t))
 
 
+@pytest.mark.parametrize("grid", [1, 2, 3, 5, 8, 16])
+def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, monkeypatch):
+    # one wave per tile for whole rounds of the (here artificially small) grid; a short last
+    # round is dealt to whole workgroups that split k.  Every grid size moves the boundary.
+    cfg, gc = case("tiny")
+    monkeypatch.setenv("LSHBEAM_FUSED", "0")
+    monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
+    monkeypatch.setenv("LSHBEAM_LOGITS_GRID", str(grid))
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    rng = np.random.default_rng(grid)
+    for S, B in [(3, 4), (2, 20), (1, 40), (4, 7)]:
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B)
+    run_and_check(cfg, gc, H[:8], np.zeros(8, np.float32), 2, 4, full_vocab=True)
+
+
 def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
     import torch
     import paper_1806_00588_amd as lsh
