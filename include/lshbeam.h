@@ -139,12 +139,14 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
 
 /* ---- per-kernel timing -------------------------------------------------------------------- */
 
-#define LSH_NUM_KERNELS 4 /* 0 candidates (hash+probe+merge; t > 1: union + compaction),
-                             1 gathered logits, 2 select, 3 per-row hit counts (t > 1 only) */
+#define LSH_NUM_KERNELS 5 /* 0 candidates (hash+probe+merge, or union of earlier bitmaps +
+                             compaction), 1 gathered logits, 2 select, 3 per-row hit counts
+                             (t > 1 only), 4 per-part hashing (sentences with many beams) */
 
 /* 1 if a step with these parameters runs candidate generation inside the logits kernel (steps
  * with little work: few sentences; the timing slot 0 then stays empty and slot 1 covers the
- * fused kernel `k_cand_logits`), 0 if it runs the three kernels separately. */
+ * fused kernel `k_cand_logits`, or `k_union_logits` when slots 3 or 4 ran first), 0 if it runs
+ * the kernels separately. */
 int32_t lsh_step_is_fused(const lsh_tables* t, const lsh_step_params* sp);
 
 

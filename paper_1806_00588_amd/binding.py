@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "liblshbeam.so")
 
 LSH_F32, LSH_BF16 = 0, 1
-NUM_KERNELS = 4
+NUM_KERNELS = 5
 
 # every symbol include/lshbeam.h declares
 EXPORTED_SYMBOLS = (

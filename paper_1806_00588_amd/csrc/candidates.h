@@ -160,9 +160,11 @@ struct CandArgs {
 };
 
 // Builds sentence s's presence bitmap (V bits, at smem[0 .. ceil(V/32))) in LDS: hashing, cuckoo
-// probes, bucket walk and the top-frequent words.  Called by all kCandThreads threads of a
-// workgroup with candidates_lds_words() words of LDS; ends with a workgroup barrier.
-__device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, uint32_t* smem) {
+// probes, bucket walk and the top-frequent words.  Only the sentence's rows [row_begin, row_end)
+// are hashed (row_end < 0: all B).  Called by all kCandThreads threads of a workgroup with
+// candidates_lds_words() words of LDS; ends with a workgroup barrier.
+__device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, uint32_t* smem,
+                                                      int row_begin = 0, int row_end = -1) {
     const float* __restrict__ H = a.H;
     const int B = a.B, d = a.d, P = a.P, K = a.K, W = a.W, bits = a.bits, V = a.V, T = a.T;
     const int32_t* __restrict__ perms = a.perms;
@@ -184,6 +186,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     const int tid = threadIdx.x;
     const int u = P / W;
     const int rows_per_chunk = candidates_rows_per_chunk(B, d, W);
+    if (row_end < 0) row_end = B;
     LSH_TRACE(0, 0);
 
     // Everything whose address is known up front is requested before anything is waited for:
@@ -196,9 +199,9 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     const bool vec_ok = (((uintptr_t)H0 | ((uintptr_t)d * 4)) & 15) == 0;
     float4 r0 = {}, r1 = {}, r2 = {}, r3 = {};
     {
-        const int n4 = (min(rows_per_chunk, B) * d) >> 2;
+        const int n4 = (min(rows_per_chunk, row_end - row_begin) * d) >> 2;
         if (vec_ok && n4 > 0) {
-            const float4* H4 = reinterpret_cast<const float4*>(H0);
+            const float4* H4 = reinterpret_cast<const float4*>(H0 + (size_t)row_begin * d);
             r0 = H4[min(tid, n4 - 1)];
             r1 = H4[min(tid + kCandThreads, n4 - 1)];
             r2 = H4[min(tid + 2 * kCandThreads, n4 - 1)];
@@ -217,8 +220,8 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     mark_id_list(bm, V, topfreq, T, tf_first);
     LSH_TRACE(0, 11);
 
-    for (int row0 = 0; row0 < B; row0 += rows_per_chunk) {
-        const int rows = min(rows_per_chunk, B - row0);
+    for (int row0 = row_begin; row0 < row_end; row0 += rows_per_chunk) {
+        const int rows = min(rows_per_chunk, row_end - row0);
         // The chunk's hidden rows are contiguous: copy them to LDS with coalesced loads (a row's
         // P*K permuted coordinates touch nearly every cache line of the row anyway), so that the
         // permuted gathers of Eq. 5 are LDS reads and no global load depends on another.
@@ -229,7 +232,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
             float4* S4 = reinterpret_cast<float4*>(stage);
             const int n4 = nval >> 2;
             for (int e0 = tid; e0 < n4; e0 += 4 * kCandThreads) {  // 4 independent loads in flight
-                if (row0 != 0 || e0 != tid) {  // the very first batch is already in registers
+                if (row0 != row_begin || e0 != tid) {  // the very first batch is already in registers
                     r0 = H4[min(e0, n4 - 1)];
                     r1 = H4[min(e0 + kCandThreads, n4 - 1)];
                     r2 = H4[min(e0 + 2 * kCandThreads, n4 - 1)];
@@ -393,6 +396,22 @@ k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count
     build_presence_bitmap(a, s, smem);
     compact_bitmap(smem, nwords, wsum, cand + (size_t)s * a.V, count + s);
     LSH_TRACE(0, 6);
+}
+
+// Sentences with many beams: the hidden rows of a sentence are hashed a chunk at a time, so one
+// workgroup per sentence serialises ceil(B / rows per chunk) rounds of dependent memory round
+// trips.  Here the sentence is cut into `nparts` parts of `part_rows` rows, one workgroup each;
+// every part leaves its own V-bit bitmap (without the top-frequent words) in global memory at
+// part_bitmaps[(s * nparts + part) * ceil(V/32)], and the consumer ORs the parts (Eq. 3's union).
+__global__ void __launch_bounds__(kCandThreads)
+k_part_bitmaps(CandArgs a, int part_rows, int nparts, uint32_t* __restrict__ part_bitmaps) {
+    extern __shared__ uint32_t smem[];
+    const int s = blockIdx.x / nparts, part = blockIdx.x - s * nparts;
+    const int nwords = (a.V + 31) >> 5;
+    a.T = 0;
+    build_presence_bitmap(a, s, smem, part * part_rows, min(a.B, (part + 1) * part_rows));
+    uint32_t* out = part_bitmaps + (size_t)blockIdx.x * nwords;
+    for (int i = threadIdx.x; i < nwords; i += kCandThreads) out[i] = smem[i];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -593,8 +612,8 @@ k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /
     LSH_TRACE(3, 6);
 }
 
-// OR of B row bitmaps of nwords words each (rows nwords apart) into the LDS bitmap bm; called by
-// all kCandThreads threads, no barrier inside.
+// OR of B bitmaps of nwords words each (nwords apart) into the LDS bitmap bm; called by all
+// kCandThreads threads, no barrier inside.
 __device__ __forceinline__ void union_row_bitmaps(const uint32_t* __restrict__ rb, int B, int nwords,
                                                   uint32_t* bm) {
     for (int i = threadIdx.x; i < nwords; i += kCandThreads) {

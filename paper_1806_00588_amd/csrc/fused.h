@@ -12,9 +12,9 @@
 // the selection kernel and the inspection calls read it.  The work is redundant across the
 // workgroups on purpose: it runs concurrently on otherwise idle CUs and shortens the critical
 // path.  Steps with many sentences keep the three-kernel path (there the candidates kernel is
-// amortised and throughput matters, not latency).  With a hit threshold above 1 the per-row hit
-// counting stays a kernel of its own (k_hit_rows) and "rebuilding the bitmap" is the OR of the
-// sentence's row bitmaps.
+// amortised and throughput matters, not latency).  With a hit threshold above 1, or with more
+// beams than one chunk of hashing holds, the hashing stays in a kernel of its own and
+// "rebuilding the bitmap" is the OR of the bitmaps that kernel left (k_union_logits).
 #pragma once
 #include "candidates.h"
 #include "logits.h"
@@ -37,38 +37,22 @@ __host__ __device__ inline size_t fused_lds_words(int V, int d, int P, int K) {
            (size_t)kFusedWaves * 4 * kWave;
 }
 
-// grid = S * G workgroups: workgroup b works for sentence b % S and takes that sentence's tiles
-// (b / S), (b / S) + G, ...
+// What follows the bitmap in both fused kernels: exclusive prefix of the bitmap words'
+// popcounts, then for each of this workgroup's tiles the 16 candidates by rank and the split-k
+// tile.  `wpref` has pow2_at_least(nwords) + 1 words, `wsum` >= 17, `red` is the cross-wave
+// reduction buffer; h_lds (or null) are the sentence's hidden rows staged in LDS as [B][d].
 template <typename ET, bool ALIGNED>
-__global__ void __launch_bounds__(kCandThreads)
-k_cand_logits(CandArgs a, const uint32_t* __restrict__ row_bitmaps, const ET* __restrict__ E,
-              int64_t ld, int S, int32_t* __restrict__ cand,
-              int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
-              float2* __restrict__ partials, int64_t ppitch) {
-    extern __shared__ uint32_t smem[];
+__device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* wsum, uint32_t* wpref,
+                                                  float (*red)[4][kWave], const float* h_lds,
+                                                  const ET* __restrict__ E, int64_t ld, int d,
+                                                  const float* __restrict__ H, int B, int V, int s,
+                                                  int g, int G, int32_t* __restrict__ cand,
+                                                  int32_t* __restrict__ count,
+                                                  float* __restrict__ logits, int64_t cpitch,
+                                                  float2* __restrict__ partials, int64_t ppitch) {
     const int tid = threadIdx.x, ln = lane_id();
-    const int s = blockIdx.x % S;
-    const int g = blockIdx.x / S, G = gridDim.x / S;
-    const int V = a.V, B = a.B;
     const int nwords = (V + 31) >> 5;
     const uint32_t npow = pow2_at_least((uint32_t)nwords);
-    uint32_t* bm = smem;
-    uint32_t* wsum = smem + candidates_lds_words(V, a.d, a.P, a.K) - 64;
-    uint32_t* wpref = smem + candidates_lds_words(V, a.d, a.P, a.K);
-    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + npow + 1);
-
-    if (row_bitmaps) {
-        // hit threshold above 1: the rows' thresholded hit bitmaps were left by k_hit_rows; the
-        // sentence's bitmap is their union with the top-frequent words (Eq. 3, Eq. 10)
-        const int32_t tf_first = (tid < a.T) ? a.topfreq[tid] : -1;
-        union_row_bitmaps(row_bitmaps + (size_t)s * B * nwords, B, nwords, bm);
-        __syncthreads();
-        mark_id_list(bm, V, a.topfreq, a.T, tf_first);
-        __syncthreads();
-    } else {
-        build_presence_bitmap(a, s, smem);
-    }
-
     // exclusive prefix of the bitmap words' popcounts; entries past the last word hold the total
     const int per_thread = (int)((npow + kCandThreads - 1) / kCandThreads);
     const int wbeg = tid * per_thread;
@@ -86,13 +70,7 @@ k_cand_logits(CandArgs a, const uint32_t* __restrict__ row_bitmaps, const ET* __
     const int C = (int)total;
     if (g == 0 && tid == 0) count[s] = C;
 
-    const int MT = (B + kTileM - 1) / kTileM;
     const int ntiles = (C + kTileN - 1) / kTileN;
-    // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
-    // the contraction takes its A operands from there instead of reading H again
-    const float* h_lds = nullptr;
-    if (!row_bitmaps && candidates_rows_per_chunk(B, a.d, a.W) >= B && (a.d & 3) == 0)
-        h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
     const int col = ln & 15;
     for (int nt = g; nt < ntiles; nt += G) {
         // this lane's candidate: output position 16 nt + col of the ascending list (clamped onto
@@ -114,10 +92,72 @@ k_cand_logits(CandArgs a, const uint32_t* __restrict__ row_bitmaps, const ET* __
         const int32_t id = (int32_t)((lo << 5) + pos);
         if (tid < kTileN && nt * kTileN + col < C) cand[(size_t)s * V + nt * kTileN + col] = id;
         LSH_TRACE(1, 2);
-        for (int mt = 0; mt < MT; ++mt)
-            logits_tile<ET, kFusedWaves, 4, ALIGNED>(E, ld, a.d, a.H, B, s, mt, nt, C, (int64_t)id,
-                                                     logits, cpitch, partials, ppitch, red, h_lds);
+        logits_tile_all_rows<ET, kFusedWaves, 4, ALIGNED>(E, ld, d, H, B, s, nt, C, (int64_t)id, logits,
+                                                          cpitch, partials, ppitch, red, h_lds);
     }
+}
+
+// grid = S * G workgroups: workgroup b works for sentence b % S and takes that sentence's tiles
+// (b / S), (b / S) + G, ...
+template <typename ET, bool ALIGNED>
+__global__ void __launch_bounds__(kCandThreads)
+k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* __restrict__ cand,
+              int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
+              float2* __restrict__ partials, int64_t ppitch) {
+    extern __shared__ uint32_t smem[];
+    const int s = blockIdx.x % S;
+    const int g = blockIdx.x / S, G = gridDim.x / S;
+    const int V = a.V, B = a.B;
+    const uint32_t npow = pow2_at_least((uint32_t)((V + 31) >> 5));
+    uint32_t* bm = smem;
+    uint32_t* wsum = smem + candidates_lds_words(V, a.d, a.P, a.K) - 64;
+    uint32_t* wpref = smem + candidates_lds_words(V, a.d, a.P, a.K);
+    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + npow + 1);
+
+    build_presence_bitmap(a, s, smem);
+    // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
+    // the contraction takes its A operands from there instead of reading H again
+    const float* h_lds = nullptr;
+    if (candidates_rows_per_chunk(B, a.d, a.W) >= B && (a.d & 3) == 0)
+        h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
+    tiles_from_bitmap<ET, ALIGNED>(bm, wsum, wpref, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
+                                   count, logits, cpitch, partials, ppitch);
+}
+
+// The same with the hashing done by an earlier kernel: the sentence's bitmap is the union of
+// `nparts` bitmaps left in global memory (one per hidden row by k_hit_rows when the hit
+// threshold is above 1, one per part of the sentence by k_part_bitmaps when it has many beams)
+// and the top-frequent words (Eq. 3).
+__host__ __device__ inline size_t union_logits_lds_words(int V) {
+    return (size_t)bitmap_words_padded(V) + 64 + ((pow2_at_least((uint32_t)(((size_t)V + 31) / 32)) + 1 + 3) & ~3u) +
+           (size_t)kFusedWaves * 4 * kWave;
+}
+
+template <typename ET, bool ALIGNED>
+__global__ void __launch_bounds__(kCandThreads)
+k_union_logits(const uint32_t* __restrict__ part_bitmaps, int nparts, const int32_t* __restrict__ topfreq,
+               int T, const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S,
+               int B, int V, int32_t* __restrict__ cand, int32_t* __restrict__ count,
+               float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
+               int64_t ppitch) {
+    extern __shared__ uint32_t smem[];
+    const int tid = threadIdx.x;
+    const int s = blockIdx.x % S;
+    const int g = blockIdx.x / S, G = gridDim.x / S;
+    const int nwords = (V + 31) >> 5;
+    const uint32_t npow = pow2_at_least((uint32_t)nwords);
+    uint32_t* bm = smem;
+    uint32_t* wsum = bm + bitmap_words_padded(V);
+    uint32_t* wpref = wsum + 64;
+    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + ((npow + 1 + 3) & ~3u));
+
+    const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
+    union_row_bitmaps(part_bitmaps + (size_t)s * nparts * nwords, nparts, nwords, bm);
+    __syncthreads();
+    mark_id_list(bm, V, topfreq, T, tf_first);
+    __syncthreads();
+    tiles_from_bitmap<ET, ALIGNED>(bm, wsum, wpref, red, nullptr, E, ld, d, H, B, V, s, g, G, cand,
+                                   count, logits, cpitch, partials, ppitch);
 }
 
 }  // namespace lshbeam

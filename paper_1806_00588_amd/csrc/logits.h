@@ -49,14 +49,16 @@ constexpr int kTileN = 16;  // candidates per tile
 constexpr int kTileM = 16;  // hidden rows per tile
 constexpr int kMaxSentencesLogits = 4096;
 
-// One tile: logits of hidden rows [16 mt, 16 mt + 16) of sentence s against 16 candidates, this
-// lane's candidate being row j of E (lanes beyond the list hold any valid row; their results are
-// dropped).  Called by all WAVES*64 threads of the workgroup; contains two workgroup barriers.
-// h_lds, if given, is an LDS copy of the sentence's B hidden rows (16-byte aligned, pitch d).
+// MTB tiles: logits of hidden rows [16 mt, 16 (mt + MTB)) of sentence s against 16 candidates,
+// this lane's candidate being row j of E (lanes beyond the list hold any valid row; their results
+// are dropped; row groups beyond B are computed on clamped rows and dropped too).  The candidate
+// rows are loaded once for all MTB row groups.  Called by all WAVES*64 threads of the workgroup;
+// contains 2 MTB workgroup barriers.  h_lds, if given, is an LDS copy of the sentence's B hidden
+// rows (16-byte aligned, pitch d).
 //
 // ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
 // d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
-template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int MTB = 1>
 __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld, int d,
                                             const float* __restrict__ H, int B, int s, int mt,
                                             int nt, int C, int64_t j, float* __restrict__ logits,
@@ -70,13 +72,20 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
     const int nks = (d + KSTEP - 1) / KSTEP;
     const int n0 = nt * kTileN;
     const ET* erow = E + j * ld;
-    const int hr = min(mt * kTileM + col, B - 1);  // clamped like the candidate: never stored
-    // the sentence's hidden rows, from LDS when the caller has them staged there ([B][d])
-    const float* hrow = h_lds ? h_lds + (size_t)hr * d : H + ((size_t)s * B + hr) * d;
+    // the sentence's hidden rows, from LDS when the caller has them staged there ([B][d]);
+    // rows beyond B are clamped like the candidate: never stored
+    const float* hrow[MTB];
+#pragma unroll
+    for (int m = 0; m < MTB; ++m) {
+        const int hr = min((mt + m) * kTileM + col, B - 1);
+        hrow[m] = h_lds ? h_lds + (size_t)hr * d : H + ((size_t)s * B + hr) * d;
+    }
 
-    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+    floatx4 acc[MTB];
+#pragma unroll
+    for (int m = 0; m < MTB; ++m) acc[m] = floatx4{0.f, 0.f, 0.f, 0.f};
     for (int ks0 = wv; ks0 < nks; ks0 += WAVES * UNROLL) {
-        float ev[UNROLL][VEC], hv[UNROLL][VEC];
+        float ev[UNROLL][VEC], hv[MTB][UNROLL][VEC];
 #pragma unroll
         for (int uu = 0; uu < UNROLL; ++uu) {
             const int k = (ks0 + uu * WAVES) * KSTEP + kq * VEC;
@@ -84,21 +93,28 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
                 if (k < d) {
                     ElemTraits<ET>::load16(erow + k, ev[uu]);
 #pragma unroll
-                    for (int q = 0; q < VEC; q += 4) {
-                        const float4 h4 = *reinterpret_cast<const float4*>(hrow + k + q);
-                        hv[uu][q] = h4.x; hv[uu][q + 1] = h4.y;
-                        hv[uu][q + 2] = h4.z; hv[uu][q + 3] = h4.w;
-                    }
+                    for (int m = 0; m < MTB; ++m)
+#pragma unroll
+                        for (int q = 0; q < VEC; q += 4) {
+                            const float4 h4 = *reinterpret_cast<const float4*>(hrow[m] + k + q);
+                            hv[m][uu][q] = h4.x; hv[m][uu][q + 1] = h4.y;
+                            hv[m][uu][q + 2] = h4.z; hv[m][uu][q + 3] = h4.w;
+                        }
                 } else {
 #pragma unroll
-                    for (int q = 0; q < VEC; ++q) { ev[uu][q] = 0.f; hv[uu][q] = 0.f; }
+                    for (int q = 0; q < VEC; ++q) {
+                        ev[uu][q] = 0.f;
+#pragma unroll
+                        for (int m = 0; m < MTB; ++m) hv[m][uu][q] = 0.f;
+                    }
                 }
             } else {
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) {
                     const bool in = (k + q) < d;
                     ev[uu][q] = in ? elem_f32(erow + k + q) : 0.f;
-                    hv[uu][q] = in ? hrow[k + q] : 0.f;
+#pragma unroll
+                    for (int m = 0; m < MTB; ++m) hv[m][uu][q] = in ? hrow[m][k + q] : 0.f;
                 }
             }
         }
@@ -106,31 +122,69 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
         for (int uu = 0; uu < UNROLL; ++uu)
 #pragma unroll
             for (int q = 0; q < VEC; ++q)
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[uu][q], ev[uu][q], acc, 0, 0, 0);
+#pragma unroll
+                for (int m = 0; m < MTB; ++m)
+                    acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[m][uu][q], ev[uu][q], acc[m],
+                                                                  0, 0, 0);
     }
 
     LSH_TRACE(1, 3);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[r];
-    __syncthreads();
-    if (tid < kTileM * kTileN) {
-        const int i = tid >> 4, jc = tid & 15;
-        const int src = (i >> 2) * 16 + jc, r = i & 3;
-        float sum = 0.f;
+    for (int m = 0; m < MTB; ++m) {
 #pragma unroll
-        for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
-        const int row = mt * kTileM + i, c = n0 + jc;
-        const bool valid = row < B && c < C;
-        if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
-        // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
-        // tile's 16 candidates; the 16 lanes that share a row are one DPP row
-        const float mx = row16_max(valid ? sum : -INFINITY);
-        const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
-        if (jc == 0 && row < B)
-            partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+        for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[m][r];
+        __syncthreads();
+        if (tid < kTileM * kTileN) {
+            const int i = tid >> 4, jc = tid & 15;
+            const int src = (i >> 2) * 16 + jc, r = i & 3;
+            float sum = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
+            const int row = (mt + m) * kTileM + i, c = n0 + jc;
+            const bool valid = row < B && c < C;
+            if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
+            // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
+            // tile's 16 candidates; the 16 lanes that share a row are one DPP row
+            const float mx = row16_max(valid ? sum : -INFINITY);
+            const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
+            if (jc == 0 && row < B)
+                partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+        }
+        __syncthreads();
     }
-    __syncthreads();
     LSH_TRACE(1, 4);
+}
+
+// All row groups of one tile of candidates, the candidate rows being read once for up to four
+// groups (64 beams) at a time.
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
+__device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, int64_t ld, int d,
+                                                     const float* __restrict__ H, int B, int s,
+                                                     int nt, int C, int64_t j,
+                                                     float* __restrict__ logits, int64_t cpitch,
+                                                     float2* __restrict__ partials, int64_t ppitch,
+                                                     float (*red)[4][kWave],
+                                                     const float* h_lds = nullptr) {
+    // loads in flight per row group shrink as the groups grow: the operands of all groups have
+    // to fit the register budget of a 1024-thread workgroup
+    constexpr int U4 = UNROLL >= 4 ? UNROLL / 4 : 1;
+    constexpr int U2 = ElemTraits<ET>::VEC > 4 ? U4 : (UNROLL >= 2 ? UNROLL / 2 : 1);
+    const int MT = (B + kTileM - 1) / kTileM;
+    if (MT == 1) {
+        logits_tile<ET, WAVES, UNROLL, ALIGNED, 1>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
+                                                   partials, ppitch, red, h_lds);
+    } else if (MT == 2) {
+        logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
+                                               partials, ppitch, red, h_lds);
+    } else if (ElemTraits<ET>::VEC > 4) {  // bf16: twice the registers per load, two groups at most
+        for (int mt = 0; mt < MT; mt += 2)
+            logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
+                                                   partials, ppitch, red, h_lds);
+    } else {
+        for (int mt = 0; mt < MT; mt += 4)
+            logits_tile<ET, WAVES, U4, ALIGNED, 4>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
+                                                   partials, ppitch, red, h_lds);
+    }
 }
 
 template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
@@ -348,10 +402,9 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int C = count ? count[s] : V;
         const int cidx = min(nt * kTileN + col, C - 1);
         const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
-        for (int mt = 0; mt < MT; ++mt)
-            logits_tile<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED>(E, ld, d, H, B, s, mt, nt, C, j,
-                                                                   logits, cpitch, partials, ppitch,
-                                                                   red);
+        logits_tile_all_rows<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED>(E, ld, d, H, B, s, nt, C, j,
+                                                                        logits, cpitch, partials,
+                                                                        ppitch, red);
     }
 }
 

@@ -41,7 +41,7 @@ struct Profiler {
     bool on = false;
     int max_steps = 0;
     std::vector<hipEvent_t> ev[LSH_NUM_KERNELS];  // start/stop pairs
-    int used[LSH_NUM_KERNELS] = {0, 0, 0, 0};
+    int used[LSH_NUM_KERNELS] = {0, 0, 0, 0, 0};
 };
 
 }  // namespace
@@ -62,6 +62,7 @@ struct lsh_tables {
     int wg_fused_lds = 0;
     int wg_hit_rows_lds = 0;   // 0: the hit-count kernel cannot run on these tables (t > 1 unsupported)
     int hit_list_cap = 0;
+    int wg_union_logits_lds = 0;
     Profiler prof;
 };
 
@@ -157,7 +158,7 @@ struct Workspace {
     int32_t* count;      // [S]
     float* logits;       // [R, cpitch]
     float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max))
-    uint32_t* row_bitmaps;  // [R, ceil(V/32)]  thresholded hit rows (t > 1 only)
+    uint32_t* row_bitmaps;  // [R, ceil(V/32)]  per-row (t > 1) or per-part (many beams) bitmaps
     float* lse;          // [R]
     int64_t ppitch;
     int64_t cpitch;
@@ -176,7 +177,7 @@ Workspace carve(const lsh_tables* t, const lsh_step_params* sp, void* base) {
     w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
     w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(float2));
     w.lse = (float*)take(R * sizeof(float));
-    w.row_bitmaps = (uint32_t*)take(sp->threshold > 1 && !sp->full_vocab ? R * ((V + 31) / 32) * sizeof(uint32_t) : 0);
+    w.row_bitmaps = (uint32_t*)take(sp->full_vocab ? 0 : R * ((V + 31) / 32) * sizeof(uint32_t));
     w.bytes = off;
     return w;
 }
@@ -200,6 +201,17 @@ bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
     const bool possible = !sp->full_vocab && (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
     const bool wanted = env_int("LSHBEAM_FUSED", sp->S * MT <= 8 ? 1 : 0) != 0;
     return possible && wanted;
+}
+
+// Rows of a sentence hashed per workgroup when the sentence is cut into parts (t = 1, more beams
+// than one chunk of hashing holds); 0 = the sentence is hashed by one workgroup.
+// LSHBEAM_PART_ROWS forces a part size (for tests and measurements).
+int part_rows_of(const lsh_tables* t, const lsh_step_params* sp) {
+    if (sp->full_vocab || sp->threshold != 1) return 0;
+    const int rpc = candidates_rows_per_chunk(sp->B, t->d, t->W);
+    const int forced = env_int("LSHBEAM_PART_ROWS", 0);
+    if (forced > 0) return std::min(forced, rpc);
+    return sp->B > rpc ? rpc : 0;
 }
 
 template <typename ET, int WAVES>
@@ -300,6 +312,7 @@ const char* lsh_kernel_name(int32_t which) {
         case 1: return "k_logits";
         case 2: return "k_select";
         case 3: return "k_hit_rows";
+        case 4: return "k_part_bitmaps";
     }
     return "";
 }
@@ -417,6 +430,17 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     }
     HIP_TRY(hipFuncSetAttribute((const void*)k_union_compact, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)(((t->V + 31) / 32 + 64) * sizeof(uint32_t))));
+    HIP_TRY(hipFuncSetAttribute((const void*)k_part_bitmaps, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                t->wg_candidates_lds));
+    t->wg_union_logits_lds = (int)(union_logits_lds_words(t->V) * sizeof(uint32_t));
+    {
+        const void* fu[4] = {(const void*)k_union_logits<float, true>, (const void*)k_union_logits<float, false>,
+                             (const void*)k_union_logits<uint16_t, true>,
+                             (const void*)k_union_logits<uint16_t, false>};
+        for (const void* f : fu)
+            HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        t->wg_union_logits_lds));
+    }
     t->wg_fused_lds = (int)(fused_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
     if ((size_t)t->wg_fused_lds <= kMaxDynLds) {
         const void* fused[4] = {(const void*)k_cand_logits<float, true>, (const void*)k_cand_logits<float, false>,
@@ -455,39 +479,54 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     const int32_t* count = nullptr;
     const CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
                       t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T};
-    const bool fused = step_is_fused(t, sp);
-    const uint32_t* rbm = nullptr;
+    // Bitmaps made by an earlier kernel, to be OR-ed per sentence: one per hidden row when the
+    // hit threshold is above 1 (Eq. 9-10), one per part of the sentence when it has many beams.
+    const uint32_t* parts = nullptr;
+    int nparts = 0;
     if (!sp->full_vocab && sp->threshold > 1) {
-        // Eq. 9-10 with t > 1: per-row hit counts, thresholded into one bitmap per row
         launch(t, 3, k_hit_rows, dim3(sp->S * sp->B), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds, st,
                ca, (int)sp->threshold, t->hit_list_cap, w.row_bitmaps);
-        rbm = w.row_bitmaps;
+        parts = w.row_bitmaps;
+        nparts = sp->B;
+    } else if (const int pr = part_rows_of(t, sp)) {
+        nparts = (sp->B + pr - 1) / pr;
+        launch(t, 4, k_part_bitmaps, dim3(sp->S * nparts), dim3(kCandThreads), (size_t)t->wg_candidates_lds,
+               st, ca, pr, nparts, w.row_bitmaps);
+        parts = w.row_bitmaps;
     }
+    const bool fused = step_is_fused(t, sp);
     if (fused) {
         const int per_sentence = std::max(1, env_int("LSHBEAM_FUSED_GRID", 256) / sp->S);
         const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
         const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
-        if (t->dtype == LSH_F32) {
-            const bool al = aligned16 && t->ld % 4 == 0;
-            if (al) launch(t, 1, k_cand_logits<float, true>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
-                           (const float*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
-            else launch(t, 1, k_cand_logits<float, false>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
-                        (const float*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
+        const bool f32 = t->dtype == LSH_F32;
+        const bool al = f32 ? (aligned16 && t->ld % 4 == 0) : (aligned16 && t->ld % 8 == 0 && t->d % 8 == 0);
+        if (parts) {
+            const size_t lds = (size_t)t->wg_union_logits_lds;
+#define LSH_UNION_LOGITS(ET, AL)                                                                  \
+    launch(t, 1, k_union_logits<ET, AL>, grid, block, lds, st, parts, nparts, topfreq_dev, sp->T, \
+           (const ET*)t->E, t->ld, t->d, H_dev, sp->S, sp->B, t->V, w.cand, w.count, w.logits,    \
+           w.cpitch, w.partials, w.ppitch)
+            if (f32) { if (al) LSH_UNION_LOGITS(float, true); else LSH_UNION_LOGITS(float, false); }
+            else { if (al) LSH_UNION_LOGITS(uint16_t, true); else LSH_UNION_LOGITS(uint16_t, false); }
+#undef LSH_UNION_LOGITS
         } else {
-            const bool al = aligned16 && t->ld % 8 == 0 && t->d % 8 == 0;
-            if (al) launch(t, 1, k_cand_logits<uint16_t, true>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
-                           (const uint16_t*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
-            else launch(t, 1, k_cand_logits<uint16_t, false>, grid, block, (size_t)t->wg_fused_lds, st, ca, rbm,
-                        (const uint16_t*)t->E, t->ld, sp->S, w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch);
+            const size_t lds = (size_t)t->wg_fused_lds;
+#define LSH_CAND_LOGITS(ET, AL)                                                                   \
+    launch(t, 1, k_cand_logits<ET, AL>, grid, block, lds, st, ca, (const ET*)t->E, t->ld, sp->S,  \
+           w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch)
+            if (f32) { if (al) LSH_CAND_LOGITS(float, true); else LSH_CAND_LOGITS(float, false); }
+            else { if (al) LSH_CAND_LOGITS(uint16_t, true); else LSH_CAND_LOGITS(uint16_t, false); }
+#undef LSH_CAND_LOGITS
         }
         cand = w.cand;
         count = w.count;
     } else {
-        if (rbm) {
-            // union of the sentence's rows + top-frequent words + compaction
+        if (parts) {
+            // union of the sentence's bitmaps + top-frequent words + compaction
             launch(t, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
-                   (size_t)(((t->V + 31) / 32 + 64) * sizeof(uint32_t)), st,
-                   (const uint32_t*)w.row_bitmaps, sp->B, t->V, topfreq_dev, sp->T, w.cand, w.count);
+                   (size_t)(((t->V + 31) / 32 + 64) * sizeof(uint32_t)), st, parts, nparts, t->V,
+                   topfreq_dev, sp->T, w.cand, w.count);
             cand = w.cand;
             count = w.count;
         } else if (!sp->full_vocab) {

@@ -95,30 +95,64 @@ struct SelShared {
     float lse[256];
     float bs[256];
     uint32_t wtau[kSelWaves];
-    uint32_t bitcnt[2][kSelWaves];
     uint32_t misc[8];
 };
 
-// The k-th largest of the workgroup's 1024 thread values, k in 1..1024: the same bitwise descent
-// as wave_kth_largest_lb, with the per-bit population summed over the waves through LDS (one
-// barrier per bit; the counters are double-buffered).
+// A lower bound tau of the k-th largest of the workgroup's 1024 thread values (k in 1..1024)
+// that at least k and at most k + kSelSlack values reach (more only if more than that are equal
+// in all resolved digits): radix descent, 8 bits per pass, on an LDS histogram.  A pass: clear
+// the 256 bins, every thread still matching the resolved prefix adds itself to its digit's bin
+// (a wave whose active lanes all share the digit -- the rule in the top byte -- adds once),
+// wave 0 walks the bins from the top until the count crosses what is still needed.  It stops
+// as soon as taking the whole crossing bin costs at most kSelSlack extra values; tau is that
+// bin's lower edge.  Three barriers per pass and at most four passes, against one barrier per
+// bit for a bitwise descent.
+constexpr uint32_t kSelSlack = 8;
 __device__ __forceinline__ uint32_t block_kth_largest_lb(uint32_t v, int k, SelShared* sh) {
-    const int wv = wave_id();
-    uint64_t active = ~0ull;
-    uint32_t kth = 0;
-    int need = k;
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint64_t ones = __ballot((v >> bit) & 1u) & active;
-        uint32_t* cnt = sh->bitcnt[bit & 1];
-        if (lane_id() == 0) cnt[wv] = (uint32_t)__popcll(ones);
+    const int tid = threadIdx.x, ln = lane_id();
+    uint32_t prefix = 0, mask = 0, remaining = (uint32_t)k;
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) sh->hist[tid] = 0;
         __syncthreads();
-        int c = 0;
+        const bool act = (v & mask) == prefix;
+        const uint32_t digit = (v >> shift) & 255u;
+        const uint64_t actm = __ballot(act);
+        if (actm) {
+            const int first = __ffsll((unsigned long long)actm) - 1;
+            const uint32_t d0 = wave_read_lane(digit, first);
+            if (__ballot(act && digit == d0) == actm) {
+                if (ln == first) atomicAdd(&sh->hist[d0], (uint32_t)__popcll(actm));
+            } else if (act) {
+                atomicAdd(&sh->hist[digit], 1u);
+            }
+        }
+        __syncthreads();
+        if (tid < kWave) {
+            // lane L owns bins 255-4L .. 252-4L (descending): a scan over lanes walks the
+            // histogram from the largest digit down; one lane sees the count cross `remaining`
+            const int b0 = 255 - 4 * tid;
+            uint32_t h[4], local = 0;
 #pragma unroll
-        for (int w = 0; w < kSelWaves; ++w) c += (int)cnt[w];
-        if (c >= need) { active = ones; kth |= 1u << bit; }
-        else { need -= c; active &= ~ones; }
+            for (int q = 0; q < 4; ++q) { h[q] = sh->hist[b0 - q]; local += h[q]; }
+            uint32_t excl = wave_incl_scan(local) - local;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (excl < remaining && remaining <= excl + h[q]) {
+                    sh->misc[0] = (uint32_t)(b0 - q);
+                    sh->misc[1] = remaining - excl;
+                    sh->misc[2] = h[q];
+                }
+                excl += h[q];
+            }
+        }
+        __syncthreads();
+        const uint32_t bin = sh->misc[0], cnt = sh->misc[2];
+        remaining = sh->misc[1];
+        prefix |= bin << shift;
+        mask |= 0xFFu << shift;
+        if (cnt <= remaining + kSelSlack) break;
     }
-    return kth;
+    return prefix;
 }
 
 // Everything a sweep over the sentence's scores needs.

@@ -326,7 +326,8 @@ def test_step_is_deterministic():
 
 
 @pytest.mark.parametrize("name,S,B,t", [("paper", 1, 12, 1), ("tiny", 2, 4, 1), ("tiny", 1, 20, 1),
-                                        ("tiny", 2, 4, 2), ("paperscale", 1, 12, 5)])
+                                        ("tiny", 2, 4, 2), ("paperscale", 1, 12, 5),
+                                        ("paper", 1, 30, 1)])
 def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypatch):
     # few sentences: candidates are regenerated inside the logits kernel; LSHBEAM_FUSED=0 forces
     # the general three-kernel path.  Same arithmetic, same order: every output must be identical.
@@ -348,6 +349,34 @@ def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypat
         assert np.array_equal(res["1"][3][s], res["0"][3][s])
         assert np.array_equal(res["1"][4][s], res["0"][4][s])
         assert np.array_equal(res["1"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq, t))
+
+
+@pytest.mark.parametrize("part_rows", [1, 3, 5])
+def test_sentence_hashed_in_parts(part_rows, monkeypatch):
+    # sentences with many beams are hashed by several workgroups, each leaving a bitmap that the
+    # consumer ORs; LSHBEAM_PART_ROWS forces small parts so that the tiny shape takes this plan
+    monkeypatch.setenv("LSHBEAM_PART_ROWS", str(part_rows))
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)
+    rng = np.random.default_rng(part_rows)
+    for S, B in [(1, 4), (2, 17), (9, 17), (1, 40), (3, 20)]:      # fused and separate plans
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B)
+    gb, gw, gs, sp, ws = gc.step(H[:8], np.zeros(8, np.float32), 2, 4, T=0)
+    for s in range(2):
+        assert np.array_equal(gc.tables.debug_candidates(ws, sp, s),
+                              gc.index.candidates(H[4 * s:4 * s + 4], gc.topfreq[:0]))
+
+
+def test_paper_shape_wide_beams():
+    # the beam sizes of Table 8: more rows than one chunk of hashing holds
+    cfg, gc = case("paper")
+    H = hidden(cfg, gc, 8).reshape(-1, cfg.d)                     # 96 rows
+    rng = np.random.default_rng(8)
+    for S, B in [(1, 24), (1, 48), (2, 36), (3, 30)]:
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(B == 24))
 
 
 @pytest.mark.parametrize("grid", [1, 2, 3, 5, 8, 16])
@@ -378,10 +407,6 @@ def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
     osc = torch.full((1, 4), 42.0, device="cuda")
     sp = binding.step_params(1, 4, 50)
     ws = torch.empty(lsh.step_workspace_bytes(gc.tables, sp), dtype=torch.uint8, device="cuda")
-    with pytest.raises(lsh.LshBeamError) as e:
-        lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, binding.step_params(1, 4, 50, threshold=2),
-                        ws, ob, ow, osc)
-    assert e.value.status == 6                                  # t > 1 needs a larger workspace
     with pytest.raises(lsh.LshBeamError) as e:
         lsh.decode_step(gc.tables, H, bs, gc.topfreq_dev, binding.step_params(1, 4, 50, threshold=0),
                         ws, ob, ow, osc)

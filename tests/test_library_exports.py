@@ -28,7 +28,7 @@ def test_status_strings_and_kernel_names():
     lib = _lib()
     assert lib.lsh_status_string(0) == b"ok"
     assert lib.lsh_status_string(6) == b"workspace too small"
-    assert lsh.kernel_names() == ["k_candidates", "k_logits", "k_select", "k_hit_rows"]
+    assert lsh.kernel_names() == ["k_candidates", "k_logits", "k_select", "k_hit_rows", "k_part_bitmaps"]
 
 
 def test_null_arguments_are_rejected_without_a_gpu():
