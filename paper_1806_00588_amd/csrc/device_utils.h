@@ -57,6 +57,33 @@ __device__ __forceinline__ uint32_t wave_or(uint32_t v) {
     return wave_read_lane(v, kWave - 1);
 }
 
+// Wave-wide float reductions on the DPP network (same data movement as the scan: valid in lane
+// 63, returned wave-uniform).  Lanes that receive nothing keep the identity.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32_or(float v, float identity) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(identity), __float_as_int(v),
+                                                      CTRL, ROW_MASK, 0xf, false));
+}
+__device__ __forceinline__ float wave_max_f32(float v) {
+    const float ninf = -INFINITY;
+    v = fmaxf(v, dpp_f32_or<0x111, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_f32_or<0x112, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_f32_or<0x114, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_f32_or<0x118, 0xf>(v, ninf));
+    v = fmaxf(v, dpp_f32_or<0x142, 0xa>(v, ninf));
+    v = fmaxf(v, dpp_f32_or<0x143, 0xc>(v, ninf));
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));
+}
+__device__ __forceinline__ float wave_sum_f32(float v) {
+    v += dpp_f32_or<0x111, 0xf>(v, 0.f);
+    v += dpp_f32_or<0x112, 0xf>(v, 0.f);
+    v += dpp_f32_or<0x114, 0xf>(v, 0.f);
+    v += dpp_f32_or<0x118, 0xf>(v, 0.f);
+    v += dpp_f32_or<0x142, 0xa>(v, 0.f);
+    v += dpp_f32_or<0x143, 0xc>(v, 0.f);
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), kWave - 1));
+}
+
 // All-reduce inside each group of 16 consecutive lanes (a DPP "row"): xor-1 and xor-2 inside
 // quads, then the half-row and full-row mirrors.  Every lane of the group ends with the result.
 template <int CTRL>

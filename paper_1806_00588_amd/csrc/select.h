@@ -31,7 +31,9 @@ constexpr int kSelWaves = kSelThreads / kWave;
 constexpr int kSelListCap = 4096;    // short list of keys >= tau
 constexpr int kSelRankCap = 1024;    // keys ranked directly (== kSelThreads)
 constexpr int kSelRefineAbove = 256; // longer lists are thinned once more before ranking
-constexpr int kSelBatch = 4;         // tile partials in flight per lane
+constexpr int kSelBatch = 8;         // tile partials per lane and batch (a batch = 512 tiles of a row)
+constexpr int kSelKeep = 4;          // batches of tile maxima a wave keeps in registers for pass 2
+constexpr int kSelOpenCap = 4096;    // tiles whose maximum reaches tau (more: exact radix select)
 
 __device__ __forceinline__ uint64_t make_key(float v, uint32_t index) {
     return ((uint64_t)f32_sortable(v + 0.0f) << 32) | (uint64_t)(~index);
@@ -88,7 +90,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 struct SelShared {
-    int32_t open_tiles[kSelWaves][kSelBatch * kWave];  // per wave: tiles to open in this batch
+    uint32_t open_list[kSelOpenCap];  // tiles to open: row << 20 | tile (tile < 2^20 as V <= 2^24)
     uint64_t list[kSelListCap];
     uint32_t rank[kSelRankCap];
     uint32_t hist[256];
@@ -240,46 +242,81 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     const int C = count ? count[s] : V;
     const int ntiles = (C + 15) >> 4;
     const float* lg = logits + (size_t)s * B * cpitch;
-    if (tid == 0) sh.misc[4] = 0;
+    if (tid == 0) { sh.misc[4] = 0; sh.misc[5] = 0; }
 
-    // ---- per row (one wave each): log-sum-exp from the tile partials, and the lane's best
-    //      tile-maximum score.  All loads of a batch are issued before any is consumed. ----
+    // ---- per row: log-sum-exp from the tile partials, and the lane's best tile-maximum score.
+    //      Wave w takes rows w, w + 16, ...; a row is visited in batches of 512 tiles.  The
+    //      partials were written by other XCDs, so every load is a trip to memory: the next
+    //      batch (of this row or of the wave's next row) is requested before the current one is
+    //      reduced, and loads are never branched around (indices are clamped, padding is masked
+    //      after the load). ----
     uint32_t lmax = 0;
-    float2 p0[kSelBatch];  // first batch of the wave's first row: kept for the second pass
-    for (int i = wv; i < B; i += kSelWaves) {
-        const float2* pr = partials + ((size_t)s * B + i) * ppitch;
-        float m = -INFINITY, sum = 0.f, lmx = -INFINITY;
-        for (int t0 = 0; t0 < ntiles; t0 += kWave * kSelBatch) {
-            float2 p[kSelBatch];
+    // The tile maxima of the wave's first kSelKeep batches stay in registers for the second pass.
+    float keep[kSelKeep][kSelBatch];
+    constexpr int kBatchTiles = kWave * kSelBatch;
+    const int nb = (ntiles + kBatchTiles - 1) / kBatchTiles;                     // batches per row
+    const int nit = (wv < B ? (B - wv + kSelWaves - 1) / kSelWaves : 0) * nb;    // of this wave
+    // lanes x kSelBatch slots of a batch that hold tiles at all (wave-uniform; the rest is
+    // skipped outright: this kernel runs 16 waves on one CU and is bound by instruction issue)
+    auto slots_of = [&](int bt) { return min(kSelBatch, (ntiles - bt * kBatchTiles + kWave - 1) / kWave); };
+    auto load_batch = [&](int it, float2 (&p)[kSelBatch]) {
+        const int r = it / nb, bt = it - r * nb;
+        const int nq = slots_of(bt);
+        const float2* pr = partials + ((size_t)s * B + (wv + r * kSelWaves)) * ppitch;
 #pragma unroll
-            for (int q = 0; q < kSelBatch; ++q) {
-                const int t = t0 + ln + q * kWave;
-                p[q] = (t < ntiles) ? pr[t] : make_float2(-INFINITY, 0.f);
+        for (int q = 0; q < kSelBatch; ++q)
+            if (q < nq) p[q] = pr[min(bt * kBatchTiles + ln + q * kWave, ntiles - 1)];
+    };
+    {
+        float2 cur[kSelBatch], nxt[kSelBatch];
+        if (nit > 0) load_batch(0, cur);
+        float m = -INFINITY, sum = 0.f, lmx = -INFINITY, bsi = 0.f;
+        for (int it = 0; it < nit; ++it) {
+            const int r = it / nb, bt = it - r * nb;
+            const int i = wv + r * kSelWaves;
+            const int nq = slots_of(bt);
+            if (it + 1 < nit) load_batch(it + 1, nxt);
+            if (bt == 0) {
+                m = -INFINITY; sum = 0.f; lmx = -INFINITY;
+                bsi = beam_scores[s * B + i];
             }
-            if (i == wv && t0 == 0) {
 #pragma unroll
-                for (int q = 0; q < kSelBatch; ++q) p0[q] = p[q];
-            }
-            float bm = p[0].x;
+            for (int q = 0; q < kSelBatch; ++q)
+                if (q >= nq || bt * kBatchTiles + ln + q * kWave >= ntiles)
+                    cur[q] = make_float2(-INFINITY, 0.f);
 #pragma unroll
-            for (int q = 1; q < kSelBatch; ++q) bm = fmaxf(bm, p[q].x);
+            for (int k = 0; k < kSelKeep; ++k)  // registers cannot be indexed at run time
+                if (k == it) {
+#pragma unroll
+                    for (int q = 0; q < kSelBatch; ++q) keep[k][q] = cur[q].x;
+                }
+            float bm = cur[0].x;
+#pragma unroll
+            for (int q = 1; q < kSelBatch; ++q)
+                if (q < nq) bm = fmaxf(bm, cur[q].x);
             lmx = fmaxf(lmx, bm);
-            if (bm > m) { sum *= expf(m - bm); m = bm; }
+            if (bm > m) { sum *= __expf(m - bm); m = bm; }
             if (m != -INFINITY) {
 #pragma unroll
-                for (int q = 0; q < kSelBatch; ++q) sum += p[q].y * expf(p[q].x - m);  // padding: 0 * 0
+                for (int q = 0; q < kSelBatch; ++q)
+                    if (q < nq) sum += cur[q].y * __expf(cur[q].x - m);  // padding: 0 * 0
             }
+            if (bt == nb - 1) {
+                const float M = wave_max_f32(m);
+                const float part = wave_sum_f32((m == -INFINITY) ? 0.f : sum * __expf(m - M));
+                const float lse = M + logf(part);
+                if (ln == 0) { sh.lse[i] = lse; sh.bs[i] = bsi; lse_out[s * B + i] = lse; }
+                if (lmx != -INFINITY) lmax = max(lmax, f32_sortable(bsi + (lmx - lse) + 0.0f));
+            }
+#pragma unroll
+            for (int q = 0; q < kSelBatch; ++q) cur[q] = nxt[q];
         }
-        float M = m;
-#pragma unroll
-        for (int off = kWave / 2; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
-        float part = (m == -INFINITY) ? 0.f : sum * expf(m - M);
-#pragma unroll
-        for (int off = kWave / 2; off > 0; off >>= 1) part += __shfl_xor(part, off, kWave);
-        const float lse = M + logf(part);
-        const float bsi = beam_scores[s * B + i];
-        if (ln == 0) { sh.lse[i] = lse; sh.bs[i] = bsi; lse_out[s * B + i] = lse; }
-        if (lmx != -INFINITY) lmax = max(lmax, f32_sortable(bsi + (lmx - lse) + 0.0f));
+    }
+    if (nb == 0) {  // empty candidate list: every row's log-sum-exp is -inf
+        for (int i = wv; i < B; i += kSelWaves)
+            if (ln == 0) {
+                sh.lse[i] = -INFINITY; sh.bs[i] = beam_scores[s * B + i]; lse_out[s * B + i] = -INFINITY;
+            }
     }
     LSH_TRACE(2, 1);
 
@@ -303,61 +340,98 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
 
     // ---- second pass: tiles whose maximum reaches tau are opened, 16 lanes per tile ----
     const ScoreSrc src{lg, cpitch, B, C, sh.lse, sh.bs};
-    for (int i = wv; i < B; i += kSelWaves) {
-        const float2* pr = partials + ((size_t)s * B + i) * ppitch;
-        const float* row = lg + (size_t)i * cpitch;
+    // (a) every wave lists the tiles of its rows that qualify in one workgroup-wide LDS list:
+    //     which rows hold them is as uneven as the beam scores (the best beam's row can hold
+    //     nearly all), so they are opened by the whole workgroup, not by the row's wave
+    for (int it = 0; it < nit; ++it) {
+        const int r = it / nb, bt = it - r * nb;
+        const int i = wv + r * kSelWaves;
+        const int t0 = bt * kBatchTiles;
         const float lse = sh.lse[i], bsi = sh.bs[i];
-        for (int t0 = 0; t0 < ntiles; t0 += kWave * kSelBatch) {
-            float2 p[kSelBatch];
-            if (i == wv && t0 == 0) {
+        float px[kSelBatch];  // the batch's tile maxima
+        if (it < kSelKeep) {
 #pragma unroll
-                for (int q = 0; q < kSelBatch; ++q) p[q] = p0[q];
-            } else {
+            for (int k = 0; k < kSelKeep; ++k)
+                if (k == it) {
 #pragma unroll
-                for (int q = 0; q < kSelBatch; ++q) {
-                    const int t = t0 + ln + q * kWave;
-                    p[q] = (t < ntiles) ? pr[t] : make_float2(-INFINITY, 0.f);
+                    for (int q = 0; q < kSelBatch; ++q) px[q] = keep[k][q];
                 }
-            }
-            // tiles to open, compacted in (q, lane) order into the wave's LDS list
-            int32_t* ol = sh.open_tiles[wv];
-            uint32_t n_open = 0;
+        } else {
+            float2 p[kSelBatch];
+            load_batch(it, p);
+#pragma unroll
+            for (int q = 0; q < kSelBatch; ++q) px[q] = p[q].x;
+        }
+        // most batches hold no qualifying tile: one test on the lane's best of the batch
+        // settles that (this kernel is bound by instruction issue, 16 waves on one CU)
+        float best = px[0];
+#pragma unroll
+        for (int q = 1; q < kSelBatch; ++q) best = fmaxf(best, px[q]);
+        if (__ballot(f32_sortable(bsi + (best - lse) + 0.0f) >= tau) == 0) continue;
+        uint64_t bal[kSelBatch];
+        uint32_t n_mine = 0;
+#pragma unroll
+        for (int q = 0; q < kSelBatch; ++q) {
+            const int t = t0 + ln + q * kWave;
+            bal[q] = __ballot(t < ntiles && f32_sortable(bsi + (px[q] - lse) + 0.0f) >= tau);
+            n_mine += (uint32_t)__popcll(bal[q]);
+        }
+        if (n_mine) {  // wave-uniform
+            uint32_t base = 0;
+            if (ln == 0) base = atomicAdd(&sh.misc[5], n_mine);
+            base = wave_read_lane(base, 0);
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q) {
-                const int t = t0 + ln + q * kWave;
-                const bool open = t < ntiles && f32_sortable(bsi + (p[q].x - lse) + 0.0f) >= tau;
-                const uint64_t bal = __ballot(open);
-                if (open) ol[n_open + lanes_below(bal)] = t;
-                n_open += (uint32_t)__popcll(bal);
+                const uint32_t pos = base + lanes_below(bal[q]);
+                if (((bal[q] >> ln) & 1ull) && pos < (uint32_t)kSelOpenCap)
+                    sh.open_list[pos] = ((uint32_t)i << 20) | (uint32_t)(t0 + ln + q * kWave);
+                base += (uint32_t)__popcll(bal[q]);
             }
-            wave_lds_sync();
-            // 16 lanes per tile, 4 tiles per load, two loads in flight
-            for (uint32_t g0 = 0; g0 < n_open; g0 += 8) {
-                const uint32_t ja = g0 + (ln >> 4), jb = ja + 4;
-                const int ta = (ja < n_open) ? ol[ja] : -1;
-                const int tb = (jb < n_open) ? ol[jb] : -1;
-                const int ca = ta * 16 + (ln & 15), cb = tb * 16 + (ln & 15);
-                const bool va = ta >= 0 && ca < C, vb = tb >= 0 && cb < C;
-                const float xa = va ? row[ca] : -INFINITY;
-                const float xb = vb ? row[cb] : -INFINITY;
-                const float sa = bsi + (xa - lse), sb = bsi + (xb - lse);
-                if (va && f32_sortable(sa + 0.0f) >= tau) {
-                    const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
-                    if (pos < (uint32_t)kSelListCap)
-                        sh.list[pos] = make_key(sa, ((uint32_t)i << 24) | (uint32_t)ca);
-                }
-                if (vb && f32_sortable(sb + 0.0f) >= tau) {
-                    const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
-                    if (pos < (uint32_t)kSelListCap)
-                        sh.list[pos] = make_key(sb, ((uint32_t)i << 24) | (uint32_t)cb);
-                }
-            }
-            wave_lds_sync();
         }
+    }
+    LSH_TRACE(2, 6);
+    __syncthreads();
+    LSH_TRACE(2, 7);
+    // (b) 16 lanes per tile, 64 tiles per sweep of the workgroup, four sweeps in flight
+    const uint32_t n_open = sh.misc[5];
+    if (n_open <= (uint32_t)kSelOpenCap) {
+        for (uint32_t g0 = (uint32_t)(tid >> 4); g0 < n_open; g0 += 4 * (kSelThreads / 16)) {
+            float x[4], lsev[4], bsq[4];
+            int c[4], iq[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const uint32_t j = g0 + u * (kSelThreads / 16);
+                const uint32_t ent = sh.open_list[min(j, n_open - 1)];
+                iq[u] = (int)(ent >> 20);
+                const int cc = (int)(ent & 0xFFFFFu) * 16 + (ln & 15);
+                c[u] = (j < n_open && cc < C) ? cc : -1;
+                x[u] = lg[(size_t)iq[u] * cpitch + max(c[u], 0)];
+                lsev[u] = sh.lse[iq[u]];
+                bsq[u] = sh.bs[iq[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float sc = bsq[u] + (x[u] - lsev[u]);
+                if (c[u] >= 0 && f32_sortable(sc + 0.0f) >= tau) {
+                    const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
+                    if (pos < (uint32_t)kSelListCap)
+                        sh.list[pos] = make_key(sc, ((uint32_t)iq[u] << 24) | (uint32_t)c[u]);
+                }
+            }
+        }
+        LSH_TRACE(2, 8);
+    } else if (tid == 0) {
+        sh.misc[4] = kSelListCap + 1;  // too many qualifying tiles (heavy ties): exact select below
     }
     __syncthreads();
     int m = (int)sh.misc[4];
     LSH_TRACE(2, 3);
+#ifdef LSHBEAM_TRACE
+    if (blockIdx.x == 0 && tid == 0) {
+        g_trace[2][10] = g_trace[2][0] + n_open;  // counts, printed as offsets from slot 0
+        g_trace[2][11] = g_trace[2][0] + (unsigned)m;
+    }
+#endif
     // A long list (many near-equal tile maxima, e.g. many beams) is thinned once more with the
     // same argument applied to the list itself: thread t owns keys t, t+1024, ...; the B-th
     // largest thread maximum bounds the B-th largest key from below.
