@@ -157,7 +157,7 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
 
 // All row groups of one tile of candidates, the candidate rows being read once for up to four
 // groups (64 beams) at a time.
-template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int FIXED_MT = 0>
 __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, int64_t ld, int d,
                                                      const float* __restrict__ H, int B, int s,
                                                      int nt, int C, int64_t j,
@@ -167,9 +167,13 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
                                                      const float* h_lds = nullptr) {
     // loads in flight per row group shrink as the groups grow: the operands of all groups have
     // to fit the register budget of a 1024-thread workgroup
+    // (measured: keeping the full unroll in 256-thread workgroups, where registers would allow
+    // it, is slower -- the hidden-row loads of four groups then crowd out the candidate rows)
     constexpr int U4 = UNROLL >= 4 ? UNROLL / 4 : 1;
     constexpr int U2 = ElemTraits<ET>::VEC > 4 ? U4 : (UNROLL >= 2 ? UNROLL / 2 : 1);
-    const int MT = (B + kTileM - 1) / kTileM;
+    // FIXED_MT: the caller knows the number of row groups at compile time (only that case is
+    // instantiated, so its registers do not count against the others)
+    const int MT = FIXED_MT ? FIXED_MT : (B + kTileM - 1) / kTileM;
     if (MT == 1) {
         logits_tile<ET, WAVES, UNROLL, ALIGNED, 1>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
                                                    partials, ppitch, red, h_lds);
@@ -271,8 +275,8 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
 // however many beams there are.  Waves of a workgroup take consecutive tiles; the grid is
 // persistent.
 //
-// Whole rounds (every wave of the grid one tile) run this way.  A last round that would occupy
-// fewer than half of the waves is different: while all waves stream, the kernel runs at the
+// Whole rounds (every wave of the grid one tile) run this way.  A last (or only) round that would
+// occupy fewer than half of the waves is different: while all waves stream, the kernel runs at the
 // memory system's rate, but a few hundred waves left alone with a 64 KB tile each run at one
 // wave's latency-bound rate, and that tail was a sixth of the kernel.  Such a remainder is
 // therefore dealt to whole workgroups, whose four waves split k and sum their partial tiles
@@ -309,8 +313,7 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     const int nks = (d + KSTEP - 1) / KSTEP;
     // tiles [0, wave_tiles) one wave each; the rest one workgroup each
     const uint32_t whole = total_tiles / nwaves * nwaves;
-    const uint32_t wave_tiles =
-        (whole == 0 || (total_tiles - whole) * 2u > nwaves) ? total_tiles : whole;
+    const uint32_t wave_tiles = ((total_tiles - whole) * 2u > nwaves) ? total_tiles : whole;
     auto sentence_of = [&](uint32_t t) {
         int lo = 0, hi = S;  // last s with tile_pref[s] <= t
         while (hi - lo > 1) {
@@ -320,7 +323,12 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         return lo;
     };
 
-    for (uint32_t t = blockIdx.x * 4u + wv; t < wave_tiles; t += nwaves) {
+    // workgroup b takes the consecutive tiles [b * per_wg, (b + 1) * per_wg), dealt round-robin to
+    // its waves: neighbouring tiles (same sentence, same hidden rows in L1) stay together, and
+    // with fewer tiles than waves every workgroup (hence every CU) still gets its share
+    const uint32_t per_wg = (wave_tiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t wg_end = min(wave_tiles, (blockIdx.x + 1u) * per_wg);
+    for (uint32_t t = blockIdx.x * per_wg + wv; t < wg_end; t += 4u) {
         const int s = sentence_of(t);
         const int nt = (int)(t - tile_pref[s]);
         const int C = count ? count[s] : V;
@@ -402,7 +410,7 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int C = count ? count[s] : V;
         const int cidx = min(nt * kTileN + col, C - 1);
         const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
-        logits_tile_all_rows<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED>(E, ld, d, H, B, s, nt, C, j,
+        logits_tile_all_rows<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(E, ld, d, H, B, s, nt, C, j,
                                                                         logits, cpitch, partials,
                                                                         ppitch, red);
     }

@@ -199,7 +199,9 @@ int env_int(const char* name, int dflt) {
 bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
     const int MT = (sp->B + kTileM - 1) / kTileM;
     const bool possible = !sp->full_vocab && (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
-    const bool wanted = env_int("LSHBEAM_FUSED", sp->S * MT <= 8 ? 1 : 0) != 0;
+    // (with three or more groups of 16 beams the separate split-k kernel, one (tile, group) per
+    // workgroup at a time, is faster than the fused kernel's all-groups-per-tile loop)
+    const bool wanted = env_int("LSHBEAM_FUSED", (sp->S * MT <= 8 && MT <= 2) ? 1 : 0) != 0;
     return possible && wanted;
 }
 
