@@ -55,14 +55,17 @@ typedef struct {
     uint64_t seed;   /* seeds the cuckoo hash functions only (results never depend on it)        */
 } lsh_build_params;
 
-/* Build the index over the rows of E (once, after training; section "Cuckoo lookup", first step).
+/* Build the index over the rows of E (once, after training, or again whenever E changes; section
+ * "Cuckoo lookup", first step).
  *   E_dev      [V, ld_e] row-major, fp32 or bf16.  BORROWED: must stay valid and unchanged until
  *              lsh_free_tables; the decode step gathers its rows.
  *   perms_dev  int32 [P, K]: row p holds the first K entries of permutation p of 0..d-1
  *              (Eq. 5: Permute_p(x)[k] = x[perms[p][k]]).  Copied; validated to lie in [0, d).
  * Computes the band code of every row on the device (ties in the argmax go to the lowest k),
- * groups word ids by band code into one flat array per band (ids ascending inside a span) and
- * stores (start, length) of every span in a two-choice cuckoo table per band.
+ * groups word ids by band code into one flat array per band (ids ascending inside a span; one
+ * device radix sort over all bands) and stores (start, length) of every span in a two-choice
+ * cuckoo table per band (parallel insertion on the device; the host only draws the hash
+ * parameters and takes over if a band cannot be placed).
  * Synchronous.  On success *out receives the handle. */
 lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const lsh_build_params* p,
                             void* hip_stream, lsh_tables** out);
@@ -125,6 +128,12 @@ lsh_status lsh_debug_csr(const lsh_tables* t, int32_t band, int32_t* n_keys_out,
 /* Slots in one band's cuckoo table and keys stored (capacity is a power of two >= 2 * keys). */
 lsh_status lsh_debug_cuckoo_shape(const lsh_tables* t, int32_t band, int32_t* capacity_out,
                                   int32_t* n_keys_out);
+
+/* How the tables were built: *on_device_out = 1 if sort and cuckoo insertion ran on the device
+ * (0: on the host, after the device insertion had given up or by request); *attempts_out =
+ * insertion rounds the device made (bands whose insertion fails are redone with new hash
+ * parameters). */
+lsh_status lsh_debug_build_info(const lsh_tables* t, int32_t* on_device_out, int32_t* attempts_out);
 
 /* Candidate list of sentence s left in the workspace by the last LSH step on it. */
 lsh_status lsh_debug_candidates(const lsh_tables* t, const void* workspace_dev,

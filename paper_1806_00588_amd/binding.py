@@ -19,6 +19,7 @@ EXPORTED_SYMBOLS = (
     "lsh_debug_codes", "lsh_debug_embedding_codes", "lsh_debug_bucket", "lsh_debug_csr",
     "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profile_begin",
     "lsh_profile_end", "lsh_kernel_name", "lsh_status_string", "lsh_step_is_fused",
+    "lsh_debug_build_info",
 )
 
 
@@ -69,6 +70,8 @@ def load_library():
     lib.lsh_debug_bucket.argtypes = [vp, i32, i32, i32p, i32, i32p]
     lib.lsh_debug_csr.argtypes = [vp, i32, i32p, i32p, i32p, i32, i32p]
     lib.lsh_debug_cuckoo_shape.argtypes = [vp, i32, i32p, i32p]
+    lib.lsh_debug_build_info.argtypes = [vp, i32p, i32p]
+    lib.lsh_debug_build_info.restype = i32
     lib.lsh_debug_candidates.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32, i32p, i32, i32p]
     lib.lsh_debug_logprobs.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32,
                                        ctypes.POINTER(ctypes.c_float), i32, i32p]
@@ -181,6 +184,13 @@ class Tables:
         _check(lib.lsh_debug_csr(self.handle, band, ctypes.byref(nk), _i32p(keys), _i32p(offs),
                                  nk.value, _i32p(words)), "lsh_debug_csr")
         return keys, offs, words
+
+    def debug_build_info(self):
+        """(built on the device?, insertion rounds the device made)"""
+        dev, att = ctypes.c_int32(0), ctypes.c_int32(0)
+        _check(load_library().lsh_debug_build_info(self.handle, ctypes.byref(dev), ctypes.byref(att)),
+               "lsh_debug_build_info")
+        return bool(dev.value), att.value
 
     def debug_cuckoo_shape(self, band: int):
         cap, nk = ctypes.c_int32(0), ctypes.c_int32(0)

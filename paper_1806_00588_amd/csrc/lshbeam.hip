@@ -14,6 +14,9 @@
 #include <new>
 #include <vector>
 
+#include <hipcub/hipcub.hpp>
+
+#include "build_tables.h"
 #include "candidates.h"
 #include "fused.h"
 #include "logits.h"
@@ -57,12 +60,12 @@ struct lsh_tables {
     Slot* slots_dev = nullptr;       // all bands' cuckoo slots, concatenated
     BandMeta* bands_dev = nullptr;   // [W]
     std::vector<HostBand> bands;
-    std::vector<Slot> slots_host;
     int wg_candidates_lds = 0;
     int wg_fused_lds = 0;
     int wg_hit_rows_lds = 0;   // 0: the hit-count kernel cannot run on these tables (t > 1 unsupported)
     int hit_list_cap = 0;
     int wg_union_logits_lds = 0;
+    int built_on_device = 0, build_attempts = 0;  // how the tables came about (inspection)
     Profiler prof;
 };
 
@@ -287,6 +290,206 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
         }                                               \
     } while (0)
 
+// Host path of the table build: codes are copied back, every band's (code, id) pairs are sorted
+// and inserted into its cuckoo table on the host, then uploaded.
+lsh_status build_on_host(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
+    const size_t V = t->V, W = t->W;
+    (void)hipFree(t->words_dev); t->words_dev = nullptr;
+    (void)hipFree(t->slots_dev); t->slots_dev = nullptr;
+    (void)hipFree(t->bands_dev); t->bands_dev = nullptr;
+    t->bands.clear();
+    std::vector<Slot> slots_host;
+    std::vector<int32_t> codes(V * W);
+    HIP_TRY(hipMemcpyAsync(codes.data(), t->codes_dev, V * W * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    // per band: group word ids by code (ids ascending inside a span), then the cuckoo table
+    std::vector<int32_t> words(V * W);
+    std::vector<uint64_t> order(V);
+    t->bands.resize(W);
+    for (size_t w = 0; w < W; ++w) {
+        for (size_t j = 0; j < V; ++j)
+            order[j] = ((uint64_t)(uint32_t)codes[j * W + w] << 32) | (uint64_t)j;
+        std::sort(order.begin(), order.end());
+        HostBand& hb = t->bands[w];
+        for (size_t i = 0; i < V; ++i) {
+            const int32_t code = (int32_t)(order[i] >> 32);
+            if (i == 0 || code != hb.keys.back()) {
+                hb.keys.push_back(code);
+                hb.offsets.push_back((int32_t)i);
+            }
+            words[w * V + i] = (int32_t)(uint32_t)order[i];
+        }
+        hb.offsets.push_back((int32_t)V);
+        const lsh_status rc = build_cuckoo(hb, rng, slots_host, (uint32_t)slots_host.size());
+        if (rc != LSH_OK) return rc;
+    }
+    std::vector<BandMeta> metas(W);
+    for (size_t w = 0; w < W; ++w) metas[w] = t->bands[w].meta;
+
+    // 16 bytes of slack: k_hit_rows reads ids with 16-byte loads that may straddle the end
+    HIP_TRY(hipMalloc((void**)&t->words_dev, V * W * sizeof(int32_t) + 16));
+    HIP_TRY(hipMalloc((void**)&t->slots_dev, slots_host.size() * sizeof(Slot)));
+    HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
+    HIP_TRY(hipMemcpyAsync(t->words_dev, words.data(), V * W * sizeof(int32_t), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(t->slots_dev, slots_host.data(), slots_host.size() * sizeof(Slot),
+                           hipMemcpyHostToDevice, st));
+    HIP_TRY(hipMemcpyAsync(t->bands_dev, metas.data(), W * sizeof(BandMeta), hipMemcpyHostToDevice, st));
+    HIP_TRY(hipStreamSynchronize(st));
+
+    return LSH_OK;
+}
+
+struct DevBuf {  // temporary device memory of the build, released on every exit path
+    void* p = nullptr;
+    ~DevBuf() { (void)hipFree(p); }
+    template <typename T> T* as() const { return (T*)p; }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 1); }
+};
+
+inline int bits_for(uint64_t max_value) {  // bits needed to write max_value (at least 1)
+    int b = 1;
+    while (b < 64 && (max_value >> b)) ++b;
+    return b;
+}
+
+// Device path of the table build (build_tables.h).  LSH_ERR_BUILD_FAILED = some band could not
+// be inserted after all attempts (or the problem is too large for the 32-bit item counts of the
+// sort): the caller falls back to the host path.
+lsh_status build_on_device(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
+    const int64_t V = t->V, W = t->W, N = V * W;
+    if (N >= (int64_t)INT32_MAX) return LSH_ERR_BUILD_FAILED;
+    const SortKeyLayout lay{bits_for((uint64_t)V - 1), std::max(1, t->u * t->bits)};
+    const int key_bits = lay.id_bits + lay.code_bits + bits_for((uint64_t)W - 1);
+    const dim3 blk(256), grdN((unsigned)((N + 255) / 256));
+
+    DevBuf keys_a, keys_b, head, key_index, tmp;
+    HIP_TRY(keys_a.alloc(N * sizeof(uint64_t)));
+    HIP_TRY(keys_b.alloc(N * sizeof(uint64_t)));
+    HIP_TRY(head.alloc(N * sizeof(uint32_t)));
+    HIP_TRY(key_index.alloc(N * sizeof(uint32_t)));
+    hipLaunchKernelGGL(k_make_sort_keys, grdN, blk, 0, st, (const int32_t*)t->codes_dev, V, (int)W, lay,
+                       keys_a.as<uint64_t>());
+    size_t sort_bytes = 0, scan_bytes = 0;
+    HIP_TRY(hipcub::DeviceRadixSort::SortKeys(nullptr, sort_bytes, keys_a.as<uint64_t>(),
+                                              keys_b.as<uint64_t>(), (int)N, 0, key_bits, st));
+    HIP_TRY(hipcub::DeviceScan::ExclusiveSum(nullptr, scan_bytes, head.as<uint32_t>(),
+                                             key_index.as<uint32_t>(), (int)N, st));
+    HIP_TRY(tmp.alloc(std::max(sort_bytes, scan_bytes)));
+    HIP_TRY(hipcub::DeviceRadixSort::SortKeys(tmp.p, sort_bytes, keys_a.as<uint64_t>(),
+                                              keys_b.as<uint64_t>(), (int)N, 0, key_bits, st));
+    // 16 bytes of slack: k_hit_rows reads ids with 16-byte loads that may straddle the end
+    HIP_TRY(hipMalloc((void**)&t->words_dev, N * sizeof(int32_t) + 16));
+    hipLaunchKernelGGL(k_split_sorted, grdN, blk, 0, st, (const uint64_t*)keys_b.p, V, (int)W, lay,
+                       t->words_dev, head.as<uint32_t>());
+    HIP_TRY(hipcub::DeviceScan::ExclusiveSum(tmp.p, scan_bytes, head.as<uint32_t>(),
+                                             key_index.as<uint32_t>(), (int)N, st));
+    // keys per band: the scan value at each band's first position, and the total
+    std::vector<uint32_t> first_key(W + 1);
+    uint32_t last_index = 0, last_head = 0;
+    HIP_TRY(hipMemcpy2DAsync(first_key.data(), sizeof(uint32_t), key_index.p, (size_t)V * sizeof(uint32_t),
+                             sizeof(uint32_t), (size_t)W, hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&last_index, key_index.as<uint32_t>() + (N - 1), sizeof(uint32_t),
+                           hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(&last_head, head.as<uint32_t>() + (N - 1), sizeof(uint32_t),
+                           hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    const uint32_t n_keys = last_index + last_head;
+    first_key[W] = n_keys;
+
+    DevBuf key_code, key_start, key_band, key_len;
+    HIP_TRY(key_code.alloc(n_keys * sizeof(int32_t)));
+    HIP_TRY(key_start.alloc(n_keys * sizeof(uint32_t)));
+    HIP_TRY(key_band.alloc(n_keys * sizeof(int32_t)));
+    HIP_TRY(key_len.alloc(n_keys * sizeof(uint32_t)));
+    hipLaunchKernelGGL(k_emit_keys, grdN, blk, 0, st, (const uint64_t*)keys_b.p, (const uint32_t*)head.p,
+                       (const uint32_t*)key_index.p, V, (int)W, lay, key_code.as<int32_t>(),
+                       key_start.as<uint32_t>(), key_band.as<int32_t>());
+    const dim3 grdK((n_keys + 255) / 256);
+    hipLaunchKernelGGL(k_key_lengths, grdK, blk, 0, st, (const uint32_t*)key_start.p,
+                       (const int32_t*)key_band.p, n_keys, (uint32_t)V, key_len.as<uint32_t>());
+
+    // table geometry: a power of two of at least three slots per key and band (load <= 1/3:
+    // two-choice cuckoo insertion then succeeds at the first attempt almost always)
+    t->bands.assign(W, HostBand{});
+    std::vector<BandMeta> metas(W);
+    std::vector<uint32_t> caps(W), flags(W, 0u);
+    uint64_t n_slots = 0;
+    int max_lg = 1;
+    for (int64_t w = 0; w < W; ++w) {
+        const uint32_t nk = first_key[w + 1] - first_key[w];
+        int lg = 1;
+        while ((uint64_t)(1u << lg) < 3ull * nk) ++lg;
+        max_lg = std::max(max_lg, lg);
+        caps[w] = 1u << lg;
+        metas[w] = BandMeta{};
+        metas[w].slot_off = (uint32_t)n_slots;
+        metas[w].shift = 32u - (uint32_t)lg;
+        n_slots += caps[w];
+    }
+    if (n_slots >= (1ull << 32)) return LSH_ERR_BUILD_FAILED;
+    auto draw = [&](BandMeta& m) {
+        m.a0 = (uint32_t)rng.next() | 1u; m.b0 = (uint32_t)rng.next();
+        m.a1 = (uint32_t)rng.next() | 1u; m.b1 = (uint32_t)rng.next();
+    };
+    for (auto& m : metas) draw(m);
+
+    DevBuf table, caps_dev, redo_dev, failed_dev;
+    HIP_TRY(table.alloc(n_slots * sizeof(uint64_t)));
+    HIP_TRY(caps_dev.alloc(W * sizeof(uint32_t)));
+    HIP_TRY(redo_dev.alloc(W * sizeof(uint32_t)));
+    HIP_TRY(failed_dev.alloc(W * sizeof(uint32_t)));
+    HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
+    HIP_TRY(hipMalloc((void**)&t->slots_dev, n_slots * sizeof(Slot)));
+    HIP_TRY(hipMemcpyAsync(caps_dev.p, caps.data(), W * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+    const dim3 grdClear((unsigned)std::min<uint64_t>(64, ((1ull << max_lg) + 255) / 256), (unsigned)W);
+    // LSHBEAM_CUCKOO_CHAIN shortens the eviction chains (tests of the retry and fallback paths)
+    const int max_chain = env_int("LSHBEAM_CUCKOO_CHAIN", 16 * (max_lg + 1));
+    bool done = false;
+    for (int attempt = 0; attempt < 24 && !done; ++attempt) {
+        t->build_attempts = attempt + 1;
+        const uint32_t* redo = attempt ? redo_dev.as<uint32_t>() : nullptr;
+        HIP_TRY(hipMemcpyAsync(t->bands_dev, metas.data(), W * sizeof(BandMeta), hipMemcpyHostToDevice, st));
+        HIP_TRY(hipMemsetAsync(failed_dev.p, 0, W * sizeof(uint32_t), st));
+        hipLaunchKernelGGL(k_cuckoo_clear, grdClear, blk, 0, st, table.as<uint64_t>(),
+                           (const BandMeta*)t->bands_dev, (const uint32_t*)caps_dev.p, (int)W, redo);
+        if (n_keys)
+            hipLaunchKernelGGL(k_cuckoo_insert, grdK, blk, 0, st, table.as<uint64_t>(),
+                               (const BandMeta*)t->bands_dev, (const int32_t*)key_code.p,
+                               (const int32_t*)key_band.p, n_keys, max_chain, redo,
+                               failed_dev.as<uint32_t>());
+        HIP_TRY(hipMemcpyAsync(flags.data(), failed_dev.p, W * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+        HIP_TRY(hipStreamSynchronize(st));
+        done = true;
+        for (int64_t w = 0; w < W; ++w)
+            if (flags[w]) { done = false; draw(metas[w]); }
+        if (!done)
+            HIP_TRY(hipMemcpyAsync(redo_dev.p, flags.data(), W * sizeof(uint32_t), hipMemcpyHostToDevice, st));
+    }
+    if (!done) return LSH_ERR_BUILD_FAILED;
+    hipLaunchKernelGGL(k_cuckoo_finalize, dim3((unsigned)((n_slots + 255) / 256)), blk, 0, st,
+                       (const uint64_t*)table.p, n_slots, (const uint32_t*)key_start.p,
+                       (const uint32_t*)key_len.p, t->slots_dev);
+    HIP_TRY(hipGetLastError());
+
+    // host mirrors for the inspection calls: distinct codes and span boundaries of every band
+    std::vector<int32_t> codes_h(n_keys);
+    std::vector<uint32_t> starts_h(n_keys);
+    HIP_TRY(hipMemcpyAsync(codes_h.data(), key_code.p, n_keys * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipMemcpyAsync(starts_h.data(), key_start.p, n_keys * sizeof(uint32_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int64_t w = 0; w < W; ++w) {
+        HostBand& hb = t->bands[w];
+        hb.keys.assign(codes_h.begin() + first_key[w], codes_h.begin() + first_key[w + 1]);
+        hb.offsets.assign(starts_h.begin() + first_key[w], starts_h.begin() + first_key[w + 1]);
+        hb.offsets.push_back((int32_t)V);
+        hb.capacity = (int)caps[w];
+        hb.meta = metas[w];
+    }
+    t->built_on_device = 1;
+    return LSH_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -375,44 +578,12 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
                                t->ld, (int64_t)V, t->perms_dev, t->P, t->K, t->W, bits, t->codes_dev);
         HIP_TRY(hipGetLastError());
     }
-    std::vector<int32_t> codes(V * W);
-    HIP_TRY(hipMemcpyAsync(codes.data(), t->codes_dev, V * W * sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
-
-    // per band: group word ids by code (ids ascending inside a span), then the cuckoo table
-    std::vector<int32_t> words(V * W);
-    std::vector<uint64_t> order(V);
-    t->bands.resize(W);
+    // bucket tables + cuckoo tables: on the device; LSHBEAM_HOST_BUILD=1 (tests) or a band that
+    // keeps failing its insertion takes the host path instead
     SplitMix64 rng{p->seed ^ 0xC0FFEE1234ABCDEFull};
-    for (size_t w = 0; w < W; ++w) {
-        for (size_t j = 0; j < V; ++j)
-            order[j] = ((uint64_t)(uint32_t)codes[j * W + w] << 32) | (uint64_t)j;
-        std::sort(order.begin(), order.end());
-        HostBand& hb = t->bands[w];
-        for (size_t i = 0; i < V; ++i) {
-            const int32_t code = (int32_t)(order[i] >> 32);
-            if (i == 0 || code != hb.keys.back()) {
-                hb.keys.push_back(code);
-                hb.offsets.push_back((int32_t)i);
-            }
-            words[w * V + i] = (int32_t)(uint32_t)order[i];
-        }
-        hb.offsets.push_back((int32_t)V);
-        const lsh_status rc = build_cuckoo(hb, rng, t->slots_host, (uint32_t)t->slots_host.size());
-        if (rc != LSH_OK) return rc;
-    }
-    std::vector<BandMeta> metas(W);
-    for (size_t w = 0; w < W; ++w) metas[w] = t->bands[w].meta;
-
-    // 16 bytes of slack: k_hit_rows reads ids with 16-byte loads that may straddle the end
-    HIP_TRY(hipMalloc((void**)&t->words_dev, V * W * sizeof(int32_t) + 16));
-    HIP_TRY(hipMalloc((void**)&t->slots_dev, t->slots_host.size() * sizeof(Slot)));
-    HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
-    HIP_TRY(hipMemcpyAsync(t->words_dev, words.data(), V * W * sizeof(int32_t), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(t->slots_dev, t->slots_host.data(), t->slots_host.size() * sizeof(Slot),
-                           hipMemcpyHostToDevice, st));
-    HIP_TRY(hipMemcpyAsync(t->bands_dev, metas.data(), W * sizeof(BandMeta), hipMemcpyHostToDevice, st));
-    HIP_TRY(hipStreamSynchronize(st));
+    lsh_status brc = env_int("LSHBEAM_HOST_BUILD", 0) ? LSH_ERR_BUILD_FAILED : build_on_device(t, st, rng);
+    if (brc == LSH_ERR_BUILD_FAILED) brc = build_on_host(t, st, rng);
+    if (brc != LSH_OK) return brc;
 
     t->wg_candidates_lds = (int)(candidates_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
     if (t->wg_candidates_lds > 48 * 1024)
@@ -607,6 +778,13 @@ lsh_status lsh_debug_csr(const lsh_tables* t, int32_t band, int32_t* n_keys_out,
     if (words_host)
         HIP_TRY(hipMemcpy(words_host, t->words_dev + (size_t)band * t->V, (size_t)t->V * sizeof(int32_t),
                           hipMemcpyDeviceToHost));
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_build_info(const lsh_tables* t, int32_t* on_device_out, int32_t* attempts_out) {
+    if (!t || !on_device_out || !attempts_out) return LSH_ERR_INVALID_ARG;
+    *on_device_out = t->built_on_device;
+    *attempts_out = t->build_attempts;
     return LSH_OK;
 }
 

@@ -70,6 +70,48 @@ def test_buckets_through_cuckoo_bit_exact(name, max_keys):
             assert gc.tables.debug_bucket(w, code) is None
 
 
+@pytest.mark.parametrize("env", [{"LSHBEAM_HOST_BUILD": "1"}, {"LSHBEAM_CUCKOO_CHAIN": "4"},
+                                 {"LSHBEAM_CUCKOO_CHAIN": "8"}, {"LSHBEAM_CUCKOO_CHAIN": "1"}])
+@pytest.mark.parametrize("name", ["tiny", "paper"])
+def test_table_build_paths_agree(name, env, monkeypatch):
+    # default: sort + parallel cuckoo insertion on the device.  Host build, device build with
+    # eviction chains so short that bands must be redone with new hash parameters, and chains of
+    # one (any collision fails the band: on the tiny shape the host path takes over after all
+    # attempts; on the paper shape multiplicative hashing of 12-bit codes into 2^14 slots happens
+    # to be collision-free) must all give the same bucket layout and the same answers through
+    # their own cuckoo tables.
+    cfg, gc = case(name)
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    other = GpuCase.from_config(cfg)
+    assert gc.tables.debug_build_info() == (True, 1)               # load <= 1/3: first attempt
+    on_device, attempts = other.tables.debug_build_info()
+    if "LSHBEAM_HOST_BUILD" in env:
+        assert (on_device, attempts) == (False, 0)
+    else:
+        # short chains: bands are redone with new hash parameters until all fit (or, after 24
+        # rounds, the host takes over)
+        assert (on_device and 1 <= attempts <= 24) or (not on_device and attempts == 24)
+        print(name, env, "on_device", on_device, "attempts", attempts)
+    for w in range(cfg.W):
+        k0, o0, w0 = gc.tables.debug_csr(w)
+        k1, o1, w1 = other.tables.debug_csr(w)
+        assert np.array_equal(k0, k1) and np.array_equal(o0, o1) and np.array_equal(w0, w1)
+        for i in range(len(k0)):
+            assert np.all(np.diff(w0[o0[i]:o0[i + 1]]) > 0)          # ids ascending inside a span
+        cap, nk = other.tables.debug_cuckoo_shape(w)
+        assert nk == len(k1) and cap >= 2 * nk and cap & (cap - 1) == 0
+        for code in k0[:: max(1, len(k0) // 64)]:
+            assert np.array_equal(other.tables.debug_bucket(w, int(code)), w0[o0[np.searchsorted(k0, code)]:
+                                                                            o0[np.searchsorted(k0, code) + 1]])
+    H = hidden(cfg, gc, 1)[0]
+    bs = np.zeros(cfg.R, np.float32)
+    a = gc.step(H, bs, cfg.S, cfg.B)
+    b = other.step(H, bs, cfg.S, cfg.B)
+    for x, y in zip(a[:3], b[:3]):
+        assert np.array_equal(x, y)
+
+
 def test_cuckoo_with_wide_band_codes():
     # 24-bit band codes (K=64, u=4): far too many possible codes for direct addressing
     rng = np.random.default_rng(11)
