@@ -30,13 +30,14 @@ def log(*a):
 
 def measured_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
-    path = os.path.join(ROOT, "profiles", f"k_cand_logits_{workload}_pmc.md")
-    try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1].split()[0])
-    except OSError:
-        pass
+    for kernel in ("k_cand_logits", "k_logits_wave"):
+        path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.md")
+        try:
+            for line in open(path):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].split()[0])
+        except OSError:
+            pass
     return None
 
 
@@ -193,7 +194,9 @@ def main():
     achieved = alg_bytes / (k_ms * 1e-3) / 1e9 if k_ms > 0 else 0.0
     flops = 2.0 * B * mean_rows * cfg.d
     fused = binding.step_is_fused(tables, sp)
-    dominant = "k_cand_logits (candidate generation fused into the logits kernel)" if fused \
+    pre_hashed = prof["k_hit_rows"][1] > 0 or prof["k_part_bitmaps"][1] > 0
+    fused_name = "k_union_logits" if pre_hashed else "k_cand_logits"
+    dominant = (fused_name + " (candidate generation fused into the logits kernel)") if fused \
         else "k_logits"
     roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
@@ -250,6 +253,7 @@ def main():
                   "algorithmic_bytes_per_launch": bbytes,
                   "achieved_GBps": round(bbytes / (bms * 1e-3) / 1e9, 1),
                   "frac_of_hbm_peak": round(bbytes / (bms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                  "traffic": measured_traffic("batched"),
                   "kernels_us": {k: round(v[0] * 1e3, 2) for k, v in bprof.items()}}
         log(f"[bench] bandwidth regime ({regime['workload']}): k_logits {bms*1e3:.1f} us, "
             f"{regime['achieved_GBps']} GB/s = {regime['frac_of_hbm_peak']*100:.1f}% of HBM peak")
@@ -288,7 +292,7 @@ def main():
                                f"W={cfg.W} T={cfg.T} t={cfg.threshold}, {nst}-step sentences, seed 0",
                    "mode": args.mode, "mean_candidates_per_sentence": round(mean_rows / S, 1)},
         "roofline": roofline,
-        "kernels_us": {("k_cand_logits" if (fused and k == "k_logits") else k): round(v[0] * 1e3, 3)
+        "kernels_us": {(fused_name if (fused and k == "k_logits") else k): round(v[0] * 1e3, 3)
                        for k, v in prof.items() if v[1]},
         "full_vocab": full,
         "bandwidth_regime": regime,
