@@ -52,6 +52,8 @@ def main():
                          "stream: launch every step from the host")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-full-vocab", action="store_true")
+    ap.add_argument("--no-bookkeeping", action="store_true",
+                    help="skip the extra measurement of the step followed by lsh_beam_advance")
     ap.add_argument("--no-regime", action="store_true",
                     help="skip the extra bandwidth-regime measurement (the logits kernel on the "
                          "32-sentence 'batched' shape, same embeddings and tables)")
@@ -259,6 +261,31 @@ def main():
             f"{regime['achieved_GBps']} GB/s = {regime['frac_of_hbm_peak']*100:.1f}% of HBM peak")
         del Hb, bws
 
+    # ---- the step followed by the beam bookkeeping (state reorder of a 2-layer LSTM: h and c of
+    #      both layers, history, next scores): what a decoder loop adds around the hot path -------
+    book = None
+    if not args.no_bookkeeping:
+        hist = binding.BeamHistory(S, B, nst, n_states=4, state_dim=cfg.d, eos=-1)
+        st_bufs = [[torch.randn(R, cfg.d, device="cuda") for _ in range(4)] for _ in range(2)]
+        call = binding.make_step_caller(tables, sp, ws, tf_dev)
+
+        def run_book(first: int, n: int, stream_ptr_: int):
+            for i in range(first, first + n):
+                st = i % nst
+                a, b2 = st & 1, (st + 1) & 1
+                call(h_ptrs[st], zero.data_ptr() if st == 0 else score[a].data_ptr(), ob.data_ptr(),
+                     ow.data_ptr(), score[b2].data_ptr(), stream_ptr_)
+                # scores for the next step are written by the bookkeeping call (in place: the
+                # kernel reads out_score[r] and writes next_scores[r] in the same thread)
+                binding.beam_advance(hist, st, ob, ow, score[b2], st_bufs[a], st_bufs[b2], score[b2],
+                                     stream=stream_ptr_)
+        kb = max(nst, min(K, 1000) // nst * nst)
+        bsecs, _ = time_region(run_book, kb, args.mode)
+        book = {"steps": kb, "ms_per_step": round(bsecs / kb * 1e3, 6),
+                "steps_per_s": round(kb / bsecs, 1), "state_arrays": 4, "state_dim": cfg.d,
+                "extra_us_per_step": round((bsecs / kb - secs / K) * 1e6, 2)}
+        log(f"[bench] {cfg.name} step + lsh_beam_advance (4 state arrays): {bsecs/kb*1e6:.2f} us/step")
+
     # ---- the oracle on the host cores, bounded sample -----------------------------------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -296,6 +323,7 @@ def main():
                        for k, v in prof.items() if v[1]},
         "full_vocab": full,
         "bandwidth_regime": regime,
+        "with_bookkeeping": book,
         "step_bytes_over_step_time_GBps": round(alg_bytes / secs * K / 1e9, 1),
         "cpu_baseline": cpu,
     }

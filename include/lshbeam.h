@@ -106,6 +106,46 @@ lsh_status lsh_decode_step(const lsh_tables* t, const float* H_dev, const float*
                            void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
                            int32_t* out_word_dev, float* out_score_dev, void* hip_stream);
 
+/* ---- beam bookkeeping around the step (Introduction, "Beam expansion"; Table 1, row "Hidden
+ *      states reorder") ----------------------------------------------------------------------- */
+
+typedef struct {
+    int32_t S, B;      /* as in lsh_step_params                                                   */
+    int32_t n_states;  /* recurrent state arrays reordered per step, 0 .. 16 (a 2-layer LSTM: 4)  */
+    int32_t state_dim; /* fp32 values per row of every state array                                */
+    int32_t eos;       /* word id that ends a hypothesis, or -1 for none                          */
+    int32_t max_len;   /* time steps the history arrays hold                                      */
+} lsh_beam_params;
+
+/* After lsh_decode_step at time step `step` (0-based): slot b of sentence s continues parent beam
+ * p = out_beam[s, b] with word w = out_word[s, b].  For every state array k:
+ *   states_out[k][s*B + b, :] = states_in[k][s*B + p, :]   (zeros for an empty slot, p = -1);
+ * the choice is recorded, backptr[step, s, b] = p, words[step, s, b] = w, scores[step, s, b] =
+ * out_score[s, b]; and the accumulated scores for the next step are written:
+ *   next_scores[s, b] = out_score[s, b], or -inf if w == eos or the slot is empty
+ * (a finished hypothesis is never expanded again; it stays in the history for the backtrace).
+ *   states_in / states_out   HOST arrays of n_states DEVICE pointers, each [S*B, state_dim] fp32,
+ *                            pitch state_dim; an array must not be its own output.
+ *   backptr_dev, words_dev, scores_dev   device [max_len, S, B] (int32, int32, fp32), caller-owned.
+ *   next_scores_dev          device fp32 [S*B]: the beam_scores of the next step; may be
+ *                            out_score_dev itself (each entry is read before it is written).
+ * Asynchronous on the stream, allocates nothing, one kernel. */
+lsh_status lsh_beam_advance(const lsh_beam_params* bp, int32_t step, const int32_t* out_beam_dev,
+                            const int32_t* out_word_dev, const float* out_score_dev,
+                            const float* const* states_in, float* const* states_out,
+                            int32_t* backptr_dev, int32_t* words_dev, float* scores_dev,
+                            float* next_scores_dev, void* hip_stream);
+
+/* After n_steps recorded steps: per sentence the best finished hypothesis (a slot whose word is
+ * eos) over all steps -- highest score, then earliest step, then lowest slot -- or, if none
+ * finished, the best slot of the last step; its words in order, found by walking the parent
+ * pointers back to step 0.
+ *   tokens_dev int32 [S, max_len] (only the first length[s] entries of a row are written),
+ *   length_dev int32 [S] (0 if nothing was recorded), best_score_dev fp32 [S]. */
+lsh_status lsh_beam_backtrace(const lsh_beam_params* bp, int32_t n_steps, const int32_t* backptr_dev,
+                              const int32_t* words_dev, const float* scores_dev, int32_t* tokens_dev,
+                              int32_t* length_dev, float* best_score_dev, void* hip_stream);
+
 /* ---- inspection (synchronous device-to-host copies; never on the timed path) ---------------- */
 
 /* Band codes (Eq. 6-8) of R fp32 rows of pitch d, computed by the same device hash routine the

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = (
     "lsh_debug_codes", "lsh_debug_embedding_codes", "lsh_debug_bucket", "lsh_debug_csr",
     "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profile_begin",
     "lsh_profile_end", "lsh_kernel_name", "lsh_status_string", "lsh_step_is_fused",
-    "lsh_debug_build_info",
+    "lsh_debug_build_info", "lsh_beam_advance", "lsh_beam_backtrace",
 )
 
 
@@ -33,6 +33,11 @@ class BuildParams(ctypes.Structure):
     _fields_ = [("V", ctypes.c_int32), ("d", ctypes.c_int32), ("ld_e", ctypes.c_int64),
                 ("e_dtype", ctypes.c_int32), ("K", ctypes.c_int32), ("P", ctypes.c_int32),
                 ("bands", ctypes.c_int32), ("seed", ctypes.c_uint64)]
+
+
+class BeamParams(ctypes.Structure):
+    _fields_ = [("S", ctypes.c_int32), ("B", ctypes.c_int32), ("n_states", ctypes.c_int32),
+                ("state_dim", ctypes.c_int32), ("eos", ctypes.c_int32), ("max_len", ctypes.c_int32)]
 
 
 class StepParams(ctypes.Structure):
@@ -71,6 +76,11 @@ def load_library():
     lib.lsh_debug_csr.argtypes = [vp, i32, i32p, i32p, i32p, i32, i32p]
     lib.lsh_debug_cuckoo_shape.argtypes = [vp, i32, i32p, i32p]
     lib.lsh_debug_build_info.argtypes = [vp, i32p, i32p]
+    lib.lsh_beam_advance.argtypes = [ctypes.POINTER(BeamParams), i32, vp, vp, vp, ctypes.POINTER(vp),
+                                     ctypes.POINTER(vp), vp, vp, vp, vp, vp]
+    lib.lsh_beam_advance.restype = i32
+    lib.lsh_beam_backtrace.argtypes = [ctypes.POINTER(BeamParams), i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.lsh_beam_backtrace.restype = i32
     lib.lsh_debug_build_info.restype = i32
     lib.lsh_debug_candidates.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32, i32p, i32, i32p]
     lib.lsh_debug_logprobs.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32,
@@ -109,6 +119,8 @@ def _i32p(a: np.ndarray):
 
 def _stream_ptr(stream) -> int:
     import torch
+    if isinstance(stream, int):  # a raw hipStream_t
+        return stream
     if stream is None:
         stream = torch.cuda.current_stream()
     return int(stream.cuda_stream)
@@ -308,3 +320,42 @@ def make_step_caller(tables: Tables, sp: StepParams, workspace, topfreq):
             raise LshBeamError(rc, "lsh_decode_step")
 
     return call
+
+
+class BeamHistory:
+    """Caller-owned device arrays of the beam bookkeeping calls (torch is only the allocator)."""
+
+    def __init__(self, S: int, B: int, max_len: int, n_states: int = 0, state_dim: int = 0, eos: int = -1):
+        import torch
+        self.bp = BeamParams(S, B, n_states, state_dim, eos, max_len)
+        self.backptr = torch.empty((max_len, S, B), dtype=torch.int32, device="cuda")
+        self.words = torch.empty((max_len, S, B), dtype=torch.int32, device="cuda")
+        self.scores = torch.empty((max_len, S, B), dtype=torch.float32, device="cuda")
+
+
+def beam_advance(hist: BeamHistory, step: int, out_beam, out_word, out_score, states_in, states_out,
+                 next_scores, stream=None) -> None:
+    """lsh_beam_advance; states_in / states_out are sequences of device tensors [S*B, state_dim]."""
+    n = hist.bp.n_states
+    assert len(states_in) == n and len(states_out) == n
+    pin = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in states_in])
+    pout = (ctypes.c_void_p * max(n, 1))(*[t.data_ptr() for t in states_out])
+    _check(load_library().lsh_beam_advance(ctypes.byref(hist.bp), step, out_beam.data_ptr(),
+                                           out_word.data_ptr(), out_score.data_ptr(), pin, pout,
+                                           hist.backptr.data_ptr(), hist.words.data_ptr(),
+                                           hist.scores.data_ptr(), next_scores.data_ptr(),
+                                           _stream_ptr(stream)), "lsh_beam_advance")
+
+
+def beam_backtrace(hist: BeamHistory, n_steps: int, stream=None):
+    """lsh_beam_backtrace -> (tokens [S, max_len] int32, length [S] int32, score [S] fp32), device."""
+    import torch
+    S, L = hist.bp.S, hist.bp.max_len
+    tokens = torch.full((S, L), -1, dtype=torch.int32, device="cuda")
+    length = torch.empty(S, dtype=torch.int32, device="cuda")
+    score = torch.empty(S, dtype=torch.float32, device="cuda")
+    _check(load_library().lsh_beam_backtrace(ctypes.byref(hist.bp), n_steps, hist.backptr.data_ptr(),
+                                             hist.words.data_ptr(), hist.scores.data_ptr(),
+                                             tokens.data_ptr(), length.data_ptr(), score.data_ptr(),
+                                             _stream_ptr(stream)), "lsh_beam_backtrace")
+    return tokens, length, score

@@ -16,6 +16,7 @@
 
 #include <hipcub/hipcub.hpp>
 
+#include "beam.h"
 #include "build_tables.h"
 #include "candidates.h"
 #include "fused.h"
@@ -873,6 +874,48 @@ lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
         launches_out[k] = pf.used[k];
         mean_ms_out[k] = pf.used[k] ? total / pf.used[k] : 0.0;
     }
+    return LSH_OK;
+}
+
+lsh_status lsh_beam_advance(const lsh_beam_params* bp, int32_t step, const int32_t* out_beam_dev,
+                            const int32_t* out_word_dev, const float* out_score_dev,
+                            const float* const* states_in, float* const* states_out,
+                            int32_t* backptr_dev, int32_t* words_dev, float* scores_dev,
+                            float* next_scores_dev, void* hip_stream) {
+    if (!bp || !out_beam_dev || !out_word_dev || !out_score_dev || !backptr_dev || !words_dev ||
+        !scores_dev || !next_scores_dev)
+        return LSH_ERR_INVALID_ARG;
+    if (bp->S < 1 || bp->B < 1 || bp->B > kMaxB || (int64_t)bp->S * bp->B > INT32_MAX / 2 ||
+        bp->n_states < 0 || bp->n_states > kMaxBeamStates || bp->max_len < 1 || step < 0 ||
+        step >= bp->max_len || (bp->n_states > 0 && (bp->state_dim < 1 || !states_in || !states_out)))
+        return LSH_ERR_INVALID_ARG;
+    BeamStatePtrs ptrs{};
+    for (int k = 0; k < bp->n_states; ++k) {
+        if (!states_in[k] || !states_out[k] || states_in[k] == states_out[k]) return LSH_ERR_INVALID_ARG;
+        ptrs.in[k] = states_in[k];
+        ptrs.out[k] = states_out[k];
+    }
+    const size_t R = (size_t)bp->S * bp->B, off = (size_t)step * R;
+    hipLaunchKernelGGL(k_beam_advance, dim3((unsigned)R, (unsigned)std::max(bp->n_states, 1)), dim3(256), 0,
+                       (hipStream_t)hip_stream, ptrs, (int)bp->n_states, (int)bp->state_dim, (int)bp->B,
+                       (int)bp->eos, out_beam_dev, out_word_dev, out_score_dev, backptr_dev + off,
+                       words_dev + off, scores_dev + off, next_scores_dev);
+    HIP_TRY(hipGetLastError());
+    return LSH_OK;
+}
+
+lsh_status lsh_beam_backtrace(const lsh_beam_params* bp, int32_t n_steps, const int32_t* backptr_dev,
+                              const int32_t* words_dev, const float* scores_dev, int32_t* tokens_dev,
+                              int32_t* length_dev, float* best_score_dev, void* hip_stream) {
+    if (!bp || !backptr_dev || !words_dev || !scores_dev || !tokens_dev || !length_dev || !best_score_dev)
+        return LSH_ERR_INVALID_ARG;
+    if (bp->S < 1 || bp->B < 1 || bp->B > kMaxB || bp->max_len < 1 || n_steps < 0 ||
+        n_steps > bp->max_len || (int64_t)n_steps * bp->B > INT32_MAX / 2)
+        return LSH_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_beam_backtrace, dim3((unsigned)bp->S), dim3(kWave), 0, (hipStream_t)hip_stream,
+                       (int)bp->S, (int)bp->B, (int)bp->eos, (int)n_steps, backptr_dev, words_dev,
+                       scores_dev, (int)bp->max_len, tokens_dev, length_dev, best_score_dev);
+    HIP_TRY(hipGetLastError());
     return LSH_OK;
 }
 
