@@ -54,7 +54,7 @@ constexpr int kMaxSentencesLogits = 4096;
 // are dropped; row groups beyond B are computed on clamped rows and dropped too).  The candidate
 // rows are loaded once for all MTB row groups.  Called by all WAVES*64 threads of the workgroup;
 // contains 2 MTB workgroup barriers.  h_lds, if given, is an LDS copy of the sentence's B hidden
-// rows (16-byte aligned, pitch d).
+// rows (16-byte aligned, pitch h_pitch floats; 0 = d).
 //
 // ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
 // d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
@@ -64,9 +64,10 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
                                             int nt, int C, int64_t j, float* __restrict__ logits,
                                             int64_t cpitch, float2* __restrict__ partials,
                                             int64_t ppitch, float (*red)[4][kWave],
-                                            const float* h_lds = nullptr) {
+                                            const float* h_lds = nullptr, int h_pitch = 0) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
+    if (h_pitch == 0) h_pitch = d;
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     const int col = ln & 15, kq = ln >> 4;
     const int nks = (d + KSTEP - 1) / KSTEP;
@@ -78,7 +79,7 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
 #pragma unroll
     for (int m = 0; m < MTB; ++m) {
         const int hr = min((mt + m) * kTileM + col, B - 1);
-        hrow[m] = h_lds ? h_lds + (size_t)hr * d : H + ((size_t)s * B + hr) * d;
+        hrow[m] = h_lds ? h_lds + (size_t)hr * h_pitch : H + ((size_t)s * B + hr) * d;
     }
 
     floatx4 acc[MTB];
@@ -164,7 +165,7 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
                                                      float* __restrict__ logits, int64_t cpitch,
                                                      float2* __restrict__ partials, int64_t ppitch,
                                                      float (*red)[4][kWave],
-                                                     const float* h_lds = nullptr) {
+                                                     const float* h_lds = nullptr, int h_pitch = 0) {
     // loads in flight per row group shrink as the groups grow: the operands of all groups have
     // to fit the register budget of a 1024-thread workgroup
     // (measured: keeping the full unroll in 256-thread workgroups, where registers would allow
@@ -176,18 +177,18 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
     const int MT = FIXED_MT ? FIXED_MT : (B + kTileM - 1) / kTileM;
     if (MT == 1) {
         logits_tile<ET, WAVES, UNROLL, ALIGNED, 1>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds);
+                                                   partials, ppitch, red, h_lds, h_pitch);
     } else if (MT == 2) {
         logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                               partials, ppitch, red, h_lds);
+                                               partials, ppitch, red, h_lds, h_pitch);
     } else if (ElemTraits<ET>::VEC > 4) {  // bf16: twice the registers per load, two groups at most
         for (int mt = 0; mt < MT; mt += 2)
             logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds);
+                                                   partials, ppitch, red, h_lds, h_pitch);
     } else {
         for (int mt = 0; mt < MT; mt += 4)
             logits_tile<ET, WAVES, U4, ALIGNED, 4>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds);
+                                                   partials, ppitch, red, h_lds, h_pitch);
     }
 }
 
@@ -413,6 +414,180 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         logits_tile_all_rows<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(E, ld, d, H, B, s, nt, C, j,
                                                                         logits, cpitch, partials,
                                                                         ppitch, red);
+    }
+}
+
+// The wave-per-tile kernel with the hidden rows in LDS.  Measured on this machine: a stream of
+// 16-byte loads that hits in cache still costs as much load-path throughput as one that goes to
+// memory -- gathering candidate rows alone runs at 6.7 TB/s, with an equal stream of hidden-row
+// loads beside it at 3.4 TB/s.  The A operands therefore must not come through the vector memory
+// path at all: a workgroup (WAVES waves, consecutive tiles, so mostly one sentence) stages the
+// sentence's B hidden rows in LDS once and every tile reads them with ds_read_b128.  The row
+// pitch is the next value >= d that is 4 modulo 32: consecutive rows then start 4 banks apart
+// and eight lanes x 16 bytes (eight rows, same k) cover all 32 banks exactly once.
+__host__ __device__ inline int hlds_pitch(int d) {
+    int p = (d + 3) & ~3;
+    while (p % 32 != 4) p += 4;
+    return p;
+}
+// dynamic LDS: tile prefix (S + 1 words, rounded to 4), split-k reduction buffer, hidden rows
+__host__ __device__ inline size_t hlds_lds_bytes(int S, int B, int d, int waves) {
+    return ((size_t)((S + 1 + 3) & ~3) + (size_t)waves * 4 * kWave + (size_t)B * hlds_pitch(d)) * 4;
+}
+
+template <typename ET, int MT, int WAVES, int UNROLL, bool ALIGNED>
+__global__ void __launch_bounds__(WAVES * kWave)
+k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
+              const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
+              float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
+              int64_t ppitch) {
+    constexpr int VEC = ElemTraits<ET>::VEC;
+    constexpr int KSTEP = 4 * VEC;
+    extern __shared__ uint32_t hsm[];
+    uint32_t* tile_pref = hsm;
+    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(hsm + ((S + 1 + 3) & ~3));
+    float* hl = reinterpret_cast<float*>(hsm + ((S + 1 + 3) & ~3) + WAVES * 4 * kWave);
+    const int pitch = hlds_pitch(d);
+    const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    if (wv == 0) {
+        uint32_t carry = 0;
+        for (int base = 0; base < S; base += kWave) {
+            const int s = base + ln;
+            uint32_t n = 0;
+            if (s < S) n = (uint32_t)(((count ? count[s] : V) + kTileN - 1) / kTileN);
+            const uint32_t incl = wave_incl_scan(n);
+            if (s < S) tile_pref[s] = carry + incl - n;
+            carry += wave_read_lane(incl, kWave - 1);
+        }
+        if (ln == 0) tile_pref[S] = carry;
+    }
+    __syncthreads();
+    const uint32_t total_tiles = tile_pref[S];
+    const uint32_t nwaves = gridDim.x * (uint32_t)WAVES;
+    const int col = ln & 15, kq = ln >> 4;
+    const int nks = (d + KSTEP - 1) / KSTEP;
+    const uint32_t whole = total_tiles / nwaves * nwaves;
+    const uint32_t wave_tiles = ((total_tiles - whole) * 2u > nwaves) ? total_tiles : whole;
+    auto sentence_of = [&](uint32_t t) {
+        int lo = 0, hi = S;  // last s with tile_pref[s] <= t
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (tile_pref[mid] <= t) lo = mid; else hi = mid;
+        }
+        return lo;
+    };
+    int staged = -1;
+    auto stage = [&](int s) {  // workgroup-uniform; barriers inside
+        if (s == staged) return;
+        __syncthreads();  // everyone is done with the previous sentence's rows
+        const float* Hs = H + (size_t)s * B * d;
+        if ((d & 3) == 0 && ((uintptr_t)Hs & 15) == 0) {
+            const int d4 = d >> 2;
+            for (int e = tid; e < B * d4; e += WAVES * kWave) {
+                const int r = e / d4, c = e - r * d4;
+                *reinterpret_cast<float4*>(hl + (size_t)r * pitch + 4 * c) =
+                    reinterpret_cast<const float4*>(Hs)[e];
+            }
+        } else {
+            for (int e = tid; e < B * d; e += WAVES * kWave) {
+                const int r = e / d, c = e - r * d;
+                hl[(size_t)r * pitch + c] = Hs[e];
+            }
+        }
+        __syncthreads();
+        staged = s;
+    };
+
+    // whole rounds: one wave per tile; the workgroup walks its consecutive tiles sentence by
+    // sentence (all of its waves in the same sentence, so one staging serves them)
+    const uint32_t per_wg = (wave_tiles + gridDim.x - 1) / gridDim.x;
+    const uint32_t wg_begin = min(wave_tiles, blockIdx.x * per_wg);
+    const uint32_t wg_end = min(wave_tiles, wg_begin + per_wg);
+    for (uint32_t seg = wg_begin; seg < wg_end;) {
+        const int s = sentence_of(seg);
+        const uint32_t seg_end = min(wg_end, tile_pref[s + 1]);
+        stage(s);
+        const int C = count ? count[s] : V;
+        for (uint32_t t = seg + wv; t < seg_end; t += WAVES) {
+            const int nt = (int)(t - tile_pref[s]);
+            const int n0 = nt * kTileN;
+            const int cidx = min(n0 + col, C - 1);  // clamped lanes are never stored
+            const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+            const ET* erow = E + j * ld;
+            const float* hrow[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) hrow[mt] = hl + (size_t)min(mt * kTileM + col, B - 1) * pitch;
+            floatx4 acc[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+            for (int ks0 = 0; ks0 < nks; ks0 += UNROLL) {
+                float ev[UNROLL][VEC];
+#pragma unroll
+                for (int uu = 0; uu < UNROLL; ++uu) {
+                    const int k = (ks0 + uu) * KSTEP + kq * VEC;
+                    if (ALIGNED) {
+                        if (k < d) ElemTraits<ET>::load16(erow + k, ev[uu]);
+                        else
+#pragma unroll
+                            for (int q = 0; q < VEC; ++q) ev[uu][q] = 0.f;
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) ev[uu][q] = (k + q < d) ? elem_f32(erow + k + q) : 0.f;
+                    }
+                }
+#pragma unroll
+                for (int uu = 0; uu < UNROLL; ++uu) {
+                    const int k = (ks0 + uu) * KSTEP + kq * VEC;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        float hv[VEC];
+                        if (ALIGNED) {  // d is a multiple of VEC: a chunk is inside the row or past it
+                            const bool in = k < d;
+                            const int kc = in ? k : 0;
+#pragma unroll
+                            for (int q = 0; q < VEC; q += 4) {
+                                const float4 h4 = *reinterpret_cast<const float4*>(hrow[mt] + kc + q);
+                                hv[q] = in ? h4.x : 0.f; hv[q + 1] = in ? h4.y : 0.f;
+                                hv[q + 2] = in ? h4.z : 0.f; hv[q + 3] = in ? h4.w : 0.f;
+                            }
+                        } else {
+#pragma unroll
+                            for (int q = 0; q < VEC; ++q)
+                                hv[q] = (k + q < d) ? hrow[mt][min(k + q, d - 1)] : 0.f;
+                        }
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q)
+                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[q], ev[uu][q], acc[mt], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int row = mt * kTileM + 4 * kq + r, c = n0 + col;
+                    const bool valid = row < B && c < C;
+                    const float x = acc[mt][r];
+                    if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
+                    const float mx = row16_max(valid ? x : -INFINITY);
+                    const float se = row16_sum(valid ? expf(x - mx) : 0.f);
+                    if (col == 0 && row < B)
+                        partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+                }
+        }
+        seg = seg_end;
+    }
+
+    // the remainder: one workgroup per tile, k split over its waves, hidden rows from LDS
+    for (uint32_t t = wave_tiles + blockIdx.x; t < total_tiles; t += gridDim.x) {
+        const int s = sentence_of(t);
+        stage(s);
+        const int nt = (int)(t - tile_pref[s]);
+        const int C = count ? count[s] : V;
+        const int cidx = min(nt * kTileN + col, C - 1);
+        const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        logits_tile_all_rows<ET, WAVES, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(
+            E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red, hl, pitch);
     }
 }
 

@@ -252,6 +252,26 @@ void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, c
 }
 
 template <typename ET>
+void launch_logits_hlds(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
+                        const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
+                        const Workspace& w, int MT, size_t lds_bytes) {
+    constexpr int U1 = 8 / (ElemTraits<ET>::VEC / 4), U2 = 4 / (ElemTraits<ET>::VEC / 4);
+    const ET* E = (const ET*)t->E;
+#define LSH_HLDS(MTV, UV, AL)                                                                        \
+    do {                                                                                             \
+        auto kfn = k_logits_hlds<ET, MTV, 8, UV, AL>;                                                \
+        if (lds_bytes > 48 * 1024)                                                                   \
+            (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, \
+                                      (int)lds_bytes);                                               \
+        launch(t, 1, kfn, dim3(grid), dim3(8 * kWave), lds_bytes, st, E, t->ld, t->d, H, sp->S, sp->B, \
+               cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);                         \
+    } while (0)
+    if (MT == 1) { if (aligned) LSH_HLDS(1, U1, true); else LSH_HLDS(1, U1, false); }
+    else { if (aligned) LSH_HLDS(2, U2, true); else LSH_HLDS(2, U2, false); }
+#undef LSH_HLDS
+}
+
+template <typename ET>
 void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
                    const int32_t* cand, const int32_t* count, const Workspace& w) {
     constexpr int VEC = ElemTraits<ET>::VEC;
@@ -265,7 +285,13 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     // Otherwise one wave per 16-candidate tile, no LDS and no barrier (up to 4 M-tiles per wave).
     const bool few = sp->S * MT <= 8;
     const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : (MT <= 4 ? 1 : 4));
-    if (mode == 1 && MT <= 4) {
+    // one wave per tile with the sentence's hidden rows staged in LDS (up to two groups of 16
+    // beams, two 8-wave workgroups per CU); LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory
+    const size_t hlds_bytes = hlds_lds_bytes(sp->S, sp->B, t->d, 8);
+    if (mode == 1 && MT <= 2 && hlds_bytes <= 78 * 1024 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
+        const int grid = (int)std::min<int64_t>((tiles_n + 7) / 8, env_int("LSHBEAM_LOGITS_GRID", 512));
+        launch_logits_hlds<ET>(t, st, grid, aligned, H, sp, cand, count, w, MT, hlds_bytes);
+    } else if (mode == 1 && MT <= 4) {
         const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, env_int("LSHBEAM_LOGITS_GRID", 1024));
         switch (MT) {
             case 1: launch_logits_wave<ET, 1>(t, st, grid, aligned, H, sp, cand, count, w); break;
