@@ -30,7 +30,7 @@ def log(*a):
 
 def measured_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
-    for kernel in ("k_cand_logits", "k_logits_wave"):
+    for kernel in ("k_cand_logits", "k_logits_hlds", "k_logits_wave"):
         path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.md")
         try:
             for line in open(path):
@@ -183,11 +183,14 @@ def main():
     # ---- per-kernel durations over the same K steps, from HIP events around each kernel -------
     run_lsh(0, min(Wm, nst), stream_ptr())
     torch.cuda.synchronize()
-    tables.profile_begin(K)
+    # (a kernel may be launched more than once per step -- the contraction takes more than 32 beams
+    #  in groups -- so room for several launches per step, and durations are summed per step)
+    launches_per_step = (B + 31) // 32
+    tables.profile_begin(K * launches_per_step)
     run_lsh(0, K, stream_ptr())
-    prof = tables.profile_end()
+    prof = {name: (ms * n / K, n) for name, (ms, n) in tables.profile_end().items()}
     for name, (ms, n) in prof.items():
-        log(f"[bench]   {name:14s} mean {ms*1e3:8.2f} us over {n} launches")
+        log(f"[bench]   {name:14s} mean {ms*1e3:8.2f} us per step ({n} launches)")
 
     e_bytes = 2 if cfg.e_dtype == workloads.BF16 else 4
     mean_rows = float(counts.sum(axis=1).mean())                 # gathered E rows per launch
@@ -212,11 +215,11 @@ def main():
         _, _, run_full = make_runner(True)
         kf = max(nst, min(K, 400) // nst * nst)
         fsecs, _ = time_region(run_full, kf, args.mode)
-        tables.profile_begin(kf)
+        tables.profile_begin(kf * launches_per_step)
         run_full(0, kf, stream_ptr())
-        fprof = tables.profile_end()
+        fprof = {name: (ms * n / kf, n) for name, (ms, n) in tables.profile_end().items()}
         for name, (ms, n) in fprof.items():
-            log(f"[bench]   full-vocab {name:14s} mean {ms*1e3:8.2f} us over {n} launches")
+            log(f"[bench]   full-vocab {name:14s} mean {ms*1e3:8.2f} us per step ({n} launches)")
         full = {"steps": kf, "ms_per_step": round(fsecs / kf * 1e3, 5),
                 "kernels_us": {k: round(v[0] * 1e3, 3) for k, v in fprof.items() if v[1]},
                 "steps_per_s": round(kf / fsecs, 1),
@@ -247,11 +250,11 @@ def main():
         tables.profile_begin(64)
         for i in range(64):
             lsh.decode_step(tables, Hb[i % 8], bz, tf_dev, bsp, bws, bo[0], bo[1], bsc)
-        bprof = tables.profile_end()
+        bprof = {name: (ms * n / 64, n) for name, (ms, n) in tables.profile_end().items()}
         bbytes = float(np.mean(rows)) * bcfg.d * e_bytes
         bms = bprof["k_logits"][0]
         regime = {"workload": f"batched: S={bcfg.S} B={bcfg.B}, same E and tables",
-                  "kernel": "k_logits_wave", "kernel_us": round(bms * 1e3, 2),
+                  "kernel": "k_logits_hlds", "kernel_us": round(bms * 1e3, 2),
                   "algorithmic_bytes_per_launch": bbytes,
                   "achieved_GBps": round(bbytes / (bms * 1e-3) / 1e9, 1),
                   "frac_of_hbm_peak": round(bbytes / (bms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),

@@ -199,9 +199,11 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
 int32_t lsh_step_is_fused(const lsh_tables* t, const lsh_step_params* sp);
 
 
-/* Start recording the device start/stop time of every kernel of the next steps (at most
- * max_steps of them) on this handle; lsh_profile_end synchronises the device, writes the mean
- * duration in milliseconds of each kernel and the number of recorded launches, and stops. */
+/* Start recording the device start/stop time of every kernel launch of the next steps (at most
+ * max_steps launches per kernel) on this handle; lsh_profile_end synchronises the device, writes
+ * the mean duration in milliseconds per launch of each kernel and the number of recorded
+ * launches, and stops.  A step can launch a kernel more than once (the contraction takes more
+ * than 32 beams in groups of 32): time per step = mean x launches / steps. */
 lsh_status lsh_profile_begin(lsh_tables* t, int32_t max_steps);
 lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
                            int32_t launches_out[LSH_NUM_KERNELS]);

@@ -54,7 +54,8 @@ constexpr int kMaxSentencesLogits = 4096;
 // are dropped; row groups beyond B are computed on clamped rows and dropped too).  The candidate
 // rows are loaded once for all MTB row groups.  Called by all WAVES*64 threads of the workgroup;
 // contains 2 MTB workgroup barriers.  h_lds, if given, is an LDS copy of the sentence's B hidden
-// rows (16-byte aligned, pitch h_pitch floats; 0 = d).
+// rows (16-byte aligned, pitch h_pitch floats; 0 = d).  [row_lo, row_hi) restricts the call to
+// a range of the sentence's rows (mt counts groups of 16 from row_lo; h_lds then holds that range).
 //
 // ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
 // d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
@@ -64,10 +65,12 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
                                             int nt, int C, int64_t j, float* __restrict__ logits,
                                             int64_t cpitch, float2* __restrict__ partials,
                                             int64_t ppitch, float (*red)[4][kWave],
-                                            const float* h_lds = nullptr, int h_pitch = 0) {
+                                            const float* h_lds = nullptr, int h_pitch = 0,
+                                            int row_lo = 0, int row_hi = -1) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
     if (h_pitch == 0) h_pitch = d;
+    if (row_hi < 0) row_hi = B;
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     const int col = ln & 15, kq = ln >> 4;
     const int nks = (d + KSTEP - 1) / KSTEP;
@@ -78,8 +81,8 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
     const float* hrow[MTB];
 #pragma unroll
     for (int m = 0; m < MTB; ++m) {
-        const int hr = min((mt + m) * kTileM + col, B - 1);
-        hrow[m] = h_lds ? h_lds + (size_t)hr * h_pitch : H + ((size_t)s * B + hr) * d;
+        const int hr = min(row_lo + (mt + m) * kTileM + col, row_hi - 1);
+        hrow[m] = h_lds ? h_lds + (size_t)(hr - row_lo) * h_pitch : H + ((size_t)s * B + hr) * d;
     }
 
     floatx4 acc[MTB];
@@ -141,14 +144,14 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
             float sum = 0.f;
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
-            const int row = (mt + m) * kTileM + i, c = n0 + jc;
-            const bool valid = row < B && c < C;
+            const int row = row_lo + (mt + m) * kTileM + i, c = n0 + jc;
+            const bool valid = row < row_hi && c < C;
             if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
             // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
             // tile's 16 candidates; the 16 lanes that share a row are one DPP row
             const float mx = row16_max(valid ? sum : -INFINITY);
             const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
-            if (jc == 0 && row < B)
+            if (jc == 0 && row < row_hi)
                 partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
         }
         __syncthreads();
@@ -165,7 +168,8 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
                                                      float* __restrict__ logits, int64_t cpitch,
                                                      float2* __restrict__ partials, int64_t ppitch,
                                                      float (*red)[4][kWave],
-                                                     const float* h_lds = nullptr, int h_pitch = 0) {
+                                                     const float* h_lds = nullptr, int h_pitch = 0,
+                                                     int row_lo = 0, int row_hi = -1) {
     // loads in flight per row group shrink as the groups grow: the operands of all groups have
     // to fit the register budget of a 1024-thread workgroup
     // (measured: keeping the full unroll in 256-thread workgroups, where registers would allow
@@ -174,21 +178,21 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
     constexpr int U2 = ElemTraits<ET>::VEC > 4 ? U4 : (UNROLL >= 2 ? UNROLL / 2 : 1);
     // FIXED_MT: the caller knows the number of row groups at compile time (only that case is
     // instantiated, so its registers do not count against the others)
-    const int MT = FIXED_MT ? FIXED_MT : (B + kTileM - 1) / kTileM;
+    const int MT = FIXED_MT ? FIXED_MT : ((row_hi < 0 ? B : row_hi - row_lo) + kTileM - 1) / kTileM;
     if (MT == 1) {
         logits_tile<ET, WAVES, UNROLL, ALIGNED, 1>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds, h_pitch);
+                                                   partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
     } else if (MT == 2) {
         logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                               partials, ppitch, red, h_lds, h_pitch);
+                                               partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
     } else if (ElemTraits<ET>::VEC > 4) {  // bf16: twice the registers per load, two groups at most
         for (int mt = 0; mt < MT; mt += 2)
             logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds, h_pitch);
+                                                   partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
     } else {
         for (int mt = 0; mt < MT; mt += 4)
             logits_tile<ET, WAVES, U4, ALIGNED, 4>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds, h_pitch);
+                                                   partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
     }
 }
 
@@ -431,13 +435,14 @@ __host__ __device__ inline int hlds_pitch(int d) {
     return p;
 }
 // dynamic LDS: tile prefix (S + 1 words, rounded to 4), split-k reduction buffer, hidden rows
-__host__ __device__ inline size_t hlds_lds_bytes(int S, int B, int d, int waves) {
-    return ((size_t)((S + 1 + 3) & ~3) + (size_t)waves * 4 * kWave + (size_t)B * hlds_pitch(d)) * 4;
+__host__ __device__ inline size_t hlds_lds_bytes(int S, int rows, int d, int waves) {
+    return ((size_t)((S + 1 + 3) & ~3) + (size_t)waves * 4 * kWave + (size_t)rows * hlds_pitch(d)) * 4;
 }
 
 template <typename ET, int MT, int WAVES, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(WAVES * kWave)
 k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
+              int row0, int Bg /*rows [row0, row0 + Bg) of every sentence, Bg <= 16 MT*/,
               const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
               float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
               int64_t ppitch) {
@@ -480,16 +485,16 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     auto stage = [&](int s) {  // workgroup-uniform; barriers inside
         if (s == staged) return;
         __syncthreads();  // everyone is done with the previous sentence's rows
-        const float* Hs = H + (size_t)s * B * d;
+        const float* Hs = H + ((size_t)s * B + row0) * d;
         if ((d & 3) == 0 && ((uintptr_t)Hs & 15) == 0) {
             const int d4 = d >> 2;
-            for (int e = tid; e < B * d4; e += WAVES * kWave) {
+            for (int e = tid; e < Bg * d4; e += WAVES * kWave) {
                 const int r = e / d4, c = e - r * d4;
                 *reinterpret_cast<float4*>(hl + (size_t)r * pitch + 4 * c) =
                     reinterpret_cast<const float4*>(Hs)[e];
             }
         } else {
-            for (int e = tid; e < B * d; e += WAVES * kWave) {
+            for (int e = tid; e < Bg * d; e += WAVES * kWave) {
                 const int r = e / d, c = e - r * d;
                 hl[(size_t)r * pitch + c] = Hs[e];
             }
@@ -516,7 +521,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
             const ET* erow = E + j * ld;
             const float* hrow[MT];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) hrow[mt] = hl + (size_t)min(mt * kTileM + col, B - 1) * pitch;
+            for (int mt = 0; mt < MT; ++mt) hrow[mt] = hl + (size_t)min(mt * kTileM + col, Bg - 1) * pitch;
             floatx4 acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -565,13 +570,13 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int row = mt * kTileM + 4 * kq + r, c = n0 + col;
-                    const bool valid = row < B && c < C;
+                    const int row = row0 + mt * kTileM + 4 * kq + r, c = n0 + col;
+                    const bool valid = row < row0 + Bg && c < C;
                     const float x = acc[mt][r];
                     if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
                     const float mx = row16_max(valid ? x : -INFINITY);
                     const float se = row16_sum(valid ? expf(x - mx) : 0.f);
-                    if (col == 0 && row < B)
+                    if (col == 0 && row < row0 + Bg)
                         partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
                 }
         }
@@ -587,7 +592,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int cidx = min(nt * kTileN + col, C - 1);
         const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
         logits_tile_all_rows<ET, WAVES, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(
-            E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red, hl, pitch);
+            E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red, hl, pitch, row0, row0 + Bg);
     }
 }
 

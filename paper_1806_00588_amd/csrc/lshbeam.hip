@@ -251,23 +251,47 @@ void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, c
                H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
 }
 
+// Launches of k_logits_hlds over the sentence's rows in groups of at most 32 (two groups of 16
+// per launch): a group's rows must fit in LDS.  Up to 78 KB two 8-wave workgroups share a CU,
+// beyond that one 16-wave workgroup has it alone.  Returns false if even one 16-row group does
+// not fit (very large d): the caller then keeps the hidden rows in global memory.
+constexpr size_t kHldsHalf = 78 * 1024;
+inline int hlds_group_rows(int S, int B, int d) {
+    for (int rows : {32, 16})
+        if (hlds_lds_bytes(S, std::min(rows, B), d, 16) <= kMaxDynLds) return std::min(rows, B);
+    return 0;
+}
+
 template <typename ET>
-void launch_logits_hlds(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
+void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool aligned, const float* H,
                         const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
-                        const Workspace& w, int MT, size_t lds_bytes) {
+                        const Workspace& w, int group_rows) {
     constexpr int U1 = 8 / (ElemTraits<ET>::VEC / 4), U2 = 4 / (ElemTraits<ET>::VEC / 4);
     const ET* E = (const ET*)t->E;
-#define LSH_HLDS(MTV, UV, AL)                                                                        \
+#define LSH_HLDS(MTV, WV, UV, AL)                                                                    \
     do {                                                                                             \
-        auto kfn = k_logits_hlds<ET, MTV, 8, UV, AL>;                                                \
-        if (lds_bytes > 48 * 1024)                                                                   \
+        auto kfn = k_logits_hlds<ET, MTV, WV, UV, AL>;                                               \
+        const size_t lds = hlds_lds_bytes(sp->S, rows, t->d, WV);                                    \
+        if (lds > 48 * 1024)                                                                         \
             (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                      (int)lds_bytes);                                               \
-        launch(t, 1, kfn, dim3(grid), dim3(8 * kWave), lds_bytes, st, E, t->ld, t->d, H, sp->S, sp->B, \
-               cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);                         \
+                                      (int)lds);                                                     \
+        const int grid = (int)std::min<int64_t>((tiles_n + WV - 1) / WV,                             \
+                                                env_int("LSHBEAM_LOGITS_GRID", 4096 / WV));          \
+        launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
+               row0, rows, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);             \
     } while (0)
-    if (MT == 1) { if (aligned) LSH_HLDS(1, U1, true); else LSH_HLDS(1, U1, false); }
-    else { if (aligned) LSH_HLDS(2, U2, true); else LSH_HLDS(2, U2, false); }
+    for (int row0 = 0; row0 < sp->B; row0 += group_rows) {
+        const int rows = std::min(group_rows, sp->B - row0);
+        const bool two = rows > kTileM;
+        const bool small = hlds_lds_bytes(sp->S, rows, t->d, 8) <= kHldsHalf;
+        if (small) {
+            if (two) { if (aligned) LSH_HLDS(2, 8, U2, true); else LSH_HLDS(2, 8, U2, false); }
+            else { if (aligned) LSH_HLDS(1, 8, U1, true); else LSH_HLDS(1, 8, U1, false); }
+        } else {
+            if (two) { if (aligned) LSH_HLDS(2, 16, U2, true); else LSH_HLDS(2, 16, U2, false); }
+            else { if (aligned) LSH_HLDS(1, 16, U1, true); else LSH_HLDS(1, 16, U1, false); }
+        }
+    }
 #undef LSH_HLDS
 }
 
@@ -284,13 +308,16 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     // split across the 16 waves of a workgroup and the partial tiles are summed through LDS.
     // Otherwise one wave per 16-candidate tile, no LDS and no barrier (up to 4 M-tiles per wave).
     const bool few = sp->S * MT <= 8;
-    const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : (MT <= 4 ? 1 : 4));
-    // one wave per tile with the sentence's hidden rows staged in LDS (up to two groups of 16
-    // beams, two 8-wave workgroups per CU); LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory
-    const size_t hlds_bytes = hlds_lds_bytes(sp->S, sp->B, t->d, 8);
-    if (mode == 1 && MT <= 2 && hlds_bytes <= 78 * 1024 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
-        const int grid = (int)std::min<int64_t>((tiles_n + 7) / 8, env_int("LSHBEAM_LOGITS_GRID", 512));
-        launch_logits_hlds<ET>(t, st, grid, aligned, H, sp, cand, count, w, MT, hlds_bytes);
+    const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : 1);
+    // one wave per tile with the sentence's hidden rows staged in LDS, the rows taken in groups
+    // of at most 32 (one launch each); LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory
+    // (measured: with more than 32 beams -- two or more launches, each over the few tiles of a
+    // few sentences -- the grouped form is slower than one launch with the rows in global
+    // memory: 75 against 55 us at S = 4, B = 50; LSHBEAM_LOGITS_HLDS=2 forces it anyway)
+    const int group_rows = hlds_group_rows(sp->S, sp->B, t->d);
+    const int want_hlds = env_int("LSHBEAM_LOGITS_HLDS", 1);
+    if (mode == 1 && group_rows > 0 && (want_hlds == 2 || (want_hlds == 1 && sp->B <= group_rows))) {
+        launch_logits_hlds<ET>(t, st, tiles_n, aligned, H, sp, cand, count, w, group_rows);
     } else if (mode == 1 && MT <= 4) {
         const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, env_int("LSHBEAM_LOGITS_GRID", 1024));
         switch (MT) {

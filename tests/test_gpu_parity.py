@@ -421,6 +421,25 @@ def test_paper_shape_wide_beams():
         run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(B == 24))
 
 
+@pytest.mark.parametrize("hlds", ["0", "2"])
+def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, monkeypatch):
+    # many-tile steps stage the sentence's hidden rows in LDS (rows in groups of 32, one launch
+    # each, when forced for more than 32 beams); LSHBEAM_LOGITS_HLDS=0 reads them from global memory
+    cfg, gc = case("tiny")
+    monkeypatch.setenv("LSHBEAM_FUSED", "0")
+    monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
+    monkeypatch.setenv("LSHBEAM_LOGITS_HLDS", hlds)
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)
+    rng = np.random.default_rng(3)
+    for grid in ("1", "3", "512"):
+        monkeypatch.setenv("LSHBEAM_LOGITS_GRID", grid)
+        for S, B in [(5, 16), (2, 17), (3, 40), (2, 70), (1, 33), (7, 4)]:
+            bs = rng.standard_normal(S * B).astype(np.float32)
+            run_and_check(cfg, gc, H[:S * B], bs, S, B)
+    run_and_check(cfg, gc, H[:80], np.zeros(80, np.float32), 2, 40, full_vocab=True)
+
+
 @pytest.mark.parametrize("grid", [1, 2, 3, 5, 8, 16])
 def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, monkeypatch):
     # one wave per tile for whole rounds of the (here artificially small) grid; a short last
