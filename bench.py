@@ -6,7 +6,7 @@ candidate list, gathered logits, log-softmax, top-B -- for one batch of syntheti
 with every input already resident in HBM.  Steps of a synthetic "sentence" are chained: the
 scores a step returns are the next step's beam scores.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line (the fields are described in the README and the design notes).
 """
 from __future__ import annotations
 
@@ -64,7 +64,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the hot path is a single-GPU kernel "
-              "sequence; sharding is described in DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "sequence; how it would shard is described in the design notes). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
