@@ -6,6 +6,11 @@
 //                   (lines 3-6) marking a V-bit presence bitmap held in LDS, ORs in the
 //                   top-frequent words (Eq. 3) and compacts the bitmap into an ascending id list
 //                   (Eq. 10 with t = 1).
+//   k_part_bitmaps: the same hashing for a range of a sentence's rows, the bitmap left in global
+//                   memory (sentences with many beams are hashed by several workgroups).
+//   k_hit_rows    : hit threshold t > 1 (Eq. 9-10 in full): one workgroup per hidden row counts
+//                   the row's collisions per word in LDS and leaves the thresholded bitmap.
+//   k_union_compact: OR of a sentence's part / row bitmaps + top-frequent words + compaction.
 //
 // The paper keeps an integer hit matrix L[B,V] in global memory and compacts it with a shared-
 // memory scan by lane 0 of each warp.  With t = 1 only "hit at least once" matters, so L

@@ -17,6 +17,15 @@
 // The k slots of one instruction may hold any four k indices as long as A and B agree, so lane l
 // loads ONE 16-byte chunk of its candidate's row (fp32: 4 consecutive k, bf16: 8) and feeds one
 // element per instruction: per load instruction a wave touches 16 rows x 64 contiguous bytes.
+//
+// Drivers of the tile code:
+//   k_logits<WAVES>  a workgroup of 16 or 4 waves per (tile, row group), k split over the waves
+//                    (few sentences; more than 64 beams);
+//   k_logits_wave    one wave per tile, up to four row groups in the wave, hidden rows read from
+//                    global memory (33..64 beams);
+//   k_logits_hlds    one wave per tile, the sentence's hidden rows staged in LDS (up to 32 beams:
+//                    the bandwidth-bound case);
+//   fused.h          the same tiles inside the kernels that also produce the candidate list.
 #pragma once
 #include "device_utils.h"
 

@@ -1,7 +1,8 @@
-// C ABI of the lshbeam library (see include/lshbeam.h): table build, decode step, inspection.
-// gfx950 only.  Host side: argument validation, the once-only grouping of word ids by band code
-// and cuckoo insertion, kernel launches.  Every per-step computation runs in the HIP kernels of
-// candidates.h / logits.h / select.h.
+// C ABI of the lshbeam library (see include/lshbeam.h): table build, decode step, beam
+// bookkeeping, inspection.  gfx950 only.  Host side: argument validation, the choice of the
+// launch plan, kernel launches, the hash parameters of the cuckoo tables (and a host fallback of
+// the table build).  Every per-step computation runs in the HIP kernels of candidates.h /
+// fused.h / logits.h / select.h / beam.h, the table build in those of build_tables.h.
 #include "../../include/lshbeam.h"
 
 #include <hip/hip_ext.h>
