@@ -276,8 +276,7 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
         if (lds > 48 * 1024)                                                                         \
             (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                       (int)lds);                                                     \
-        const int grid = (int)std::min<int64_t>((tiles_n + WV - 1) / WV,                             \
-                                                env_int("LSHBEAM_LOGITS_GRID", 4096 / WV));          \
+        const int grid = (int)std::min<int64_t>(tiles_n, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV)); \
         launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
                row0, rows, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);             \
     } while (0)
@@ -308,7 +307,9 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     // Few (sentence, M-tile) groups: little work per step and it is latency that counts, so k is
     // split across the 16 waves of a workgroup and the partial tiles are summed through LDS.
     // Otherwise one wave per 16-candidate tile, no LDS and no barrier (up to 4 M-tiles per wave).
-    const bool few = sp->S * MT <= 8;
+    // (the full-vocabulary mode has V / 16 tiles per sentence, known here: thousands of tiles
+    // are "many" even for one sentence -- 29.9 against 37.1 us at V = 40000)
+    const bool few = sp->S * MT <= 8 && !(count == nullptr && tiles_n >= 1024);
     const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : 1);
     // one wave per tile with the sentence's hidden rows staged in LDS, the rows taken in groups
     // of at most 32 (one launch each); LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory
