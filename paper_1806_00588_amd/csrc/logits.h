@@ -463,6 +463,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     float* hl = reinterpret_cast<float*>(hsm + ((S + 1 + 3) & ~3) + WAVES * 4 * kWave);
     const int pitch = hlds_pitch(d);
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    LSH_TRACE(1, 0);
     if (wv == 0) {
         uint32_t carry = 0;
         for (int base = 0; base < S; base += kWave) {
@@ -476,6 +477,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         if (ln == 0) tile_pref[S] = carry;
     }
     __syncthreads();
+    LSH_TRACE(1, 1);
     const uint32_t total_tiles = tile_pref[S];
     const uint32_t nwaves = gridDim.x * (uint32_t)WAVES;
     const int col = ln & 15, kq = ln >> 4;
@@ -521,6 +523,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int s = sentence_of(seg);
         const uint32_t seg_end = min(wg_end, tile_pref[s + 1]);
         stage(s);
+        LSH_TRACE(1, 2);
         const int C = count ? count[s] : V;
         for (uint32_t t = seg + wv; t < seg_end; t += WAVES) {
             const int nt = (int)(t - tile_pref[s]);
@@ -534,47 +537,86 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
             floatx4 acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-            for (int ks0 = 0; ks0 < nks; ks0 += UNROLL) {
+            if (ALIGNED) {
+                // Rolling prefetch: UNROLL candidate-row loads stay in flight all the time.  Slot
+                // uu is consumed (LDS read of the hidden rows, VEC matrix instructions) and at
+                // once refilled with the chunk UNROLL k-steps ahead, so memory latency and
+                // arithmetic overlap inside the wave instead of alternating.  Addresses past
+                // the row are clamped into it (no branch around a load); such chunks meet
+                // hidden values forced to zero.
                 float ev[UNROLL][VEC];
+                const int klast = d - VEC;  // d is a multiple of VEC here
 #pragma unroll
                 for (int uu = 0; uu < UNROLL; ++uu) {
-                    const int k = (ks0 + uu) * KSTEP + kq * VEC;
-                    if (ALIGNED) {
-                        if (k < d) ElemTraits<ET>::load16(erow + k, ev[uu]);
-                        else
+                    ElemTraits<ET>::load16(erow + min(uu * KSTEP + kq * VEC, klast), ev[uu]);
+                    __builtin_amdgcn_sched_barrier(0);  // issue order = consumption order
+                }
+                // the hidden chunk of a slot is read from LDS one slot ahead, so that its latency
+                // hides behind the previous slot's matrix instructions
+                float hn[MT][VEC];
+                auto read_hidden = [&](int k, float (&dst)[MT][VEC]) {
+                    const bool in = k < d;
+                    const int kc = in ? k : 0;
 #pragma unroll
-                            for (int q = 0; q < VEC; ++q) ev[uu][q] = 0.f;
-                    } else {
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int q = 0; q < VEC; q += 4) {
+                            const float4 h4 = *reinterpret_cast<const float4*>(hrow[mt] + kc + q);
+                            dst[mt][q] = in ? h4.x : 0.f; dst[mt][q + 1] = in ? h4.y : 0.f;
+                            dst[mt][q + 2] = in ? h4.z : 0.f; dst[mt][q + 3] = in ? h4.w : 0.f;
+                        }
+                };
+                read_hidden(kq * VEC, hn);
+                for (int ks0 = 0; ks0 < nks; ks0 += UNROLL) {
+#pragma unroll
+                    for (int uu = 0; uu < UNROLL; ++uu) {
+                        const int k = (ks0 + uu) * KSTEP + kq * VEC;
+                        float hv[MT][VEC];
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int q = 0; q < VEC; ++q) hv[mt][q] = hn[mt][q];
+                        read_hidden(k + KSTEP, hn);  // next slot (past the row: zeros)
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int q = 0; q < VEC; ++q)
+                                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[mt][q], ev[uu][q], acc[mt], 0, 0, 0);
+                        // (unconditional: a branch around the load would make the compiler wait
+                        // for every outstanding load at the top of the round; past the end of the
+                        // row the clamped address re-reads its last chunk, a cache hit)
+                        ElemTraits<ET>::load16(erow + min(k + UNROLL * KSTEP, klast), ev[uu]);
+                        // keep the refill here: the scheduler would otherwise sink it towards
+                        // its use a round later and leave one or two loads in flight
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            } else {
+                for (int ks0 = 0; ks0 < nks; ks0 += UNROLL) {
+                    float ev[UNROLL][VEC];
+#pragma unroll
+                    for (int uu = 0; uu < UNROLL; ++uu) {
+                        const int k = (ks0 + uu) * KSTEP + kq * VEC;
 #pragma unroll
                         for (int q = 0; q < VEC; ++q) ev[uu][q] = (k + q < d) ? elem_f32(erow + k + q) : 0.f;
                     }
-                }
 #pragma unroll
-                for (int uu = 0; uu < UNROLL; ++uu) {
-                    const int k = (ks0 + uu) * KSTEP + kq * VEC;
+                    for (int uu = 0; uu < UNROLL; ++uu) {
+                        const int k = (ks0 + uu) * KSTEP + kq * VEC;
 #pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        float hv[VEC];
-                        if (ALIGNED) {  // d is a multiple of VEC: a chunk is inside the row or past it
-                            const bool in = k < d;
-                            const int kc = in ? k : 0;
-#pragma unroll
-                            for (int q = 0; q < VEC; q += 4) {
-                                const float4 h4 = *reinterpret_cast<const float4*>(hrow[mt] + kc + q);
-                                hv[q] = in ? h4.x : 0.f; hv[q + 1] = in ? h4.y : 0.f;
-                                hv[q + 2] = in ? h4.z : 0.f; hv[q + 3] = in ? h4.w : 0.f;
-                            }
-                        } else {
+                        for (int mt = 0; mt < MT; ++mt) {
+                            float hv[VEC];
 #pragma unroll
                             for (int q = 0; q < VEC; ++q)
                                 hv[q] = (k + q < d) ? hrow[mt][min(k + q, d - 1)] : 0.f;
-                        }
 #pragma unroll
-                        for (int q = 0; q < VEC; ++q)
-                            acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[q], ev[uu][q], acc[mt], 0, 0, 0);
+                            for (int q = 0; q < VEC; ++q)
+                                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(hv[q], ev[uu][q], acc[mt], 0, 0, 0);
+                        }
                     }
                 }
             }
+            LSH_TRACE(1, 3);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -591,6 +633,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         }
         seg = seg_end;
     }
+    LSH_TRACE(1, 4);
 
     // the remainder: one workgroup per tile, k split over its waves, hidden rows from LDS
     for (uint32_t t = wave_tiles + blockIdx.x; t < total_tiles; t += gridDim.x) {
