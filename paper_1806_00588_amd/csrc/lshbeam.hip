@@ -268,6 +268,8 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
                         const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
                         const Workspace& w, int group_rows) {
     constexpr int U1 = 8 / (ElemTraits<ET>::VEC / 4), U2 = 4 / (ElemTraits<ET>::VEC / 4);
+    // (1024-thread workgroups have 128 registers per lane: one load less in flight)
+    constexpr int U2W = (U2 > 2) ? U2 - 1 : U2;
     const ET* E = (const ET*)t->E;
 #define LSH_HLDS(MTV, WV, UV, AL)                                                                    \
     do {                                                                                             \
@@ -288,7 +290,7 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
             if (two) { if (aligned) LSH_HLDS(2, 8, U2, true); else LSH_HLDS(2, 8, U2, false); }
             else { if (aligned) LSH_HLDS(1, 8, U1, true); else LSH_HLDS(1, 8, U1, false); }
         } else {
-            if (two) { if (aligned) LSH_HLDS(2, 16, U2, true); else LSH_HLDS(2, 16, U2, false); }
+            if (two) { if (aligned) LSH_HLDS(2, 16, U2W, true); else LSH_HLDS(2, 16, U2W, false); }
             else { if (aligned) LSH_HLDS(1, 16, U1, true); else LSH_HLDS(1, 16, U1, false); }
         }
     }
