@@ -113,22 +113,49 @@ k_cuckoo_insert(uint64_t* __restrict__ table, const BandMeta* __restrict__ bands
     failed[w] = 1u;
 }
 
-// 8-byte table words -> the 16-byte slots of the probe.
+// Where the vocabulary slices 1, 2, 3 of the hit-count kernel begin inside key k's span (ids are
+// ascending inside a span): lower bounds of slice * slice_ids, relative to the span's start.
+__global__ void __launch_bounds__(256)
+k_slice_cuts(const int32_t* __restrict__ words, const uint32_t* __restrict__ key_start,
+             const uint32_t* __restrict__ key_len, const int32_t* __restrict__ key_band,
+             uint32_t n_keys, uint32_t V, int slice_ids, uint4* __restrict__ key_cut) {
+    const uint32_t k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= n_keys) return;
+    const int32_t* span = words + (size_t)key_band[k] * V + key_start[k];
+    const uint32_t len = key_len[k];
+    uint32_t cut[3];
+    for (int q = 1; q <= 3; ++q) {
+        const int32_t bound = q * slice_ids;
+        uint32_t lo = 0, hi = len;  // first position whose id is >= bound
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (span[mid] < bound) lo = mid + 1; else hi = mid;
+        }
+        cut[q - 1] = lo;
+    }
+    key_cut[k] = make_uint4(cut[0], cut[1], cut[2], len);
+}
+
+// 8-byte table words -> the 16-byte slots of the probe (and the slice cuts beside them).
 __global__ void __launch_bounds__(256)
 k_cuckoo_finalize(const uint64_t* __restrict__ table, uint64_t n_slots,
                   const uint32_t* __restrict__ key_start, const uint32_t* __restrict__ key_len,
-                  Slot* __restrict__ slots) {
+                  const uint4* __restrict__ key_cut, Slot* __restrict__ slots,
+                  uint4* __restrict__ cuts) {
     const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_slots) return;
     const uint64_t e = table[i];
     Slot s{-1, 0u, 0u, 0u};
+    uint4 c = make_uint4(0u, 0u, 0u, 0u);
     if (e != kCuckooEmpty) {
         const uint32_t k = (uint32_t)e;
         s.key = (int32_t)(uint32_t)(e >> 32);
         s.start = key_start[k];
         s.len = key_len[k];
+        c = key_cut[k];
     }
     slots[i] = s;
+    cuts[i] = c;
 }
 
 }  // namespace lshbeam

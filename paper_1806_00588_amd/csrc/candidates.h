@@ -57,6 +57,36 @@ __device__ __forceinline__ void cuckoo_find(const Slot* __restrict__ slots, cons
     *len = hit0 ? (uint32_t)s0.z : (hit1 ? (uint32_t)s1.z : 0u);
 }
 
+// The hit-count kernel (threshold t > 1) cuts the vocabulary into kHitSlices ranges of
+// hit_slice_words(V) ids and gives every (hidden row, slice) its own workgroup.  Spans are sorted
+// by id, so the part of a span that falls into slice q is contiguous; where slices 1, 2, 3 begin
+// inside every span is computed once at build time and stored beside the slot (x, y, z of a
+// uint4; positions relative to the span's start).
+constexpr int kHitSlices = 4;
+__host__ __device__ inline int hit_slice_words(int V) {  // ids per slice: a multiple of 128
+    return (((V + kHitSlices - 1) / kHitSlices) + 127) & ~127;
+}
+
+// cuckoo_find restricted to vocabulary slice q: (start, len) of the span's part inside it.  The
+// cut positions of both candidate slots are loaded along with the slots (no dependent load).
+__device__ __forceinline__ void cuckoo_find_slice(const Slot* __restrict__ slots,
+                                                  const uint4* __restrict__ cuts, const BandMeta& m,
+                                                  int32_t code, int q, uint32_t* start, uint32_t* len) {
+    const uint32_t h0 = cuckoo_hash(m.a0, m.b0, (uint32_t)code, m.shift);
+    const uint32_t h1 = cuckoo_hash(m.a1, m.b1, (uint32_t)code, m.shift);
+    const int4 s0 = *reinterpret_cast<const int4*>(slots + m.slot_off + h0);
+    const int4 s1 = *reinterpret_cast<const int4*>(slots + m.slot_off + h1);
+    const uint4 c0 = cuts[m.slot_off + h0], c1 = cuts[m.slot_off + h1];
+    const bool hit0 = s0.x == code, hit1 = s1.x == code;
+    const uint32_t st = hit0 ? (uint32_t)s0.y : (uint32_t)s1.y;
+    const uint32_t ln = hit0 ? (uint32_t)s0.z : (hit1 ? (uint32_t)s1.z : 0u);
+    const uint4 c = hit0 ? c0 : c1;
+    const uint32_t lo = (q == 0) ? 0u : (q == 1) ? c.x : (q == 2) ? c.y : c.z;
+    const uint32_t hi = (q == 0) ? c.x : (q == 1) ? c.y : (q == 2) ? c.z : ln;
+    *start = st + min(lo, ln);
+    *len = (ln && hi > lo) ? min(hi, ln) - min(lo, ln) : 0u;
+}
+
 // Eq. 4-8 for one (row, band): u windowed argmaxes (strict '>', so the lowest k wins a tie),
 // packed with the first code in the most significant bits.
 template <typename ET>
@@ -162,6 +192,7 @@ struct CandArgs {
     int V;
     const int32_t* topfreq;  // [T]
     int T;
+    const uint4* cuts;       // per slot: where the vocabulary slices 1, 2, 3 begin inside its span
 };
 
 // Builds sentence s's presence bitmap (V bits, at smem[0 .. ceil(V/32))) in LDS: hashing, cuckoo
@@ -421,32 +452,34 @@ k_part_bitmaps(CandArgs a, int part_rows, int nparts, uint32_t* __restrict__ par
 
 // ---------------------------------------------------------------------------------------------
 // Threshold t > 1 (Eq. 9-10 in full): the hit matrix L[i, j] counts in how many bands row i and
-// word j collide, and a word is a candidate iff some row reaches t.  One workgroup per hidden
-// row keeps that row of L in LDS as 16-bit counters (the paper keeps L in global memory), walks
-// the row's W spans with one wave per span (Algorithm 1; spans are long here -- ~V / 2^(u bits)
-// words -- so a wave per span is load-balanced enough and needs no search), and leaves the
-// row's thresholded bits as a V-bit bitmap in global memory.  A second kernel ORs the sentence's
-// row bitmaps with the top-frequent words (Eq. 3) and compacts.
+// word j collide, and a word is a candidate iff some row reaches t.  One workgroup per (hidden
+// row, vocabulary slice) keeps its part of that row of L in LDS as 16-bit counters (the paper
+// keeps L in global memory), adds one for every id of the row's W hit spans that falls into the
+// slice (Algorithm 1), and leaves the thresholded bits as its part of the row's V-bit bitmap in
+// global memory.  The consumer ORs the sentence's row bitmaps with the top-frequent words
+// (Eq. 3).
 // ---------------------------------------------------------------------------------------------
 
 // LDS words of k_hit_rows without its load list: counters (2 per word, in blocks of 64 ids), the
 // hidden row, codes (2 per word), scan scratch, three per-span arrays.
 __host__ __device__ inline size_t hit_rows_fixed_lds_words(int V, int d, int P) {
-    return ((size_t)V + 63) / 64 * 32 + (size_t)((d + 3) & ~3) + ((size_t)P + 1) / 2 + 32 +
+    return (size_t)hit_slice_words(V) / 2 + (size_t)((d + 3) & ~3) + ((size_t)P + 1) / 2 + 32 +
            3 * (size_t)kCandThreads + 64;
 }
 constexpr int kHitListMin = 2048, kHitListMax = 16384;  // load-list entries per pass
 
-// grid = S*B workgroups (one per hidden row).  Requires W <= kCandThreads (one span per thread),
-// W * V < 2^30 (a 16-byte group index and a 4-bit mask share a word) and list_cap >= kHitListMin.
+// grid = S*B*kHitSlices workgroups (hidden row r = block / kHitSlices, slice q = block %
+// kHitSlices).  Requires W <= kCandThreads (one span per thread), W * V < 2^30 (a 16-byte group
+// index and a 4-bit mask share a word) and list_cap >= kHitListMin.
 __global__ void __launch_bounds__(kCandThreads)
 k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /*[S*B, nwords]*/) {
     extern __shared__ uint32_t smem[];
     const int V = a.V, d = a.d, P = a.P, K = a.K, W = a.W, bits = a.bits;
     const int u = P / W;
     const int nwords = (V + 31) >> 5;
-    uint32_t* cnt32 = smem;                                            // V 16-bit counters
-    const int ncnt = (V + 63) / 64 * 32;                               // counter words
+    const int Vq = hit_slice_words(V);                                 // ids of a slice
+    uint32_t* cnt32 = smem;                                            // Vq 16-bit counters
+    const int ncnt = Vq / 2;                                           // counter words
     float* rowv = reinterpret_cast<float*>(cnt32 + ncnt);              // the hidden row
     uint16_t* codes = reinterpret_cast<uint16_t*>(rowv + ((d + 3) & ~3));
     uint32_t* wsum = reinterpret_cast<uint32_t*>(codes) + (P + 1) / 2;  // scan scratch
@@ -454,7 +487,8 @@ k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /
     uint32_t* sp_where = sp_pref + kCandThreads + 64;  // first 16-byte group << 2 | misalignment
     uint32_t* sp_len = sp_where + kCandThreads;
     uint32_t* list = sp_len + kCandThreads;        // load list [list_cap]
-    const int r = blockIdx.x;
+    const int r = blockIdx.x / kHitSlices, slice = blockIdx.x % kHitSlices;
+    const int id0 = slice * Vq;                                        // first id of the slice
     const int tid = threadIdx.x, wv = wave_id(), ln = lane_id();
     const float* hrow = a.H + (size_t)r * d;
 
@@ -508,7 +542,7 @@ k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /
         int32_t code = 0;
         for (int q = 0; q < u; ++q) code = (code << bits) | codes[tid * u + q];
         uint32_t start;
-        cuckoo_find(a.slots, my_meta, code, &start, &len);
+        cuckoo_find_slice(a.slots, a.cuts, my_meta, code, slice, &start, &len);
         if (len) {
             const size_t g0 = (size_t)tid * V + start;
             grp0 = (uint32_t)(g0 >> 2);
@@ -538,6 +572,7 @@ k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /
     // of the id its half, so that the thresholding pass below gets whole bitmap words from a
     // ballot over the low halves and one over the high halves.
     auto bump = [&](int32_t id, uint32_t ok) {
+        id -= id0;  // position inside the slice (masked-out ids of neighbouring spans may be outside)
         if (ok) atomicAdd(&cnt32[((id >> 6) << 5) | (id & 31)], (id & 32) ? 0x10000u : 1u);
     };
     for (uint32_t pass0 = 0; pass0 < total; pass0 += (uint32_t)list_cap) {
@@ -596,6 +631,7 @@ k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /
     // that id + 32, so the two ballots are four consecutive bitmap words (in the order
     // lo[31:0], hi[31:0], lo[63:32], hi[63:32]); lanes 0..3 store them.
     uint32_t* out = row_bitmaps + (size_t)r * nwords;
+    const int w0 = id0 >> 5;                          // the slice's first bitmap word
     const int nchunks = (ncnt + kWave - 1) / kWave;   // counters of ids beyond V stay zero
     for (int c0 = wv; c0 < nchunks; c0 += 4 * kCandWaves) {  // four LDS reads in flight
         uint32_t x[4];
@@ -611,7 +647,7 @@ k_hit_rows(CandArgs a, int t, int list_cap, uint32_t* __restrict__ row_bitmaps /
             const uint64_t hi = __ballot((int)(x[q] >> 16) >= t);
             const uint32_t mine = (ln == 0) ? (uint32_t)lo : (ln == 1) ? (uint32_t)hi
                                 : (ln == 2) ? (uint32_t)(lo >> 32) : (uint32_t)(hi >> 32);
-            if (ln < 4 && 4 * c + ln < nwords) out[4 * c + ln] = mine;
+            if (ln < 4 && 4 * c + ln < ncnt / 16 && w0 + 4 * c + ln < nwords) out[w0 + 4 * c + ln] = mine;
         }
     }
     LSH_TRACE(3, 6);

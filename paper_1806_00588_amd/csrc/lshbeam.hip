@@ -60,6 +60,7 @@ struct lsh_tables {
     int32_t* codes_dev = nullptr;    // [V, W] band codes of the embedding rows
     int32_t* words_dev = nullptr;    // [W, V] word ids grouped by band code
     Slot* slots_dev = nullptr;       // all bands' cuckoo slots, concatenated
+    uint4* cuts_dev = nullptr;       // per slot: where vocabulary slices 1..3 begin in its span
     BandMeta* bands_dev = nullptr;   // [W]
     std::vector<HostBand> bands;
     int wg_candidates_lds = 0;
@@ -354,6 +355,7 @@ lsh_status build_on_host(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
     const size_t V = t->V, W = t->W;
     (void)hipFree(t->words_dev); t->words_dev = nullptr;
     (void)hipFree(t->slots_dev); t->slots_dev = nullptr;
+    (void)hipFree(t->cuts_dev); t->cuts_dev = nullptr;
     (void)hipFree(t->bands_dev); t->bands_dev = nullptr;
     t->bands.clear();
     std::vector<Slot> slots_host;
@@ -387,6 +389,24 @@ lsh_status build_on_host(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
 
     // 16 bytes of slack: k_hit_rows reads ids with 16-byte loads that may straddle the end
     HIP_TRY(hipMalloc((void**)&t->words_dev, V * W * sizeof(int32_t) + 16));
+    // where the vocabulary slices of the hit-count kernel begin inside every span
+    std::vector<uint4> cuts_host(slots_host.size(), make_uint4(0u, 0u, 0u, 0u));
+    const int slice_ids = hit_slice_words(t->V);
+    for (size_t w = 0; w < W; ++w) {
+        const BandMeta& m = t->bands[w].meta;
+        for (int i = 0; i < t->bands[w].capacity; ++i) {
+            const Slot& sl = slots_host[m.slot_off + i];
+            if (sl.key < 0) continue;
+            const int32_t* span = words.data() + w * V + sl.start;
+            uint32_t c[3];
+            for (int q = 1; q <= 3; ++q)
+                c[q - 1] = (uint32_t)(std::lower_bound(span, span + sl.len, q * slice_ids) - span);
+            cuts_host[m.slot_off + i] = make_uint4(c[0], c[1], c[2], sl.len);
+        }
+    }
+    HIP_TRY(hipMalloc((void**)&t->cuts_dev, cuts_host.size() * sizeof(uint4)));
+    HIP_TRY(hipMemcpyAsync(t->cuts_dev, cuts_host.data(), cuts_host.size() * sizeof(uint4),
+                           hipMemcpyHostToDevice, st));
     HIP_TRY(hipMalloc((void**)&t->slots_dev, slots_host.size() * sizeof(Slot)));
     HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
     HIP_TRY(hipMemcpyAsync(t->words_dev, words.data(), V * W * sizeof(int32_t), hipMemcpyHostToDevice, st));
@@ -466,6 +486,11 @@ lsh_status build_on_device(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
     const dim3 grdK((n_keys + 255) / 256);
     hipLaunchKernelGGL(k_key_lengths, grdK, blk, 0, st, (const uint32_t*)key_start.p,
                        (const int32_t*)key_band.p, n_keys, (uint32_t)V, key_len.as<uint32_t>());
+    DevBuf key_cut;
+    HIP_TRY(key_cut.alloc(n_keys * sizeof(uint4)));
+    hipLaunchKernelGGL(k_slice_cuts, grdK, blk, 0, st, (const int32_t*)t->words_dev,
+                       (const uint32_t*)key_start.p, (const uint32_t*)key_len.p, (const int32_t*)key_band.p,
+                       n_keys, (uint32_t)V, hit_slice_words(t->V), key_cut.as<uint4>());
 
     // table geometry: a power of two of at least three slots per key and band (load <= 1/3:
     // two-choice cuckoo insertion then succeeds at the first attempt almost always)
@@ -499,6 +524,7 @@ lsh_status build_on_device(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
     HIP_TRY(failed_dev.alloc(W * sizeof(uint32_t)));
     HIP_TRY(hipMalloc((void**)&t->bands_dev, W * sizeof(BandMeta)));
     HIP_TRY(hipMalloc((void**)&t->slots_dev, n_slots * sizeof(Slot)));
+    HIP_TRY(hipMalloc((void**)&t->cuts_dev, n_slots * sizeof(uint4)));
     HIP_TRY(hipMemcpyAsync(caps_dev.p, caps.data(), W * sizeof(uint32_t), hipMemcpyHostToDevice, st));
     const dim3 grdClear((unsigned)std::min<uint64_t>(64, ((1ull << max_lg) + 255) / 256), (unsigned)W);
     // LSHBEAM_CUCKOO_CHAIN shortens the eviction chains (tests of the retry and fallback paths)
@@ -527,7 +553,7 @@ lsh_status build_on_device(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
     if (!done) return LSH_ERR_BUILD_FAILED;
     hipLaunchKernelGGL(k_cuckoo_finalize, dim3((unsigned)((n_slots + 255) / 256)), blk, 0, st,
                        (const uint64_t*)table.p, n_slots, (const uint32_t*)key_start.p,
-                       (const uint32_t*)key_len.p, t->slots_dev);
+                       (const uint32_t*)key_len.p, (const uint4*)key_cut.p, t->slots_dev, t->cuts_dev);
     HIP_TRY(hipGetLastError());
 
     // host mirrors for the inspection calls: distinct codes and span boundaries of every band
@@ -586,6 +612,7 @@ void lsh_free_tables(lsh_tables* t) {
     (void)hipFree(t->codes_dev);
     (void)hipFree(t->words_dev);
     (void)hipFree(t->slots_dev);
+    (void)hipFree(t->cuts_dev);
     (void)hipFree(t->bands_dev);
     for (int k = 0; k < LSH_NUM_KERNELS; ++k)
         for (hipEvent_t e : t->prof.ev[k]) (void)hipEventDestroy(e);
@@ -709,13 +736,13 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     const int32_t* cand = nullptr;
     const int32_t* count = nullptr;
     const CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
-                      t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T};
+                      t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T, t->cuts_dev};
     // Bitmaps made by an earlier kernel, to be OR-ed per sentence: one per hidden row when the
     // hit threshold is above 1 (Eq. 9-10), one per part of the sentence when it has many beams.
     const uint32_t* parts = nullptr;
     int nparts = 0;
     if (!sp->full_vocab && sp->threshold > 1) {
-        launch(t, 3, k_hit_rows, dim3(sp->S * sp->B), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds, st,
+        launch(t, 3, k_hit_rows, dim3(sp->S * sp->B * kHitSlices), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds, st,
                ca, (int)sp->threshold, t->hit_list_cap, w.row_bitmaps);
         parts = w.row_bitmaps;
         nparts = sp->B;

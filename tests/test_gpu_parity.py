@@ -218,6 +218,14 @@ def test_tiny_hit_thresholds():
     assert np.all(gb == -1) and np.all(gw == -1) and np.all(np.isneginf(gs))
 
 
+def test_large_vocabulary_hit_threshold():
+    # V = 200000 bf16: 16 bands, t = 2..3; the hit counters of a row are spread over four workgroups
+    cfg, gc = case("largevocab")
+    H = hidden(cfg, gc, 1)[0][:30]
+    for t, S, B in [(2, 3, 10), (3, 1, 10)]:
+        run_and_check(cfg, gc, H[:S * B], np.zeros(S * B, np.float32), S, B, threshold=t, check_lp=False)
+
+
 def test_paper_banding_with_hit_threshold():
     """{K, u, W} = {8, 3, 500} on the Table 1 shape: thousands of hits per row, t selects."""
     cfg, gc = case("paperscale")
@@ -482,16 +490,19 @@ def test_argument_validation_returns_codes_and_leaves_outputs_untouched():
     assert torch.all(ob == 42) and torch.all(ow == 42) and torch.all(osc == 42.0)
     assert lsh.step_workspace_bytes(gc.tables, binding.step_params(0, 4, 0)) == 0
     assert lsh.step_workspace_bytes(gc.tables, binding.step_params(1, 257, 0)) == 0
-    # t > 1 keeps V 16-bit hit counters in LDS: 200000 words do not fit
-    _, big = case("largevocab")
-    Hb = torch.zeros(10, 1024, device="cuda")
-    spb = binding.step_params(1, 10, 0, threshold=2)
-    wsb = torch.empty(lsh.step_workspace_bytes(big.tables, spb), dtype=torch.uint8, device="cuda")
+    # t > 1 keeps a quarter of V as 16-bit hit counters in LDS: 400000 words do not fit
+    rng = np.random.default_rng(0)
+    Eb = to_dev(rng.standard_normal((400000, 16)).astype(np.float32))
+    pb = to_dev(np.stack([rng.permutation(16)[:4] for _ in range(4)]).astype(np.int32))
+    big = lsh.build_tables(Eb, pb, 4, 2)
+    Hb = torch.zeros(3, 16, device="cuda")
+    spb = binding.step_params(1, 3, 0, threshold=2)
+    wsb = torch.empty(lsh.step_workspace_bytes(big, spb), dtype=torch.uint8, device="cuda")
     with pytest.raises(lsh.LshBeamError) as e:
-        lsh.decode_step(big.tables, Hb, torch.zeros(10, device="cuda"), None, spb, wsb,
-                        torch.zeros(1, 10, dtype=torch.int32, device="cuda"),
-                        torch.zeros(1, 10, dtype=torch.int32, device="cuda"),
-                        torch.zeros(1, 10, device="cuda"))
+        lsh.decode_step(big, Hb, torch.zeros(3, device="cuda"), None, spb, wsb,
+                        torch.zeros(1, 3, dtype=torch.int32, device="cuda"),
+                        torch.zeros(1, 3, dtype=torch.int32, device="cuda"),
+                        torch.zeros(1, 3, device="cuda"))
     assert e.value.status == 2
     # build-time validation
     for K, W in [(1, 4), (8, 3), (8, 0), (8, 1)]:          # (8, 1): u * bits = 48 > 30
