@@ -224,6 +224,10 @@ def test_large_vocabulary_hit_threshold():
     H = hidden(cfg, gc, 1)[0][:30]
     for t, S, B in [(2, 3, 10), (3, 1, 10)]:
         run_and_check(cfg, gc, H[:S * B], np.zeros(S * B, np.float32), S, B, threshold=t, check_lp=False)
+    # K = 16 (windows longer than the eight entries the kernel preloads), V = 100000
+    cfg, gc = case("widebeam")
+    H = hidden(cfg, gc, 1)[0][:10]
+    run_and_check(cfg, gc, H, np.zeros(10, np.float32), 2, 5, threshold=2, check_lp=False)
 
 
 def test_paper_banding_with_hit_threshold():
