@@ -78,9 +78,9 @@ typedef struct {
     int32_t B;          /* beams per sentence, 1 .. 256; also the number of results per sentence */
     int32_t T;          /* length of the top-frequent word list (may be 0)                       */
     int32_t threshold;  /* t of Eq. 10, >= 1: a word is a candidate iff some row of the sentence
-                           shares at least t band codes with it.  t > 1 keeps a row of 16-bit
-                           hit counters in LDS: LSH_ERR_UNSUPPORTED if V is too large for that
-                           (about 70000 words) or bands * V >= 2^30                          */
+                           shares at least t band codes with it.  t > 1 keeps a quarter of a row
+                           of 16-bit hit counters in LDS: LSH_ERR_UNSUPPORTED if V is too large
+                           for that (about 290000 words) or bands * V >= 2^30                  */
     int32_t full_vocab; /* 1: skip hashing, the candidate list is all of V (Eq. 1-2 as printed)  */
 } lsh_step_params;
 
