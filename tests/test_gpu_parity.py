@@ -192,6 +192,52 @@ def test_paper_shape_steps():
         bs = gc.oracle_sentence(H[step], bs, cfg.B).score.astype(np.float32)
 
 
+def test_paper_shape_as_the_benchmark_runs_it():
+    """The launch configuration bench.py times: a 50-step sentence, steps chained through the
+    returned scores, captured once as a HIP graph and replayed; sampled steps are checked
+    against the oracle (fed with the scores the GPU itself produced for the previous step)."""
+    import torch
+    import paper_1806_00588_amd as lsh
+    from paper_1806_00588_amd import binding
+    cfg, gc = case("paper")
+    n = cfg.steps
+    H = hidden(cfg, gc, n)
+    H_dev = to_dev(H)
+    sp = binding.step_params(cfg.S, cfg.B, cfg.T)
+    ws = torch.empty(lsh.step_workspace_bytes(gc.tables, sp), dtype=torch.uint8, device="cuda")
+    call = binding.make_step_caller(gc.tables, sp, ws, gc.topfreq_dev)
+    zero = torch.zeros(cfg.R, device="cuda")
+    ob = torch.empty((n, cfg.R), dtype=torch.int32, device="cuda")
+    ow = torch.empty((n, cfg.R), dtype=torch.int32, device="cuda")
+    osc = torch.empty((n, cfg.R), device="cuda")
+
+    def run(stream):
+        for i in range(n):
+            prev = zero if i == 0 else osc[i - 1]
+            call(H_dev[i].data_ptr(), prev.data_ptr(), ob[i].data_ptr(), ow[i].data_ptr(),
+                 osc[i].data_ptr(), stream)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = (ob.clone(), ow.clone(), osc.clone())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        ob.fill_(-9); ow.fill_(-9); osc.fill_(0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ob, eager[0]) and torch.equal(ow, eager[1]) and torch.equal(osc, eager[2])
+    b, w, sc = ob.cpu().numpy(), ow.cpu().numpy(), osc.cpu().numpy()
+    for i in (0, 1, 7, 23, 38, n - 1):
+        bs = np.zeros(cfg.R, np.float32) if i == 0 else sc[i - 1]
+        ref = gc.oracle_sentence(H[i], bs, cfg.B)
+        assert_topb_matches(b[i], w[i], sc[i], ref, bs)
+
+
 def test_paper_shape_full_vocab():
     cfg, gc = case("paper")
     H = hidden(cfg, gc, 1)
