@@ -435,7 +435,10 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
 // memory -- gathering candidate rows alone runs at 6.7 TB/s, with an equal stream of hidden-row
 // loads beside it at 3.4 TB/s.  The A operands therefore must not come through the vector memory
 // path at all: a workgroup (WAVES waves, consecutive tiles, so mostly one sentence) stages the
-// sentence's B hidden rows in LDS once and every tile reads them with ds_read_b128.  The row
+// sentence's hidden rows in LDS once and every tile reads them with ds_read_b128.  More rows
+// than LDS holds are taken in groups along gridDim.y: every group reads the candidate rows
+// again (from L2 / the memory-side cache mostly), which is still far less load traffic than
+// hidden rows coming through the vector memory path.  The row
 // pitch is the next value >= d that is 4 modulo 32: consecutive rows then start 4 banks apart
 // and eight lanes x 16 bytes (eight rows, same k) cover all 32 banks exactly once.
 __host__ __device__ inline int hlds_pitch(int d) {
@@ -451,13 +454,15 @@ __host__ __device__ inline size_t hlds_lds_bytes(int S, int rows, int d, int wav
 template <typename ET, int MT, int WAVES, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(WAVES * kWave)
 k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
-              int row0, int Bg /*rows [row0, row0 + Bg) of every sentence, Bg <= 16 MT*/,
+              int group_rows /*blockIdx.y takes rows [y, y + 1) * group_rows of every sentence;
+                               group_rows <= 16 MT*/,
               const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
               float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
               int64_t ppitch) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;
     extern __shared__ uint32_t hsm[];
+    const int row0 = blockIdx.y * group_rows, Bg = min(group_rows, B - row0);
     uint32_t* tile_pref = hsm;
     float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(hsm + ((S + 1 + 3) & ~3));
     float* hl = reinterpret_cast<float*>(hsm + ((S + 1 + 3) & ~3) + WAVES * 4 * kWave);

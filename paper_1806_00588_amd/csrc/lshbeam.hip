@@ -253,12 +253,18 @@ void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, c
                H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
 }
 
-// Launches of k_logits_hlds over the sentence's rows in groups of at most 32 (two groups of 16
-// per launch): a group's rows must fit in LDS.  Up to 78 KB two 8-wave workgroups share a CU,
+// k_logits_hlds over the sentence's rows in groups (gridDim.y): a group's rows must fit in LDS.  Up to 78 KB two 8-wave workgroups share a CU,
 // beyond that one 16-wave workgroup has it alone.  Returns false if even one 16-row group does
 // not fit (very large d): the caller then keeps the hidden rows in global memory.
 constexpr size_t kHldsHalf = 78 * 1024;
 inline int hlds_group_rows(int S, int B, int d) {
+    const int forced = env_int("LSHBEAM_HLDS_ROWS", 0);  // 16 or 32 (measurements)
+    if (forced == 16 || forced == 32)
+        return hlds_lds_bytes(S, std::min(forced, B), d, 16) <= kMaxDynLds ? std::min(forced, B) : 0;
+    // up to 32 beams: one group; more: groups of 16 along gridDim.y (measured at S = 4: B = 50,
+    // V = 100k: 51 us with groups of 16, 46 with 32, 55 with the rows in global memory; B = 48,
+    // V = 40k: 48 / 54 / 51)
+    if (B > 32) return hlds_lds_bytes(S, 16, d, 16) <= kMaxDynLds ? 16 : 0;
     for (int rows : {32, 16})
         if (hlds_lds_bytes(S, std::min(rows, B), d, 16) <= kMaxDynLds) return std::min(rows, B);
     return 0;
@@ -279,21 +285,22 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
         if (lds > 48 * 1024)                                                                         \
             (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                       (int)lds);                                                     \
-        const int grid = (int)std::min<int64_t>(tiles_n, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV)); \
-        launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
-               row0, rows, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);             \
+        const int gx = (int)std::min<int64_t>(                                                       \
+            tiles_n, std::max(1, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV) / ngroups));              \
+        launch(t, 1, kfn, dim3(gx, ngroups), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S,   \
+               sp->B, rows, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);            \
     } while (0)
-    for (int row0 = 0; row0 < sp->B; row0 += group_rows) {
-        const int rows = std::min(group_rows, sp->B - row0);
-        const bool two = rows > kTileM;
-        const bool small = hlds_lds_bytes(sp->S, rows, t->d, 8) <= kHldsHalf;
-        if (small) {
-            if (two) { if (aligned) LSH_HLDS(2, 8, U2, true); else LSH_HLDS(2, 8, U2, false); }
-            else { if (aligned) LSH_HLDS(1, 8, U1, true); else LSH_HLDS(1, 8, U1, false); }
-        } else {
-            if (two) { if (aligned) LSH_HLDS(2, 16, U2W, true); else LSH_HLDS(2, 16, U2W, false); }
-            else { if (aligned) LSH_HLDS(1, 16, U1, true); else LSH_HLDS(1, 16, U1, false); }
-        }
+    // one launch: gridDim.y = groups of `rows` hidden rows (the last group may be smaller)
+    const int rows = std::min(group_rows, sp->B);
+    const int ngroups = (sp->B + rows - 1) / rows;
+    const bool two = rows > kTileM;
+    const bool small = hlds_lds_bytes(sp->S, rows, t->d, 8) <= kHldsHalf;
+    if (small) {
+        if (two) { if (aligned) LSH_HLDS(2, 8, U2, true); else LSH_HLDS(2, 8, U2, false); }
+        else { if (aligned) LSH_HLDS(1, 8, U1, true); else LSH_HLDS(1, 8, U1, false); }
+    } else {
+        if (two) { if (aligned) LSH_HLDS(2, 16, U2W, true); else LSH_HLDS(2, 16, U2W, false); }
+        else { if (aligned) LSH_HLDS(1, 16, U1, true); else LSH_HLDS(1, 16, U1, false); }
     }
 #undef LSH_HLDS
 }
@@ -314,14 +321,10 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     // are "many" even for one sentence -- 29.9 against 37.1 us at V = 40000)
     const bool few = sp->S * MT <= 8 && !(count == nullptr && tiles_n >= 1024);
     const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : 1);
-    // one wave per tile with the sentence's hidden rows staged in LDS, the rows taken in groups
-    // of at most 32 (one launch each); LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory
-    // (measured: with more than 32 beams -- two or more launches, each over the few tiles of a
-    // few sentences -- the grouped form is slower than one launch with the rows in global
-    // memory: 75 against 55 us at S = 4, B = 50; LSHBEAM_LOGITS_HLDS=2 forces it anyway)
+    // one wave per tile with the sentence's hidden rows staged in LDS, more than 32 rows in
+    // groups along gridDim.y; LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory (k_logits_wave)
     const int group_rows = hlds_group_rows(sp->S, sp->B, t->d);
-    const int want_hlds = env_int("LSHBEAM_LOGITS_HLDS", 1);
-    if (mode == 1 && group_rows > 0 && (want_hlds == 2 || (want_hlds == 1 && sp->B <= group_rows))) {
+    if (mode == 1 && group_rows > 0 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
         launch_logits_hlds<ET>(t, st, tiles_n, aligned, H, sp, cand, count, w, group_rows);
     } else if (mode == 1 && MT <= 4) {
         const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, env_int("LSHBEAM_LOGITS_GRID", 1024));

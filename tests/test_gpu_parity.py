@@ -479,14 +479,16 @@ def test_paper_shape_wide_beams():
         run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(B == 24))
 
 
-@pytest.mark.parametrize("hlds", ["0", "2"])
-def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, monkeypatch):
-    # many-tile steps stage the sentence's hidden rows in LDS (rows in groups of 32, one launch
-    # each, when forced for more than 32 beams); LSHBEAM_LOGITS_HLDS=0 reads them from global memory
+@pytest.mark.parametrize("hlds,rows", [("0", "0"), ("1", "0"), ("1", "32"), ("1", "16")])
+def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, rows, monkeypatch):
+    # many-tile steps stage the sentence's hidden rows in LDS (more than 32 beams: in groups of 16
+    # rows along the grid's second dimension; LSHBEAM_HLDS_ROWS forces a group size);
+    # LSHBEAM_LOGITS_HLDS=0 reads them from global memory
     cfg, gc = case("tiny")
     monkeypatch.setenv("LSHBEAM_FUSED", "0")
     monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
     monkeypatch.setenv("LSHBEAM_LOGITS_HLDS", hlds)
+    monkeypatch.setenv("LSHBEAM_HLDS_ROWS", rows)
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)
     rng = np.random.default_rng(3)
