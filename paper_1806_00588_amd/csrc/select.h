@@ -8,12 +8,14 @@
 //      combined from those pairs, so no exponential is taken per logit here -- and the tile
 //      maxima are all this kernel needs to read of most of the logits:
 //   2. score = beam_score + (logit - lse).  Every lane keeps the best tile-maximum score it
-//      strides over; per wave the k-th largest of the 64 lane values (bitwise descent on wave
-//      ballots, scalar registers) gives lower bounds tau on the B-th largest score overall,
-//      because B distinct scores (the maxima of B different tiles) are >= tau.
-//   3. Only tiles whose maximum reaches tau can hold a winner: their 16 logits are read and the
-//      scores >= tau -- a few B on unordered data -- are appended to a short LDS list, which is
-//      ranked by counting: that sorts it and the first B are the answer.
+//      strides over; the B-th largest of lane values (per wave by ranking for up to 16 beams,
+//      over the whole workgroup by an LDS radix histogram for more) is a lower bound tau on the
+//      B-th largest score overall, because B distinct scores (the maxima of B different tiles)
+//      are >= tau.
+//   3. Only tiles whose maximum reaches tau can hold a winner: they are listed workgroup-wide,
+//      their 16 logits are read by the whole workgroup, and the scores >= tau -- a few B on
+//      unordered data -- are appended to a short LDS list, which is ranked by counting: that
+//      sorts it and the first B are the answer.
 //   4. If the list overflows (heavily tied scores, or fewer tiles than beams) an exact 8-bit
 //      radix select over all scores takes over.
 //
@@ -41,29 +43,13 @@ __device__ __forceinline__ uint64_t make_key(float v, uint32_t index) {
 __device__ __forceinline__ float key_value(uint64_t k) { return sortable_f32((uint32_t)(k >> 32)); }
 __device__ __forceinline__ uint32_t key_index(uint64_t k) { return ~(uint32_t)k; }
 
-// The k-th largest, k in 1..64, of the 64 lanes' values (0 if fewer than k lanes are non-zero).
-// Wave-uniform result; everything lives in scalar registers.  All 32 bits are resolved: scores
-// accumulate over the steps of a sentence, and at |score| ~ 300 the low 12 bits of an fp32 span
-// 0.1 -- a threshold that coarse would let thousands of scores through.
-__device__ __forceinline__ uint32_t wave_kth_largest_lb(uint32_t v, int k) {
-    uint64_t active = ~0ull;
-    uint32_t kth = 0;
-    int need = k;
-#pragma unroll 4
-    for (int bit = 31; bit >= 0; --bit) {
-        const uint64_t ones = __ballot((v >> bit) & 1u) & active;
-        const int c = __popcll(ones);
-        if (c >= need) { active = ones; kth |= 1u << bit; }
-        else { need -= c; active &= ~ones; }
-    }
-    return kth;
-}
-
-// The k-th largest, k in 1..64, of the 64 lanes' values by ranking instead of bit descent: the
-// values travel once around the wave (DPP wave rotate by one lane), every lane counts how many
-// are greater and how many are at least its own; the lanes with greater < k <= at-least hold
-// the answer.  ~5 vector instructions per lane visited and no scalar dependency chain, against
-// ~10 dependent scalar instructions per bit for the descent.
+// The k-th largest, k in 1..64, of the 64 lanes' values, all 32 bits resolved (scores accumulate
+// over the steps of a sentence, and at |score| ~ 300 the low 12 bits of an fp32 span 0.1 -- a
+// threshold that coarse would let thousands of scores through).  By ranking: the values travel
+// once around the wave (DPP wave rotate by one lane), every lane counts how many are greater and
+// how many are at least its own; the lanes with greater < k <= at-least hold the answer.  ~5
+// vector instructions per lane visited and no scalar dependency chain, against ~10 dependent
+// scalar instructions per bit for a bitwise descent on ballots.
 __device__ __forceinline__ uint32_t wave_kth_largest_rank(uint32_t v, int k) {
     uint32_t x = v;
     int gt = 0, ge = 1;  // itself

@@ -14,11 +14,6 @@ __device__ unsigned long long g_trace[kTraceKernels][kTraceSlots];
         if (blockIdx.x == 0 && threadIdx.x == 0)                                  \
             lshbeam::g_trace[kernel][slot] = wall_clock64();                      \
     } while (0)
-#define LSH_TRACE_ANY(kernel, slot)                                               \
-    do {                                                                          \
-        if (threadIdx.x == 0) lshbeam::g_trace[kernel][slot] = wall_clock64();    \
-    } while (0)
 #else
 #define LSH_TRACE(kernel, slot) do { } while (0)
-#define LSH_TRACE_ANY(kernel, slot) do { } while (0)
 #endif
