@@ -45,18 +45,21 @@ __host__ __device__ __forceinline__ uint32_t cuckoo_hash(uint32_t a, uint32_t b,
     return (a * key + b) >> shift;
 }
 
-// Both slots are loaded unconditionally: no dependent second probe, no divergence.
-__device__ __forceinline__ void cuckoo_find(const Slot* __restrict__ slots, const BandMeta& m,
-                                            int32_t code, uint32_t* start, uint32_t* len) {
+// Both slots are loaded unconditionally: no dependent second probe, no divergence.  In two
+// halves for callers that have other work to do while the loads are in flight.
+__device__ __forceinline__ void cuckoo_load(const Slot* __restrict__ slots, const BandMeta& m,
+                                            int32_t code, int4* s0, int4* s1) {
     const uint32_t h0 = cuckoo_hash(m.a0, m.b0, (uint32_t)code, m.shift);
     const uint32_t h1 = cuckoo_hash(m.a1, m.b1, (uint32_t)code, m.shift);
-    const int4 s0 = *reinterpret_cast<const int4*>(slots + m.slot_off + h0);
-    const int4 s1 = *reinterpret_cast<const int4*>(slots + m.slot_off + h1);
+    *s0 = *reinterpret_cast<const int4*>(slots + m.slot_off + h0);
+    *s1 = *reinterpret_cast<const int4*>(slots + m.slot_off + h1);
+}
+__device__ __forceinline__ void cuckoo_resolve(const int4& s0, const int4& s1, int32_t code,
+                                               uint32_t* start, uint32_t* len) {
     const bool hit0 = s0.x == code, hit1 = s1.x == code;
     *start = hit0 ? (uint32_t)s0.y : (uint32_t)s1.y;
     *len = hit0 ? (uint32_t)s0.z : (hit1 ? (uint32_t)s1.z : 0u);
 }
-
 // The hit-count kernel (threshold t > 1) cuts the vocabulary into kHitSlices ranges of
 // hit_slice_words(V) ids and gives every (hidden row, slice) its own workgroup.  Spans are sorted
 // by id, so the part of a span that falls into slice q is contiguous; where slices 1, 2, 3 begin
@@ -67,7 +70,7 @@ __host__ __device__ inline int hit_slice_words(int V) {  // ids per slice: a mul
     return (((V + kHitSlices - 1) / kHitSlices) + 127) & ~127;
 }
 
-// cuckoo_find restricted to vocabulary slice q: (start, len) of the span's part inside it.  The
+// The probe restricted to vocabulary slice q: (start, len) of the span's part inside it.  The
 // cut positions of both candidate slots are loaded along with the slots (no dependent load).
 __device__ __forceinline__ void cuckoo_find_slice(const Slot* __restrict__ slots,
                                                   const uint4* __restrict__ cuts, const BandMeta& m,
@@ -155,29 +158,32 @@ __device__ __forceinline__ int last_not_above(const uint32_t* pref, uint32_t e) 
 // inside the wave first and one lane issues the atomic: same-address LDS atomics serialise, and
 // frequent-word ids tend to be consecutive.  `first` is this thread's already loaded list[tid]
 // (or -1).  Called by all kCandThreads threads.
+__device__ __forceinline__ void mark_ids_of_wave(uint32_t* bm, int V, int32_t id) {
+    const int ln = lane_id();
+    const bool ok = id >= 0 && id < V;
+    const uint32_t word = ok ? (uint32_t)(id >> 5) : 0xFFFFFFFFu;
+    const uint32_t bit = ok ? (1u << (id & 31)) : 0u;
+    uint64_t todo = __ballot(ok);
+    bool grouped = true;
+    while (todo && grouped) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t w0 = wave_read_lane(word, leader);
+        const bool mine = ok && word == w0;
+        const uint64_t grp = __ballot(mine);
+        const uint32_t ored = wave_or(mine ? bit : 0u);
+        if (ln == leader) atomicOr(&bm[w0], ored);
+        todo &= ~grp;
+        grouped = __popcll(grp) > 1;  // scattered ids: stop grouping, plain atomics below
+    }
+    if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
+}
 __device__ __forceinline__ void mark_id_list(uint32_t* bm, int V, const int32_t* __restrict__ list,
                                              int T, int32_t first) {
-    const int tid = threadIdx.x, ln = lane_id();
-    for (int i0 = 0; i0 < T; i0 += kCandThreads) {
-        const int i = i0 + tid;
-        const int32_t id = (i0 == 0) ? first : ((i < T) ? list[i] : -1);
-        const bool ok = id >= 0 && id < V;
-        const uint32_t word = ok ? (uint32_t)(id >> 5) : 0xFFFFFFFFu;
-        const uint32_t bit = ok ? (1u << (id & 31)) : 0u;
-        uint64_t todo = __ballot(ok);
-        bool grouped = true;
-        while (todo && grouped) {
-            const int leader = __ffsll((unsigned long long)todo) - 1;
-            const uint32_t w0 = wave_read_lane(word, leader);
-            const bool mine = ok && word == w0;
-            const uint64_t grp = __ballot(mine);
-            const uint32_t ored = wave_or(mine ? bit : 0u);
-            if (ln == leader) atomicOr(&bm[w0], ored);
-            todo &= ~grp;
-            grouped = __popcll(grp) > 1;  // scattered ids: stop grouping, plain atomics below
-        }
-        if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
-    }
+    // the first round has its ids in registers: kept apart from the loop so that it contains no
+    // load (and no wait that would also cover loads the caller has in flight)
+    if (T > 0) mark_ids_of_wave(bm, V, first);
+    for (int i = kCandThreads + (int)threadIdx.x; i - (int)threadIdx.x < T; i += kCandThreads)
+        mark_ids_of_wave(bm, V, (i < T) ? list[i] : -1);
 }
 
 // Arguments of candidate generation (everything k_candidates takes except its outputs).
@@ -224,6 +230,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     const int rows_per_chunk = candidates_rows_per_chunk(B, d, W);
     if (row_end < 0) row_end = B;
     LSH_TRACE(0, 0);
+    LSH_TRACE_WG(0);
 
     // Everything whose address is known up front is requested before anything is waited for:
     // this thread's band descriptor (its (row-in-chunk, band) pair is fixed), its first
@@ -249,12 +256,10 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     for (int i = tid; i < nwords; i += kCandThreads) bm[i] = 0u;
     if (tid < P * K) lperms[tid] = perm_first;
     for (int i = tid + kCandThreads; i < P * K; i += kCandThreads) lperms[i] = perms[i];
-    __syncthreads();
     LSH_TRACE(0, 1);
-
-    // Eq. 3: the top-frequent words are members of every candidate list.
-    mark_id_list(bm, V, topfreq, T, tf_first);
-    LSH_TRACE(0, 11);
+    // (no barrier here: the first chunk's staging barrier below also covers the cleared bitmap
+    // and the staged permutations)
+    bool topfreq_marked = false;
 
     for (int row0 = row_begin; row0 < row_end; row0 += rows_per_chunk) {
         const int rows = min(rows_per_chunk, row_end - row0);
@@ -285,6 +290,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         LSH_TRACE(0, 12);
         __syncthreads();
         LSH_TRACE(0, 2);
+        LSH_TRACE_WG(1);
 
         // Eq. 4-5: one thread per (row, permutation) takes the windowed argmax from the staged
         // row (strict '>' in window order, so the lowest k wins a tie); codes go to LDS.  When
@@ -320,20 +326,37 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         }
         // Eq. 6-8 (first code most significant), then Algorithm 1 lines 1-2 for this pair
         uint32_t start = 0, len = 0, w = 0;
+        int32_t code = 0;
+        int4 slot0, slot1;
         if (tid < npairs) {
             const int i = tid / W;
             w = my_w;
-            int32_t code = 0;
             for (int q = 0; q < u; ++q) {
                 const int best = par_codes
                     ? (int)codes[i * P + (int)w * u + q]
                     : wta(stage + (size_t)i * d, lperms + ((size_t)w * u + q) * K);
                 code = (code << bits) | best;
             }
-            cuckoo_find(slots, my_meta, code, &start, &len);
         }
+        // (threads without a pair probe code 0 of their band and drop the result: a load inside
+        // the branch would have to be waited for where the branch ends)
+        cuckoo_load(slots, my_meta, code, &slot0, &slot1);
+        // Eq. 3: the top-frequent words are members of every candidate list.  Marked here, while
+        // the first chunk's probes are on their way (the bitmap was cleared before the staging
+        // barrier; every consumer of the bitmap comes after the barrier that ends the chunk).
+        if (!topfreq_marked) {
+            mark_id_list(bm, V, topfreq, T, tf_first);
+            topfreq_marked = true;
+            LSH_TRACE(0, 11);
+        }
+        // (the compiler would otherwise compare the slots -- and wait for them -- right after
+        // the loads, before the marking; this pins their first use here)
+        asm volatile("" : "+v"(slot0.x), "+v"(slot0.y), "+v"(slot0.z), "+v"(slot1.x), "+v"(slot1.y),
+                          "+v"(slot1.z) :: "memory");
+        if (tid < npairs) cuckoo_resolve(slot0, slot1, code, &start, &len);
         __syncthreads();  // codes[] aliases p_pref
         LSH_TRACE(0, 3);
+        LSH_TRACE_WG(2);
         uint32_t total;
         const uint32_t incl = block_incl_scan(len, wsum, &total);
         LSH_TRACE(0, 4);
@@ -353,8 +376,13 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         }
         __syncthreads();
         LSH_TRACE(0, 5);
+        LSH_TRACE_WG(3);
     }
-
+    if (!topfreq_marked) {  // no rows to hash
+        __syncthreads();
+        mark_id_list(bm, V, topfreq, T, tf_first);
+        __syncthreads();
+    }
 }
 
 // Compaction of a V-bit LDS bitmap into the ascending id list out[0..count) (Eq. 10's selection

@@ -131,12 +131,13 @@ __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wsum, 
     uint32_t incl = wave_incl_scan(v);
     if (lane_id() == kWave - 1) wsum[wave_id()] = incl;
     __syncthreads();
-    uint32_t base = 0, tot = 0;
-    for (int w = 0; w < nw; ++w) {
-        uint32_t x = wsum[w];
-        if (w < wave_id()) base += x;
-        tot += x;
-    }
+    // every wave scans the (at most 64) wave totals itself, lane l taking wsum[l]: one LDS read
+    // and a DPP scan instead of a serial loop of dependent LDS reads
+    const uint32_t x = (lane_id() < nw) ? wsum[lane_id()] : 0u;
+    const uint32_t sc = wave_incl_scan(x);
+    const int wv = __builtin_amdgcn_readfirstlane(wave_id());
+    const uint32_t base = wv ? wave_read_lane(sc, wv - 1) : 0u;
+    const uint32_t tot = wave_read_lane(sc, nw - 1);
     __syncthreads();
     *total = tot;
     return incl + base;

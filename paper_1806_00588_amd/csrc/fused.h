@@ -67,6 +67,7 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
     if (tid == 0) wpref[npow] = total;
     __syncthreads();
     LSH_TRACE(0, 6);
+    LSH_TRACE_WG(4);
     const int C = (int)total;
     if (g == 0 && tid == 0) count[s] = C;
 
@@ -92,7 +93,7 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
         const int32_t id = (int32_t)((lo << 5) + pos);
         if (tid < kTileN && nt * kTileN + col < C) cand[(size_t)s * V + nt * kTileN + col] = id;
         LSH_TRACE(1, 2);
-        logits_tile_all_rows<ET, kFusedWaves, 4, ALIGNED>(E, ld, d, H, B, s, nt, C, (int64_t)id, logits,
+        logits_tile_all_rows<ET, kFusedWaves, 64 / kFusedWaves, ALIGNED>(E, ld, d, H, B, s, nt, C, (int64_t)id, logits,
                                                           cpitch, partials, ppitch, red, h_lds);
     }
 }
@@ -122,6 +123,7 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
         h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
     tiles_from_bitmap<ET, ALIGNED>(bm, wsum, wpref, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
                                    count, logits, cpitch, partials, ppitch);
+    LSH_TRACE_WG(6);
 }
 
 // The same with the hashing done by an earlier kernel: the sentence's bitmap is the union of

@@ -142,11 +142,13 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
     }
 
     LSH_TRACE(1, 3);
+    LSH_TRACE_WG(5);
 #pragma unroll
     for (int m = 0; m < MTB; ++m) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[wv][r][ln] = acc[m][r];
         __syncthreads();
+        LSH_TRACE_WG(7);
         if (tid < kTileM * kTileN) {
             const int i = tid >> 4, jc = tid & 15;
             const int src = (i >> 2) * 16 + jc, r = i & 3;

@@ -1013,6 +1013,11 @@ int lsh_trace_read(unsigned long long* out_host) {
     return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace),
                                sizeof(unsigned long long) * kTraceKernels * kTraceSlots) != hipSuccess;
 }
+int lsh_trace_read_wg(unsigned long long* out_host) {
+    if (hipDeviceSynchronize() != hipSuccess) return 1;
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace_wg),
+                               sizeof(unsigned long long) * kTraceWgs * kTraceWgSlots) != hipSuccess;
+}
 #endif
 
 }  // extern "C"

@@ -43,24 +43,57 @@ __device__ __forceinline__ uint64_t make_key(float v, uint32_t index) {
 __device__ __forceinline__ float key_value(uint64_t k) { return sortable_f32((uint32_t)(k >> 32)); }
 __device__ __forceinline__ uint32_t key_index(uint64_t k) { return ~(uint32_t)k; }
 
-// The k-th largest, k in 1..64, of the 64 lanes' values, all 32 bits resolved (scores accumulate
+// The k-th largest, k in 1..16, of the 64 lanes' values, all 32 bits resolved (scores accumulate
 // over the steps of a sentence, and at |score| ~ 300 the low 12 bits of an fp32 span 0.1 -- a
-// threshold that coarse would let thousands of scores through).  By ranking: the values travel
-// once around the wave (DPP wave rotate by one lane), every lane counts how many are greater and
-// how many are at least its own; the lanes with greater < k <= at-least hold the answer.  ~5
-// vector instructions per lane visited and no scalar dependency chain, against ~10 dependent
-// scalar instructions per bit for a bitwise descent on ballots.
-__device__ __forceinline__ uint32_t wave_kth_largest_rank(uint32_t v, int k) {
+// threshold that coarse would let thousands of scores through).  A sorting network on the DPP
+// lane-permute paths: (1) every row of 16 lanes is sorted descending by a bitonic sort whose
+// merges start with a mirror (partner = lane ^ (block - 1)), so that every compare-exchange
+// points the same way and every partner pattern but "lane ^ 4" is one DPP modifier; (2) two
+// sorted rows A, B are merged into the 16 largest of both by max(A[i], B[15 - i]) -- a bitonic
+// sequence, sorted by four more butterfly stages -- first rows 0|1 and 2|3, then the two halves
+// of the wave (these two exchanges cross rows and go through the LDS crossbar).  Every row ends
+// up holding the wave's 16 largest in descending lane order.  ~90 vector instructions, against
+// ~320 for ranking every lane against every other and ~10 dependent scalar instructions per bit
+// for a bitwise descent on ballots.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_lane_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xf, 0xf, false);
+}
+__device__ __forceinline__ uint32_t dpp_lane_xor4(uint32_t x) {
+    // lanes 0-3, 8-11 of a row read four lanes up (row_shl:4), the others four lanes down
+    const int t = __builtin_amdgcn_update_dpp(0, (int)x, 0x104, 0xf, 0x5, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(t, (int)x, 0x114, 0xf, 0xa, false);
+}
+__device__ __forceinline__ uint32_t keep_max_if(bool upper, uint32_t x, uint32_t p) {
+    return upper ? max(x, p) : min(x, p);
+}
+__device__ __forceinline__ uint32_t wave_kth_largest_sort(uint32_t v, int k) {
+    const int ln = lane_id();
+    const bool b1 = (ln & 1) == 0, b2 = (ln & 2) == 0, b4 = (ln & 4) == 0, b8 = (ln & 8) == 0;
+    constexpr int kXor1 = 0xB1, kXor2 = 0x4E, kXor3 = 0x1B;       // quad_perm
+    constexpr int kXor7 = 0x141, kXor15 = 0x140, kXor8 = 0x128;   // half mirror, mirror, row_ror:8
     uint32_t x = v;
-    int gt = 0, ge = 1;  // itself
+    x = keep_max_if(b1, x, dpp_lane_u32<kXor1>(x));
+    x = keep_max_if(b2, x, dpp_lane_u32<kXor3>(x));
+    x = keep_max_if(b1, x, dpp_lane_u32<kXor1>(x));
+    x = keep_max_if(b4, x, dpp_lane_u32<kXor7>(x));
+    x = keep_max_if(b2, x, dpp_lane_u32<kXor2>(x));
+    x = keep_max_if(b1, x, dpp_lane_u32<kXor1>(x));
+    x = keep_max_if(b8, x, dpp_lane_u32<kXor15>(x));
+    x = keep_max_if(b4, x, dpp_lane_xor4(x));
+    x = keep_max_if(b2, x, dpp_lane_u32<kXor2>(x));
+    x = keep_max_if(b1, x, dpp_lane_u32<kXor1>(x));
 #pragma unroll
-    for (int step = 1; step < kWave; ++step) {
-        x = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x13C /* wave_ror:1 */, 0xf, 0xf, false);
-        gt += (x > v) ? 1 : 0;
-        ge += (x >= v) ? 1 : 0;
+    for (int cross = 0; cross < 2; ++cross) {
+        // partner row, mirrored: lane ^ 31 pairs rows 0|1 and 2|3, lane ^ 47 rows 0|2 and 1|3
+        const int partner = ln ^ (cross == 0 ? 31 : 47);
+        x = max(x, (uint32_t)__builtin_amdgcn_ds_bpermute(partner << 2, (int)x));
+        x = keep_max_if(b8, x, dpp_lane_u32<kXor8>(x));
+        x = keep_max_if(b4, x, dpp_lane_xor4(x));
+        x = keep_max_if(b2, x, dpp_lane_u32<kXor2>(x));
+        x = keep_max_if(b1, x, dpp_lane_u32<kXor1>(x));
     }
-    const uint64_t hit = __ballot(gt < k && k <= ge);
-    return wave_read_lane(v, __ffsll((unsigned long long)hit) - 1);  // some lane always hits
+    return wave_read_lane(x, k - 1);
 }
 
 // Position of this lane among the set lanes of a ballot mask.
@@ -225,6 +258,16 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     const int s = blockIdx.x;
     LSH_TRACE(2, 0);
+    // The first batch of partials of this wave's first row is requested before the candidate
+    // count is known (one memory round trip less): indices are clamped to the row's pitch, which
+    // is allocated, and what lies beyond the last tile is masked after the load like any padding.
+    float2 first_batch[kSelBatch] = {};
+    if (wv < B) {
+        const float2* pr = partials + ((size_t)s * B + wv) * ppitch;
+#pragma unroll
+        for (int q = 0; q < kSelBatch; ++q)
+            first_batch[q] = pr[min((int64_t)(ln + q * kWave), ppitch - 1)];
+    }
     const int C = count ? count[s] : V;
     const int ntiles = (C + 15) >> 4;
     const float* lg = logits + (size_t)s * B * cpitch;
@@ -255,7 +298,8 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     };
     {
         float2 cur[kSelBatch], nxt[kSelBatch];
-        if (nit > 0) load_batch(0, cur);
+#pragma unroll
+        for (int q = 0; q < kSelBatch; ++q) cur[q] = first_batch[q];
         float m = -INFINITY, sum = 0.f, lmx = -INFINITY, bsi = 0.f;
         for (int it = 0; it < nit; ++it) {
             const int r = it / nb, bt = it - r * nb;
@@ -312,7 +356,7 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     //      per bit; with more beams the B-th largest of all 1024 lane values is much tighter. ----
     uint32_t tau;
     if (B <= kSelWaves) {
-        const uint32_t kth = wave_kth_largest_rank(lmax, B);
+        const uint32_t kth = wave_kth_largest_sort(lmax, B);
         if (ln == 0) sh.wtau[wv] = kth;
         __syncthreads();
         tau = 0;

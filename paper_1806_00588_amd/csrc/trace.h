@@ -1,6 +1,7 @@
 // Optional in-kernel phase timestamps (development aid).  Compiled out unless the library is
 // built with -DLSHBEAM_TRACE; then thread 0 of workgroup 0 of each kernel stores the 100 MHz
-// wall clock at marked points into a device array that lsh_trace_read() copies out.
+// wall clock at marked points into a device array that lsh_trace_read() copies out
+// (LSH_TRACE_LATEST: the latest time over all workgroups of the launch).
 #pragma once
 #include <hip/hip_runtime.h>
 
@@ -8,12 +9,27 @@
 namespace lshbeam {
 constexpr int kTraceKernels = 4, kTraceSlots = 16;
 __device__ unsigned long long g_trace[kTraceKernels][kTraceSlots];
+constexpr int kTraceWgs = 512, kTraceWgSlots = 8;
+__device__ unsigned long long g_trace_wg[kTraceWgs][kTraceWgSlots];  // per workgroup (one kernel)
 }
 #define LSH_TRACE(kernel, slot)                                                   \
     do {                                                                          \
         if (blockIdx.x == 0 && threadIdx.x == 0)                                  \
             lshbeam::g_trace[kernel][slot] = wall_clock64();                      \
     } while (0)
+// the latest time any workgroup of the launch passes the point
+#define LSH_TRACE_LATEST(kernel, slot)                                            \
+    do {                                                                          \
+        if (threadIdx.x == 0) atomicMax(&lshbeam::g_trace[kernel][slot], wall_clock64()); \
+    } while (0)
+// thread 0 of every workgroup (of the one kernel that uses this macro)
+#define LSH_TRACE_WG(slot)                                                        \
+    do {                                                                          \
+        if (threadIdx.x == 0 && blockIdx.x < lshbeam::kTraceWgs)                  \
+            lshbeam::g_trace_wg[blockIdx.x][slot] = wall_clock64();               \
+    } while (0)
 #else
+#define LSH_TRACE_WG(slot) do { } while (0)
 #define LSH_TRACE(kernel, slot) do { } while (0)
+#define LSH_TRACE_LATEST(kernel, slot) do { } while (0)
 #endif
