@@ -438,8 +438,8 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
 // loads beside it at 3.4 TB/s.  The A operands therefore must not come through the vector memory
 // path at all: a workgroup (WAVES waves, consecutive tiles, so mostly one sentence) stages the
 // sentence's hidden rows in LDS once and every tile reads them with ds_read_b128.  More rows
-// than LDS holds are taken in groups along gridDim.y: every group reads the candidate rows
-// again (from L2 / the memory-side cache mostly), which is still far less load traffic than
+// than LDS holds are taken in groups, a workgroup each: every group reads the candidate rows
+// again (the groups of a block of tiles run on one XCD, so from its L2 mostly), which is still far less load traffic than
 // hidden rows coming through the vector memory path.  The row
 // pitch is the next value >= d that is 4 modulo 32: consecutive rows then start 4 banks apart
 // and eight lanes x 16 bytes (eight rows, same k) cover all 32 banks exactly once.
@@ -456,15 +456,23 @@ __host__ __device__ inline size_t hlds_lds_bytes(int S, int rows, int d, int wav
 template <typename ET, int MT, int WAVES, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(WAVES * kWave)
 k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
-              int group_rows /*blockIdx.y takes rows [y, y + 1) * group_rows of every sentence;
+              int group_rows /*row group g takes rows [g, g + 1) * group_rows of every sentence;
                                group_rows <= 16 MT*/,
+              int gx /*workgroups per row group*/, int ngroups,
               const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
               float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
               int64_t ppitch) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;
     extern __shared__ uint32_t hsm[];
-    const int row0 = blockIdx.y * group_rows, Bg = min(group_rows, B - row0);
+    // grid = round_up(gx, 8) * ngroups workgroups.  Workgroup ids go round the 8 XCDs, and the
+    // row groups that read the same candidate rows should share an L2: ids that are congruent
+    // modulo 8 and consecutive otherwise form the row groups of one block of tiles.
+    const uint32_t wg_slot = blockIdx.x >> 3;
+    const uint32_t bx = (wg_slot / (uint32_t)ngroups) * 8u + (blockIdx.x & 7u);
+    const int by = (int)(wg_slot % (uint32_t)ngroups);
+    if (bx >= (uint32_t)gx) return;
+    const int row0 = by * group_rows, Bg = min(group_rows, B - row0);
     uint32_t* tile_pref = hsm;
     float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(hsm + ((S + 1 + 3) & ~3));
     float* hl = reinterpret_cast<float*>(hsm + ((S + 1 + 3) & ~3) + WAVES * 4 * kWave);
@@ -486,7 +494,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     __syncthreads();
     LSH_TRACE(1, 1);
     const uint32_t total_tiles = tile_pref[S];
-    const uint32_t nwaves = gridDim.x * (uint32_t)WAVES;
+    const uint32_t nwaves = (uint32_t)gx * (uint32_t)WAVES;
     const int col = ln & 15, kq = ln >> 4;
     const int nks = (d + KSTEP - 1) / KSTEP;
     const uint32_t whole = total_tiles / nwaves * nwaves;
@@ -523,8 +531,8 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
 
     // whole rounds: one wave per tile; the workgroup walks its consecutive tiles sentence by
     // sentence (all of its waves in the same sentence, so one staging serves them)
-    const uint32_t per_wg = (wave_tiles + gridDim.x - 1) / gridDim.x;
-    const uint32_t wg_begin = min(wave_tiles, blockIdx.x * per_wg);
+    const uint32_t per_wg = (wave_tiles + (uint32_t)gx - 1) / (uint32_t)gx;
+    const uint32_t wg_begin = min(wave_tiles, bx * per_wg);
     const uint32_t wg_end = min(wave_tiles, wg_begin + per_wg);
     for (uint32_t seg = wg_begin; seg < wg_end;) {
         const int s = sentence_of(seg);
@@ -643,7 +651,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     LSH_TRACE(1, 4);
 
     // the remainder: one workgroup per tile, k split over its waves, hidden rows from LDS
-    for (uint32_t t = wave_tiles + blockIdx.x; t < total_tiles; t += gridDim.x) {
+    for (uint32_t t = wave_tiles + bx; t < total_tiles; t += (uint32_t)gx) {
         const int s = sentence_of(t);
         stage(s);
         const int nt = (int)(t - tile_pref[s]);

@@ -253,15 +253,16 @@ void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, c
                H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
 }
 
-// k_logits_hlds over the sentence's rows in groups (gridDim.y): a group's rows must fit in LDS.  Up to 78 KB two 8-wave workgroups share a CU,
-// beyond that one 16-wave workgroup has it alone.  Returns false if even one 16-row group does
-// not fit (very large d): the caller then keeps the hidden rows in global memory.
+// k_logits_hlds over the sentence's rows in groups: a group's rows must fit in LDS.  Up to 78 KB
+// two 8-wave workgroups share a CU, beyond that one 16-wave workgroup has it alone.  Returns 0
+// if even one 16-row group does not fit (very large d): the caller then keeps the hidden rows
+// in global memory.
 constexpr size_t kHldsHalf = 78 * 1024;
 inline int hlds_group_rows(int S, int B, int d) {
     const int forced = env_int("LSHBEAM_HLDS_ROWS", 0);  // 16 or 32 (measurements)
     if (forced == 16 || forced == 32)
         return hlds_lds_bytes(S, std::min(forced, B), d, 16) <= kMaxDynLds ? std::min(forced, B) : 0;
-    // up to 32 beams: one group; more: groups of 16 along gridDim.y (measured at S = 4: B = 50,
+    // up to 32 beams: one group; more: groups of 16, a workgroup each (measured at S = 4: B = 50,
     // V = 100k: 51 us with groups of 16, 46 with 32, 55 with the rows in global memory; B = 48,
     // V = 40k: 48 / 54 / 51)
     if (B > 32) return hlds_lds_bytes(S, 16, d, 16) <= kMaxDynLds ? 16 : 0;
@@ -287,10 +288,11 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
                                       (int)lds);                                                     \
         const int gx = (int)std::min<int64_t>(                                                       \
             tiles_n, std::max(1, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV) / ngroups));              \
-        launch(t, 1, kfn, dim3(gx, ngroups), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S,   \
-               sp->B, rows, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);            \
+        const int grid = ((gx + 7) / 8 * 8) * ngroups;                                               \
+        launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
+               rows, gx, ngroups, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);      \
     } while (0)
-    // one launch: gridDim.y = groups of `rows` hidden rows (the last group may be smaller)
+    // one launch: a workgroup serves one group of `rows` hidden rows (the last group may be smaller)
     const int rows = std::min(group_rows, sp->B);
     const int ngroups = (sp->B + rows - 1) / rows;
     const bool two = rows > kTileM;
@@ -322,7 +324,7 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     const bool few = sp->S * MT <= 8 && !(count == nullptr && tiles_n >= 1024);
     const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : 1);
     // one wave per tile with the sentence's hidden rows staged in LDS, more than 32 rows in
-    // groups along gridDim.y; LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory (k_logits_wave)
+    // groups; LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory (k_logits_wave)
     const int group_rows = hlds_group_rows(sp->S, sp->B, t->d);
     if (mode == 1 && group_rows > 0 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
         launch_logits_hlds<ET>(t, st, tiles_n, aligned, H, sp, cand, count, w, group_rows);
