@@ -448,13 +448,29 @@ __host__ __device__ inline int hlds_pitch(int d) {
     while (p % 32 != 4) p += 4;
     return p;
 }
-// dynamic LDS: tile prefix (S + 1 words, rounded to 4), split-k reduction buffer, hidden rows
-__host__ __device__ inline size_t hlds_lds_bytes(int S, int rows, int d, int waves) {
-    return ((size_t)((S + 1 + 3) & ~3) + (size_t)waves * 4 * kWave + (size_t)rows * hlds_pitch(d)) * 4;
+// bf16 candidate rows with 16-byte aligned operands: the hidden rows are staged as three bf16
+// planes hi + mid + lo = h exactly (8 + 8 + 8 significand bits: each plane is the remainder so
+// far truncated to bf16), and the contraction runs on v_mfma_f32_16x16x32_bf16 -- a lane's
+// 16-byte chunk of its candidate row IS that instruction's B operand (8 consecutive k), no
+// widening; three instructions per chunk against eight fp32 ones at a quarter of the cycles each.
+// Products of two bf16 values are exact in fp32, so the result differs from the widened fp32
+// contraction by summation order only.  Plane rows are pitched 8 modulo 64 elements (16 modulo
+// 128 bytes: eight rows x 16 bytes cover all banks once).
+__host__ __device__ inline int hlds_pitch_planes(int d) {
+    int p = (d + 7) & ~7;
+    while (p % 64 != 8) p += 8;
+    return p;
 }
+// dynamic LDS: tile prefix (S + 1 words, rounded to 4), split-k reduction buffer, hidden rows
+// (fp32, or three bf16 planes)
+__host__ __device__ inline size_t hlds_lds_bytes(int S, int rows, int d, int waves, bool planes = false) {
+    const size_t hidden = planes ? (size_t)rows * hlds_pitch_planes(d) * 6 : (size_t)rows * hlds_pitch(d) * 4;
+    return ((size_t)((S + 1 + 3) & ~3) + (size_t)waves * 4 * kWave) * 4 + hidden;
+}
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <typename ET, int MT, int WAVES, int UNROLL, bool ALIGNED>
-__global__ void __launch_bounds__(WAVES * kWave)
+template <typename ET, int MT, int WAVES, int UNROLL, bool ALIGNED, bool PLANES = false>
+__global__ void __launch_bounds__(WAVES * kWave) __attribute__((amdgpu_waves_per_eu(4)))
 k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
               int group_rows /*row group g takes rows [g, g + 1) * group_rows of every sentence;
                                group_rows <= 16 MT*/,
@@ -477,6 +493,11 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
     float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(hsm + ((S + 1 + 3) & ~3));
     float* hl = reinterpret_cast<float*>(hsm + ((S + 1 + 3) & ~3) + WAVES * 4 * kWave);
     const int pitch = hlds_pitch(d);
+    // PLANES (bf16 rows, ALIGNED): hidden rows as three bf16 planes, bf16 matrix instructions
+    static_assert(!PLANES || (ALIGNED && VEC == 8), "bf16 planes need aligned bf16 rows");
+    const int ppitch_h = hlds_pitch_planes(d);
+    uint16_t* hplane = reinterpret_cast<uint16_t*>(hl);
+    const size_t plane_stride = (size_t)group_rows * ppitch_h;
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     LSH_TRACE(1, 0);
     if (wv == 0) {
@@ -512,7 +533,27 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         if (s == staged) return;
         __syncthreads();  // everyone is done with the previous sentence's rows
         const float* Hs = H + ((size_t)s * B + row0) * d;
-        if ((d & 3) == 0 && ((uintptr_t)Hs & 15) == 0) {
+        if constexpr (PLANES) {  // (ALIGNED: d is a multiple of 8 and H is 16-byte aligned)
+            const int d4 = d >> 2;
+            for (int e = tid; e < Bg * d4; e += WAVES * kWave) {
+                const int r = e / d4, c = e - r * d4;
+                const float4 v = reinterpret_cast<const float4*>(Hs)[e];
+                const float x[4] = {v.x, v.y, v.z, v.w};
+                uint32_t pl[3][4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t hi = __float_as_uint(x[q]) & 0xFFFF0000u;
+                    const float r1 = x[q] - __uint_as_float(hi);          // exact
+                    const uint32_t mid = __float_as_uint(r1) & 0xFFFF0000u;
+                    const float r2 = r1 - __uint_as_float(mid);           // exact, <= 8 bits
+                    pl[0][q] = hi >> 16; pl[1][q] = mid >> 16; pl[2][q] = __float_as_uint(r2) >> 16;
+                }
+#pragma unroll
+                for (int pnum = 0; pnum < 3; ++pnum)
+                    *reinterpret_cast<uint2*>(hplane + pnum * plane_stride + (size_t)r * ppitch_h + 4 * c) =
+                        make_uint2(pl[pnum][0] | (pl[pnum][1] << 16), pl[pnum][2] | (pl[pnum][3] << 16));
+            }
+        } else if ((d & 3) == 0 && ((uintptr_t)Hs & 15) == 0) {
             const int d4 = d >> 2;
             for (int e = tid; e < Bg * d4; e += WAVES * kWave) {
                 const int r = e / d4, c = e - r * d4;
@@ -552,7 +593,56 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
             floatx4 acc[MT];
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (ALIGNED) {
+            if constexpr (PLANES) {
+                // the rolling prefetch of the branch below, on raw 16-byte chunks (half the
+                // registers of the widened form, so twice the loads in flight)
+                constexpr int UP = 2 * UNROLL;
+                const uint16_t* hp[MT];
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) hp[mt] = hplane + (size_t)min(mt * kTileM + col, Bg - 1) * ppitch_h;
+                const uint16_t* er = reinterpret_cast<const uint16_t*>(erow);
+                uint4 eb[UP];
+                const int klast = d - VEC;
+#pragma unroll
+                for (int uu = 0; uu < UP; ++uu) {
+                    eb[uu] = *reinterpret_cast<const uint4*>(er + min(uu * KSTEP + kq * VEC, klast));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                uint4 hn[MT][3];
+                auto read_planes = [&](int k, uint4 (&dst)[MT][3]) {
+                    const bool in = k < d;
+                    const int kc = in ? k : 0;
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int pnum = 0; pnum < 3; ++pnum) {
+                            const uint4 h = *reinterpret_cast<const uint4*>(hp[mt] + pnum * plane_stride + kc);
+                            dst[mt][pnum] = in ? h : make_uint4(0u, 0u, 0u, 0u);
+                        }
+                };
+                read_planes(kq * VEC, hn);
+                for (int ks0 = 0; ks0 < nks; ks0 += UP) {
+#pragma unroll
+                    for (int uu = 0; uu < UP; ++uu) {
+                        const int k = (ks0 + uu) * KSTEP + kq * VEC;
+                        uint4 hv[MT][3];
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                            for (int pnum = 0; pnum < 3; ++pnum) hv[mt][pnum] = hn[mt][pnum];
+                        read_planes(k + KSTEP, hn);
+                        const bf16x8 b = __builtin_bit_cast(bf16x8, eb[uu]);
+#pragma unroll
+                        for (int pnum = 0; pnum < 3; ++pnum)
+#pragma unroll
+                            for (int mt = 0; mt < MT; ++mt)
+                                acc[mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                    __builtin_bit_cast(bf16x8, hv[mt][pnum]), b, acc[mt], 0, 0, 0);
+                        eb[uu] = *reinterpret_cast<const uint4*>(er + min(k + UP * KSTEP, klast));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            } else if (ALIGNED) {
                 // Rolling prefetch: UNROLL candidate-row loads stay in flight all the time.  Slot
                 // uu is consumed (LDS read of the hidden rows, VEC matrix instructions) and at
                 // once refilled with the chunk UNROLL k-steps ahead, so memory latency and
@@ -658,8 +748,10 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int C = count ? count[s] : V;
         const int cidx = min(nt * kTileN + col, C - 1);
         const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
+        // (the split-k tile code reads fp32 rows: from global memory when LDS holds bf16 planes)
         logits_tile_all_rows<ET, WAVES, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(
-            E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red, hl, pitch, row0, row0 + Bg);
+            E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red,
+            PLANES ? nullptr : hl, PLANES ? 0 : pitch, row0, row0 + Bg);
     }
 }
 

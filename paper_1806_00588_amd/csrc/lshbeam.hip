@@ -13,6 +13,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <type_traits>
 #include <vector>
 
 #include <hipcub/hipcub.hpp>
@@ -279,10 +280,13 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
     // (1024-thread workgroups have 128 registers per lane: one load less in flight)
     constexpr int U2W = (U2 > 2) ? U2 - 1 : U2;
     const ET* E = (const ET*)t->E;
-#define LSH_HLDS(MTV, WV, UV, AL)                                                                    \
+    // one launch: a workgroup serves one group of `rows` hidden rows (the last group may be smaller)
+    const int rows = std::min(group_rows, sp->B);
+    const int ngroups = (sp->B + rows - 1) / rows;
+#define LSH_HLDS(MTV, WV, UV, AL, PL)                                                                \
     do {                                                                                             \
-        auto kfn = k_logits_hlds<ET, MTV, WV, UV, AL>;                                               \
-        const size_t lds = hlds_lds_bytes(sp->S, rows, t->d, WV);                                    \
+        auto kfn = k_logits_hlds<ET, MTV, WV, UV, AL, PL>;                                           \
+        const size_t lds = hlds_lds_bytes(sp->S, rows, t->d, WV, PL);                                \
         if (lds > 48 * 1024)                                                                         \
             (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, \
                                       (int)lds);                                                     \
@@ -292,17 +296,24 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
         launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
                rows, gx, ngroups, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);      \
     } while (0)
-    // one launch: a workgroup serves one group of `rows` hidden rows (the last group may be smaller)
-    const int rows = std::min(group_rows, sp->B);
-    const int ngroups = (sp->B + rows - 1) / rows;
+    // bf16 rows, up to 16 hidden rows per group, two workgroups per CU: the hidden rows go to LDS
+    // as three bf16 planes and the contraction runs on bf16 matrix instructions
+    // (LSHBEAM_LOGITS_PLANES=0: widened to fp32 as for every other shape)
+    if constexpr (std::is_same<ET, uint16_t>::value) {
+        if (aligned && rows <= kTileM && hlds_lds_bytes(sp->S, rows, t->d, 8, true) <= kHldsHalf &&
+            env_int("LSHBEAM_LOGITS_PLANES", 1)) {
+            LSH_HLDS(1, 8, U1, true, true);
+            return;
+        }
+    }
     const bool two = rows > kTileM;
     const bool small = hlds_lds_bytes(sp->S, rows, t->d, 8) <= kHldsHalf;
     if (small) {
-        if (two) { if (aligned) LSH_HLDS(2, 8, U2, true); else LSH_HLDS(2, 8, U2, false); }
-        else { if (aligned) LSH_HLDS(1, 8, U1, true); else LSH_HLDS(1, 8, U1, false); }
+        if (two) { if (aligned) LSH_HLDS(2, 8, U2, true, false); else LSH_HLDS(2, 8, U2, false, false); }
+        else { if (aligned) LSH_HLDS(1, 8, U1, true, false); else LSH_HLDS(1, 8, U1, false, false); }
     } else {
-        if (two) { if (aligned) LSH_HLDS(2, 16, U2W, true); else LSH_HLDS(2, 16, U2W, false); }
-        else { if (aligned) LSH_HLDS(1, 16, U1, true); else LSH_HLDS(1, 16, U1, false); }
+        if (two) { if (aligned) LSH_HLDS(2, 16, U2W, true, false); else LSH_HLDS(2, 16, U2W, false, false); }
+        else { if (aligned) LSH_HLDS(1, 16, U1, true, false); else LSH_HLDS(1, 16, U1, false, false); }
     }
 #undef LSH_HLDS
 }

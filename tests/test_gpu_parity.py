@@ -322,6 +322,34 @@ def test_largevocab_bf16_shape():
         assert_topb_matches(gb[s], gw[s], gs[s], ref, np.zeros(cfg.B))
 
 
+@pytest.mark.parametrize("planes", ["1", "0"])
+def test_bf16_rows_with_hidden_rows_as_three_bf16_planes(planes, monkeypatch):
+    # bf16 rows, up to 16 beams, many tiles: the hidden rows are staged as hi + mid + lo bf16
+    # planes (an exact split of every fp32 value) and contracted with bf16 matrix instructions;
+    # LSHBEAM_LOGITS_PLANES=0 widens the rows to fp32 instead.  Hidden values span 40 binades,
+    # with full 24-bit significands, signed zeros and tiny values; d = 264 leaves a last k-step
+    # of which only a quarter lies inside the row.
+    monkeypatch.setenv("LSHBEAM_FUSED", "0")
+    monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
+    monkeypatch.setenv("LSHBEAM_LOGITS_PLANES", planes)
+    rng = np.random.default_rng(264)
+    V, d, K, P, W = 3000, 264, 8, 16, 4
+    E32 = (rng.standard_normal((V, d)) / np.sqrt(d)).astype(np.float32)
+    E = workloads.f32_to_bf16_bits(E32)
+    perms = np.stack([rng.permutation(d)[:K] for _ in range(P)]).astype(np.int32)
+    gc = GpuCase(E, perms, np.arange(100, dtype=np.int32), W)
+    H = rng.standard_normal((64, d)).astype(np.float32)
+    H *= np.exp2(rng.integers(-20, 21, size=(64, 1))).astype(np.float32)   # per-row scale
+    H[:, ::7] *= np.float32(1.0 + 2.0 ** -23)                               # low significand bits set
+    H[3, :40] = 0.0
+    H[4, :40] = -0.0
+    H[5, 100:140] = 1e-30
+    cfg = None
+    for S, B in [(3, 10), (2, 16), (5, 1), (2, 20), (4, 7)]:
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B)
+
+
 # ---------------------------------------------------------------------------------------------
 # edge cases
 # ---------------------------------------------------------------------------------------------
