@@ -183,6 +183,34 @@ def test_tiny_many_sentences_and_other_beam_counts():
     run_and_check(cfg, gc, H[:153], np.zeros(153, np.float32), 9, 17, full_vocab=True)
 
 
+def test_maximum_beam_and_sentence_counts():
+    # the largest B (256) and S (4096) the step accepts, and the first values it refuses
+    from paper_1806_00588_amd import binding
+    cfg, gc = case("tiny")
+    base = hidden(cfg, gc, 20).reshape(-1, cfg.d)                 # 80 rows
+    rng = np.random.default_rng(256)
+    mix = rng.standard_normal((4096, 80)).astype(np.float32) / 4
+    H = (mix @ base).astype(np.float32)                           # 4096 rows in the span of the 80
+    H[:80] = base
+    for S, B in [(1, 256), (2, 256), (1, 128), (3, 100)]:
+        bs = (rng.standard_normal(S * B) * 2).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(S == 1 and B == 128))
+    run_and_check(cfg, gc, H[:256], np.zeros(256, np.float32), 1, 256, full_vocab=True, check_lp=False)
+    run_and_check(cfg, gc, H[:256], np.zeros(256, np.float32), 1, 256, threshold=2, check_lp=False)
+    # 4096 sentences of one beam: every output checked against the oracle for a sample of the
+    # sentences, and for all of them that the word is the row's best candidate by the oracle
+    S = 4096
+    bs = rng.standard_normal(S).astype(np.float32)
+    gb, gw, gs, sp, ws = gc.step(H, bs, S, 1)
+    assert np.all(gb == 0)
+    for s in list(range(0, S, 97)) + [S - 1]:
+        ref = gc.oracle_sentence(H[s:s + 1], bs[s:s + 1], 1)
+        assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), ref.cand)
+        assert_topb_matches(gb[s], gw[s], gs[s], ref, bs[s:s + 1])
+    for S_bad, B_bad in [(1, 257), (4097, 1), (0, 4), (4, 0)]:
+        assert gc.lsh.step_workspace_bytes(gc.tables, binding.step_params(S_bad, B_bad, 0, 1, False)) == 0
+
+
 def test_paper_shape_steps():
     cfg, gc = case("paper")
     H = hidden(cfg, gc, cfg.steps)
