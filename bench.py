@@ -183,9 +183,9 @@ def main():
     # ---- per-kernel durations over the same K steps, from HIP events around each kernel -------
     run_lsh(0, min(Wm, nst), stream_ptr())
     torch.cuda.synchronize()
-    # (a kernel may be launched more than once per step -- the contraction takes more than 32 beams
-    #  in groups -- so room for several launches per step, and durations are summed per step)
-    launches_per_step = (B + 31) // 32
+    # (every kernel is launched at most once per step; durations are still summed per step, so the
+    #  figures stay right should a step ever launch one several times)
+    launches_per_step = 1
     tables.profile_begin(K * launches_per_step)
     run_lsh(0, K, stream_ptr())
     prof = {name: (ms * n / K, n) for name, (ms, n) in tables.profile_end().items()}

@@ -202,8 +202,8 @@ int32_t lsh_step_is_fused(const lsh_tables* t, const lsh_step_params* sp);
 /* Start recording the device start/stop time of every kernel launch of the next steps (at most
  * max_steps launches per kernel) on this handle; lsh_profile_end synchronises the device, writes
  * the mean duration in milliseconds per launch of each kernel and the number of recorded
- * launches, and stops.  A step can launch a kernel more than once (the contraction takes more
- * than 32 beams in groups of 32): time per step = mean x launches / steps. */
+ * launches, and stops.  A step launches each kernel at most once; callers that compute
+ * time per step as mean x launches / steps stay correct should that change. */
 lsh_status lsh_profile_begin(lsh_tables* t, int32_t max_steps);
 lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
                            int32_t launches_out[LSH_NUM_KERNELS]);
