@@ -22,9 +22,10 @@
 //   k_logits<WAVES>  a workgroup of 16 or 4 waves per (tile, row group), k split over the waves
 //                    (few sentences; more than 64 beams);
 //   k_logits_wave    one wave per tile, up to four row groups in the wave, hidden rows read from
-//                    global memory (33..64 beams);
+//                    global memory (kept as the LSHBEAM_LOGITS_HLDS=0 path);
 //   k_logits_hlds    one wave per tile, the sentence's hidden rows staged in LDS (up to 32 beams:
-//                    the bandwidth-bound case);
+//                    the bandwidth-bound case; more beams in groups of 16 rows);
+//   k_logits_estage  33..64 beams: hidden rows in registers, candidate rows through LDS;
 //   fused.h          the same tiles inside the kernels that also produce the candidate list.
 #pragma once
 #include "device_utils.h"
@@ -752,6 +753,141 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         logits_tile_all_rows<ET, WAVES, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(
             E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red,
             PLANES ? nullptr : hl, PLANES ? 0 : pitch, row0, row0 + Bg);
+    }
+}
+
+// 33..64 beams, fp32 rows, d <= 1024: the operands change places.  The hidden rows do not fit in
+// LDS (64 x 4 KB) and taking them in groups makes every group pull the candidate rows through
+// the vector memory path again, which is what bounds that kernel.  Here the HIDDEN rows live in
+// registers and the CANDIDATE rows pass through LDS: a workgroup of 16 waves = 4 row groups x 4
+// slices of 256 k; wave (g, q) keeps the A operands of rows 16 g .. 16 g + 15, k in [256 q,
+// 256 q + 256) in 64 registers for the whole kernel (16 k-steps x 4), and the workgroup walks the
+// tiles of its sentence: every wave copies ONE candidate row of the next tile (4 KB, contiguous:
+// whole cache lines) into the other half of a double-buffered LDS tile while all waves contract
+// the current tile out of LDS (ds_read_b128 = the B operand of four matrix instructions).  A
+// candidate row is loaded once per tile, whatever the number of beams.  The partial tiles of
+// the four slices are summed through LDS in slice order, the wave of slice q finishing
+// accumulator register q of its row group (a quarter of the tile's logits and softmax partials
+// each: one wave finishing all of it was the critical path).  One barrier per tile.
+//   LDS: 2 x 16 rows x 1028 floats (pitch 4 modulo 32: conflict-free 16-byte reads) + 2 x 12 KB of
+//   partial tiles = 155.6 KB: one workgroup per CU.  Columns d .. 1023 of the tile are zeroed
+//   once (they meet A operands that are zero, and 0 x garbage may be NaN).
+constexpr int kEsPitch = 1028, kEsSlice = 256, kEsSlices = 4;
+__host__ __device__ inline size_t estage_lds_bytes() {
+    return ((size_t)2 * kTileN * kEsPitch + (size_t)2 * 12 * 4 * kWave) * 4;
+}
+
+template <int MT>
+__global__ void __launch_bounds__(1024)
+k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S,
+                int B, const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
+                float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
+                int64_t ppitch) {
+    constexpr int KSTEP = 16, NSTEP = kEsSlice / KSTEP;
+    extern __shared__ uint32_t esm[];
+    float* etile = reinterpret_cast<float*>(esm);                         // [2][16][kEsPitch]
+    float* red = etile + 2 * kTileN * kEsPitch;                           // [2][16 waves][3][64]
+    const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    const int col = ln & 15, kk = ln >> 4;
+    const int g = wv >> 2, q = wv & 3;                                     // row group, k slice
+    const int s = blockIdx.x % S, j0 = blockIdx.x / S, G = gridDim.x / S;  // tiles j0, j0 + G, ...
+    const int C = count ? count[s] : V;
+    const int ntiles = (C + kTileN - 1) / kTileN;
+    if (j0 >= ntiles) return;                                             // (whole workgroup)
+
+    // this wave's candidate row of a tile, 4 KB as up to four 16-byte loads per lane
+    const int d4 = d >> 2;
+    auto id_of = [&](int nt) -> int64_t {                                  // (any nt >= 0)
+        const int cidx = min(nt * kTileN + wv, C - 1);                     // clamped rows are never stored
+        return cand ? (int64_t)cand[(size_t)s * V + cidx] : (int64_t)cidx;
+    };
+    auto row_of = [&](int64_t j) { return reinterpret_cast<const float4*>(E + j * ld); };
+    float4 st0, st1, st2, st3;   // (named registers: an array captured by the lambdas goes to scratch)
+    const int c0 = min(ln, d4 - 1), c1 = min(ln + kWave, d4 - 1), c2 = min(ln + 2 * kWave, d4 - 1),
+              c3 = min(ln + 3 * kWave, d4 - 1);
+    auto load_row = [&](const float4* r) { st0 = r[c0]; st1 = r[c1]; st2 = r[c2]; st3 = r[c3]; };
+    auto store_row = [&](int buf) {
+        float4* dst = reinterpret_cast<float4*>(etile + ((size_t)buf * kTileN + wv) * kEsPitch);
+        if (ln < d4) dst[ln] = st0;
+        if (ln + kWave < d4) dst[ln + kWave] = st1;
+        if (ln + 2 * kWave < d4) dst[ln + 2 * kWave] = st2;
+        if (ln + 3 * kWave < d4) dst[ln + 3 * kWave] = st3;
+    };
+    load_row(row_of(id_of(j0)));
+    int64_t id_next = id_of(j0 + G);   // candidate ids are fetched a tile ahead of their rows
+
+    // A operands: rows 16 g + col (clamped), k = 256 q + 16 step + 4 kk + (0..3); zero past d
+    float a[NSTEP][4];
+    {
+        const int row = min(g * kTileM + col, B - 1);
+        const float* hrow = H + ((size_t)s * B + row) * d;
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            const int k = q * kEsSlice + st * KSTEP + 4 * kk;
+            const float4 h = *reinterpret_cast<const float4*>(hrow + min(k, d - 4));
+            const bool in = k < d && g < MT;
+            a[st][0] = in ? h.x : 0.f; a[st][1] = in ? h.y : 0.f;
+            a[st][2] = in ? h.z : 0.f; a[st][3] = in ? h.w : 0.f;
+        }
+    }
+    // zero the columns d .. 1023 of both buffers (never written by the row copies)
+    {
+        const int padw = kEsSlices * kEsSlice - d;                         // a multiple of 4, < 1024
+        for (int e = tid; e < 2 * kTileN * padw; e += 1024) {
+            const int r = e / padw, c = e - r * padw;
+            etile[(size_t)r * kEsPitch + d + c] = 0.f;
+        }
+    }
+    store_row(0);
+    __syncthreads();
+
+    int buf = 0;
+    for (int nt = j0; nt < ntiles; nt += G, buf ^= 1) {
+        const bool more = nt + G < ntiles;
+        if (more) {                                                        // in flight during the contraction
+            load_row(row_of(id_next));
+            id_next = id_of(nt + 2 * G);
+        }
+        floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (g < MT) {
+            const float* bt = etile + ((size_t)buf * kTileN + col) * kEsPitch + q * kEsSlice + 4 * kk;
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st) {
+                const float4 b = *reinterpret_cast<const float4*>(bt + st * KSTEP);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[st][0], b.x, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[st][1], b.y, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[st][2], b.z, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[st][3], b.w, acc, 0, 0, 0);
+            }
+            // the wave of slice q finishes accumulator register q of its row group (rows 16 g +
+            // 4 kk + q): it keeps that register and leaves the other three for its siblings
+            float* rp = red + (((size_t)buf * 16 + wv) * 3) * kWave;
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (r != q) rp[(r < q ? r : r - 1) * kWave + ln] = acc[r];
+        }
+        if (more) store_row(buf ^ 1);   // the other half was last read before the previous barrier
+        __syncthreads();
+        if (g < MT) {
+            // x = sum over the four slices in slice order (this wave's own share in its place)
+            const float own = (q == 0) ? acc[0] : (q == 1) ? acc[1] : (q == 2) ? acc[2] : acc[3];
+            float x = 0.f;
+#pragma unroll
+            for (int qq = 0; qq < kEsSlices; ++qq) {
+                float part = own;
+                if (qq != q)   // wave-uniform
+                    part = red[(((size_t)buf * 16 + (g * 4 + qq)) * 3 + (q < qq ? q : q - 1)) * kWave + ln];
+                x = (qq == 0) ? part : x + part;
+            }
+            const int n0 = nt * kTileN;
+            const int row = g * kTileM + 4 * kk + q, c = n0 + col;
+            const bool valid = row < B && c < C;
+            if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
+            const float mx = row16_max(valid ? x : -INFINITY);
+            const float se = row16_sum(valid ? expf(x - mx) : 0.f);
+            if (col == 0 && row < B)
+                partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+        }
     }
 }
 

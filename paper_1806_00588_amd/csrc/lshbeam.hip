@@ -318,6 +318,27 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
 #undef LSH_HLDS
 }
 
+// k_logits_estage: 33..64 beams, fp32 rows of at most 1024 values, 16-byte aligned operands, at
+// most 256 sentences.  About one workgroup per CU, dealt evenly to the sentences.
+void launch_logits_estage(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
+                          const int32_t* cand, const int32_t* count, const Workspace& w) {
+    const float* E = (const float*)t->E;
+    const int MT = (sp->B + kTileM - 1) / kTileM;
+    const size_t lds = estage_lds_bytes();
+    const int per_sentence = std::max(1, env_int("LSHBEAM_LOGITS_GRID", 256) / sp->S);
+    const dim3 grid((unsigned)(per_sentence * sp->S)), block(1024);
+#define LSH_ESTAGE(MTV)                                                                              \
+    do {                                                                                             \
+        auto kfn = k_logits_estage<MTV>;                                                             \
+        (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize,     \
+                                  (int)lds);                                                         \
+        launch(t, 1, kfn, grid, block, lds, st, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, \
+               w.logits, w.cpitch, w.partials, w.ppitch);                                            \
+    } while (0)
+    if (MT <= 3) LSH_ESTAGE(3); else LSH_ESTAGE(4);
+#undef LSH_ESTAGE
+}
+
 template <typename ET>
 void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
                    const int32_t* cand, const int32_t* count, const Workspace& w) {
@@ -337,7 +358,14 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     // one wave per tile with the sentence's hidden rows staged in LDS, more than 32 rows in
     // groups; LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory (k_logits_wave)
     const int group_rows = hlds_group_rows(sp->S, sp->B, t->d);
-    if (mode == 1 && group_rows > 0 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
+    // 33..64 beams: hidden rows in registers, candidate rows through LDS (LSHBEAM_LOGITS_ESTAGE=0:
+    // the other drivers)
+    const bool estage_ok = std::is_same<ET, float>::value && aligned && sp->B > 2 * kTileM &&
+                           sp->B <= 4 * kTileM && t->d <= kEsSlices * kEsSlice && sp->S <= 256 &&
+                           estage_lds_bytes() <= kMaxDynLds;
+    if (estage_ok && env_int("LSHBEAM_LOGITS_ESTAGE", 1) && !env_int("LSHBEAM_LOGITS_WAVES", 0)) {
+        launch_logits_estage(t, st, H, sp, cand, count, w);
+    } else if (mode == 1 && group_rows > 0 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
         launch_logits_hlds<ET>(t, st, tiles_n, aligned, H, sp, cand, count, w, group_rows);
     } else if (mode == 1 && MT <= 4) {
         const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, env_int("LSHBEAM_LOGITS_GRID", 1024));

@@ -556,6 +556,31 @@ def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, rows, mon
     run_and_check(cfg, gc, H[:80], np.zeros(80, np.float32), 2, 40, full_vocab=True)
 
 
+@pytest.mark.parametrize("grid", ["256", "4", "1"])
+def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_lds(grid, monkeypatch):
+    # 33..64 beams, fp32 rows: the workgroup keeps the hidden rows in registers and double-buffers
+    # the tiles' candidate rows through LDS.  Small grids give a workgroup many tiles (both
+    # buffers in use, the last tile ragged); d = 1000 leaves 24 zeroed pad columns, d = 64 leaves 960.
+    monkeypatch.setenv("LSHBEAM_LOGITS_GRID", grid)
+    cfg, gc = case("paper")
+    H = hidden(cfg, gc, 12).reshape(-1, cfg.d)                    # 144 rows
+    rng = np.random.default_rng(int(grid))
+    for S, B in [(2, 50), (1, 33), (2, 64), (3, 48)]:
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(B == 33))
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    H = np.concatenate([H, H[::-1] * 0.5 + 0.1, H * 0.25 - 0.1], axis=0)
+    for S, B in [(3, 40), (2, 64), (1, 33), (4, 49)]:
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(cfg, gc, H[:S * B], bs, S, B)
+    run_and_check(cfg, gc, H[:80], np.zeros(80, np.float32), 2, 40, full_vocab=True)
+    # no candidates at all (no top-frequent words, threshold above the number of bands)
+    gb, gw, gs, sp, ws = gc.step(H[:80], np.zeros(80, np.float32), 2, 40, T=0, threshold=cfg.W + 1)
+    assert gc.tables.debug_candidates(ws, sp, 1).size == 0
+    assert np.all(gb == -1) and np.all(gw == -1) and np.all(np.isneginf(gs))
+
+
 @pytest.mark.parametrize("grid", [1, 2, 3, 5, 8, 16])
 def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, monkeypatch):
     # one wave per tile for whole rounds of the (here artificially small) grid; a short last
