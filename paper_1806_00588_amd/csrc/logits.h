@@ -794,6 +794,7 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
     const int C = count ? count[s] : V;
     const int ntiles = (C + kTileN - 1) / kTileN;
     if (j0 >= ntiles) return;                                             // (whole workgroup)
+    LSH_TRACE(1, 0);
 
     // this wave's candidate row of a tile, 4 KB as up to four 16-byte loads per lane
     const int d4 = d >> 2;
@@ -838,8 +839,10 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
             etile[(size_t)r * kEsPitch + d + c] = 0.f;
         }
     }
+    LSH_TRACE(1, 1);
     store_row(0);
     __syncthreads();
+    LSH_TRACE(1, 2);
 
     int buf = 0;
     for (int nt = j0; nt < ntiles; nt += G, buf ^= 1) {
@@ -866,8 +869,14 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
             for (int r = 0; r < 4; ++r)
                 if (r != q) rp[(r < q ? r : r - 1) * kWave + ln] = acc[r];
         }
+#ifdef LSHBEAM_TRACE
+        if ((nt - j0) / G < 5) LSH_TRACE(1, 3 + 2 * ((nt - j0) / G));
+#endif
         if (more) store_row(buf ^ 1);   // the other half was last read before the previous barrier
         __syncthreads();
+#ifdef LSHBEAM_TRACE
+        if ((nt - j0) / G < 5) LSH_TRACE(1, 4 + 2 * ((nt - j0) / G));
+#endif
         if (g < MT) {
             // x = sum over the four slices in slice order (this wave's own share in its place)
             const float own = (q == 0) ? acc[0] : (q == 1) ? acc[1] : (q == 2) ? acc[2] : acc[3];
