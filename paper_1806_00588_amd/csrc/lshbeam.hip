@@ -294,7 +294,8 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
             tiles_n, std::max(1, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV) / ngroups));              \
         const int grid = ((gx + 7) / 8 * 8) * ngroups;                                               \
         launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
-               rows, gx, ngroups, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);      \
+               rows, gx, ngroups, env_int("LSHBEAM_HLDS_REM", 4), cand, count, t->V, w.logits,      \
+               w.cpitch, w.partials, w.ppitch);                                                      \
     } while (0)
     // bf16 rows, up to 16 hidden rows per group, two workgroups per CU: the hidden rows go to LDS
     // as three bf16 planes and the contraction runs on bf16 matrix instructions

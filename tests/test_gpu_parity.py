@@ -581,13 +581,16 @@ def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_ld
     assert np.all(gb == -1) and np.all(gw == -1) and np.all(np.isneginf(gs))
 
 
+@pytest.mark.parametrize("rem", ["4", "0"])
 @pytest.mark.parametrize("grid", [1, 2, 3, 5, 8, 16])
-def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, monkeypatch):
+def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, rem, monkeypatch):
     # one wave per tile for whole rounds of the (here artificially small) grid; a short last
-    # round is dealt to whole workgroups that split k.  Every grid size moves the boundary.
+    # round (at most a quarter of the waves; LSHBEAM_HLDS_REM=0: any) is dealt to whole
+    # workgroups that split k.  Every grid size moves the boundary.
     cfg, gc = case("tiny")
     monkeypatch.setenv("LSHBEAM_FUSED", "0")
     monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
+    monkeypatch.setenv("LSHBEAM_HLDS_REM", rem)
     monkeypatch.setenv("LSHBEAM_LOGITS_GRID", str(grid))
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     rng = np.random.default_rng(grid)
