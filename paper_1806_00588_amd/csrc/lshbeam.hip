@@ -9,6 +9,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -199,6 +200,22 @@ int env_int(const char* name, int dflt) {
     return (v && *v) ? std::atoi(v) : dflt;
 }
 
+// Raises a kernel's dynamic-LDS limit to (nearly) a CU's whole LDS, once per kernel and device.
+// The limit belongs to the kernel, not to a table: it is never set to what one table needs, and
+// the decode step makes no driver call besides its launches once a kernel has been through here.
+template <auto KFN>
+hipError_t allow_whole_lds() {
+    static std::atomic<uint64_t> done{0};  // one bit per device
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = (dev >= 0 && dev < 64) ? (1ull << dev) : 0ull;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute((const void*)KFN, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxDynLds);
+    if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 // Little work per step (few sentences x 16-row groups): every workgroup of the logits grid
 // regenerates the candidates itself (k_cand_logits); otherwise one candidates workgroup per
 // sentence, then the logits grid.  LSHBEAM_FUSED=0/1 overrides the size rule (for tests and
@@ -287,9 +304,7 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
     do {                                                                                             \
         auto kfn = k_logits_hlds<ET, MTV, WV, UV, AL, PL>;                                           \
         const size_t lds = hlds_lds_bytes(sp->S, rows, t->d, WV, PL);                                \
-        if (lds > 48 * 1024)                                                                         \
-            (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize, \
-                                      (int)lds);                                                     \
+        (void)allow_whole_lds<k_logits_hlds<ET, MTV, WV, UV, AL, PL>>();                             \
         const int gx = (int)std::min<int64_t>(                                                       \
             tiles_n, std::max(1, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV) / ngroups));              \
         const int grid = ((gx + 7) / 8 * 8) * ngroups;                                               \
@@ -331,8 +346,7 @@ void launch_logits_estage(lsh_tables* t, hipStream_t st, const float* H, const l
 #define LSH_ESTAGE(MTV)                                                                              \
     do {                                                                                             \
         auto kfn = k_logits_estage<MTV>;                                                             \
-        (void)hipFuncSetAttribute((const void*)kfn, hipFuncAttributeMaxDynamicSharedMemorySize,     \
-                                  (int)lds);                                                         \
+        (void)allow_whole_lds<k_logits_estage<MTV>>();                                               \
         launch(t, 1, kfn, grid, block, lds, st, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, \
                w.logits, w.cpitch, w.partials, w.ppitch);                                            \
     } while (0)
@@ -716,9 +730,6 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (brc != LSH_OK) return brc;
 
     t->wg_candidates_lds = (int)(candidates_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
-    if (t->wg_candidates_lds > 48 * 1024)
-        HIP_TRY(hipFuncSetAttribute((const void*)k_candidates,
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_candidates_lds));
     {   // LDS plan of k_hit_rows: whatever the counters leave goes to the load list
         const size_t fixed = hit_rows_fixed_lds_words(t->V, t->d, t->P);
         const size_t room = kMaxDynLds / sizeof(uint32_t);
@@ -727,31 +738,22 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
         if (cap >= (size_t)kHitListMin && (uint64_t)t->W * (uint64_t)t->V < (1ull << 30)) {
             t->hit_list_cap = (int)cap;
             t->wg_hit_rows_lds = (int)((fixed + cap) * sizeof(uint32_t));
-            HIP_TRY(hipFuncSetAttribute((const void*)k_hit_rows,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_hit_rows_lds));
         }
     }
-    HIP_TRY(hipFuncSetAttribute((const void*)k_union_compact, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)(((t->V + 31) / 32 + 64) * sizeof(uint32_t))));
-    HIP_TRY(hipFuncSetAttribute((const void*)k_part_bitmaps, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                t->wg_candidates_lds));
     t->wg_union_logits_lds = (int)(union_logits_lds_words(t->V) * sizeof(uint32_t));
-    {
-        const void* fu[4] = {(const void*)k_union_logits<float, true>, (const void*)k_union_logits<float, false>,
-                             (const void*)k_union_logits<uint16_t, true>,
-                             (const void*)k_union_logits<uint16_t, false>};
-        for (const void* f : fu)
-            HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        t->wg_union_logits_lds));
-    }
     t->wg_fused_lds = (int)(fused_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
-    if ((size_t)t->wg_fused_lds <= kMaxDynLds) {
-        const void* fused[4] = {(const void*)k_cand_logits<float, true>, (const void*)k_cand_logits<float, false>,
-                                (const void*)k_cand_logits<uint16_t, true>,
-                                (const void*)k_cand_logits<uint16_t, false>};
-        for (const void* f : fused)
-            HIP_TRY(hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, t->wg_fused_lds));
-    }
+    HIP_TRY(allow_whole_lds<k_candidates>());
+    HIP_TRY(allow_whole_lds<k_hit_rows>());
+    HIP_TRY(allow_whole_lds<k_union_compact>());
+    HIP_TRY(allow_whole_lds<k_part_bitmaps>());
+    HIP_TRY((allow_whole_lds<k_union_logits<float, true>>()));
+    HIP_TRY((allow_whole_lds<k_union_logits<float, false>>()));
+    HIP_TRY((allow_whole_lds<k_union_logits<uint16_t, true>>()));
+    HIP_TRY((allow_whole_lds<k_union_logits<uint16_t, false>>()));
+    HIP_TRY((allow_whole_lds<k_cand_logits<float, true>>()));
+    HIP_TRY((allow_whole_lds<k_cand_logits<float, false>>()));
+    HIP_TRY((allow_whole_lds<k_cand_logits<uint16_t, true>>()));
+    HIP_TRY((allow_whole_lds<k_cand_logits<uint16_t, false>>()));
     guard.t = nullptr;
     *out = t;
     return LSH_OK;
