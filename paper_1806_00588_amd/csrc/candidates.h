@@ -123,12 +123,19 @@ k_band_codes(const ET* __restrict__ X, int64_t ld, int64_t n, const int32_t* __r
 
 constexpr int kCandThreads = 1024;
 constexpr int kCandWaves = kCandThreads / kWave;
-constexpr int kCandStage = 12288;  // hidden values staged in LDS per chunk of rows (floats)
+// Hidden values staged in LDS per chunk of rows (floats): at least this much (or one row, if a row
+// is longer), more when a step's sentences have more beams and LDS has room (the host decides per
+// step and passes the size along: CandArgs::stage_words, a multiple of 4).
+constexpr int kCandStage = 12288;
+constexpr int kCandStageRows = 32;   // a larger stage is sized for at most this many rows
+__host__ __device__ inline int candidates_min_stage(int d) {
+    return ((d > kCandStage ? d : kCandStage) + 3) & ~3;
+}
 
 // Rows of a sentence are processed in chunks small enough that the chunk's hidden rows fit the
 // LDS stage and its (row, band) pairs fit one workgroup-wide scan.
-__host__ __device__ inline int candidates_rows_per_chunk(int B, int d, int W) {
-    int rows = kCandStage / d;
+__host__ __device__ inline int candidates_rows_per_chunk(int B, int d, int W, int stage_words) {
+    int rows = stage_words / d;
     if (rows > kCandThreads / W) rows = kCandThreads / W;
     if (rows > B) rows = B;
     return rows < 1 ? 1 : rows;
@@ -138,10 +145,9 @@ __host__ __device__ inline int candidates_rows_per_chunk(int B, int d, int W) {
 // Words reserved for the V-bit bitmap: rounded to 4 so that what follows is 16-byte aligned.
 __host__ __device__ inline int bitmap_words_padded(int V) { return (((V + 31) >> 5) + 3) & ~3; }
 
-__host__ __device__ inline size_t candidates_lds_words(int V, int d, int P, int K) {
-    const size_t nwords = (size_t)bitmap_words_padded(V);
-    const size_t stage = (size_t)d > (size_t)kCandStage ? (size_t)d : (size_t)kCandStage;
-    return nwords + stage + (size_t)P * K + 3 * (size_t)kCandThreads + 64;
+__host__ __device__ inline size_t candidates_lds_words(int V, int P, int K, int stage_words) {
+    return (size_t)bitmap_words_padded(V) + (size_t)stage_words + (size_t)P * K +
+           3 * (size_t)kCandThreads + 64;
 }
 
 // Branch-free search in an ascending LDS array of kCandThreads entries whose first entry is 0:
@@ -199,6 +205,7 @@ struct CandArgs {
     const int32_t* topfreq;  // [T]
     int T;
     const uint4* cuts;       // per slot: where the vocabulary slices 1, 2, 3 begin inside its span
+    int stage_words;         // LDS words for the staged hidden rows (>= d, a multiple of 4)
 };
 
 // Builds sentence s's presence bitmap (V bits, at smem[0 .. ceil(V/32))) in LDS: hashing, cuckoo
@@ -215,7 +222,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     const int32_t* __restrict__ words = a.words;
     const int32_t* __restrict__ topfreq = a.topfreq;
     const int nwords = (V + 31) >> 5;
-    const int stage_words = d > kCandStage ? d : kCandStage;
+    const int stage_words = a.stage_words;
     uint32_t* bm = smem;                                   // presence bitmap, V bits
     const int bmw = bitmap_words_padded(V);
     float* stage = reinterpret_cast<float*>(bm + bmw);     // the chunk's hidden rows [rows][d]
@@ -227,7 +234,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
 
     const int tid = threadIdx.x;
     const int u = P / W;
-    const int rows_per_chunk = candidates_rows_per_chunk(B, d, W);
+    const int rows_per_chunk = candidates_rows_per_chunk(B, d, W, stage_words);
     if (row_end < 0) row_end = B;
     LSH_TRACE(0, 0);
     LSH_TRACE_WG(0);
@@ -456,7 +463,7 @@ k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count
     extern __shared__ uint32_t smem[];
     const int s = blockIdx.x;
     const int nwords = (a.V + 31) >> 5;
-    uint32_t* wsum = smem + candidates_lds_words(a.V, a.d, a.P, a.K) - 64;
+    uint32_t* wsum = smem + candidates_lds_words(a.V, a.P, a.K, a.stage_words) - 64;
     build_presence_bitmap(a, s, smem);
     compact_bitmap(smem, nwords, wsum, cand + (size_t)s * a.V, count + s);
     LSH_TRACE(0, 6);

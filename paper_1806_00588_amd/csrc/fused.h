@@ -31,9 +31,9 @@ __host__ __device__ inline uint32_t pow2_at_least(uint32_t x) {
 
 // LDS words: candidate generation + prefix array (padded to a power of two, plus one) + the
 // cross-wave reduction buffer of the contraction.
-__host__ __device__ inline size_t fused_lds_words(int V, int d, int P, int K) {
+__host__ __device__ inline size_t fused_lds_words(int V, int P, int K, int stage_words) {
     const uint32_t nwords = (uint32_t)(((size_t)V + 31) / 32);
-    return candidates_lds_words(V, d, P, K) + pow2_at_least(nwords) + 1 +
+    return candidates_lds_words(V, P, K, stage_words) + pow2_at_least(nwords) + 1 +
            (size_t)kFusedWaves * 4 * kWave;
 }
 
@@ -111,15 +111,15 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
     const int V = a.V, B = a.B;
     const uint32_t npow = pow2_at_least((uint32_t)((V + 31) >> 5));
     uint32_t* bm = smem;
-    uint32_t* wsum = smem + candidates_lds_words(V, a.d, a.P, a.K) - 64;
-    uint32_t* wpref = smem + candidates_lds_words(V, a.d, a.P, a.K);
+    uint32_t* wsum = smem + candidates_lds_words(V, a.P, a.K, a.stage_words) - 64;
+    uint32_t* wpref = smem + candidates_lds_words(V, a.P, a.K, a.stage_words);
     float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + npow + 1);
 
     build_presence_bitmap(a, s, smem);
     // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
     // the contraction takes its A operands from there instead of reading H again
     const float* h_lds = nullptr;
-    if (candidates_rows_per_chunk(B, a.d, a.W) >= B && (a.d & 3) == 0)
+    if (candidates_rows_per_chunk(B, a.d, a.W, a.stage_words) >= B && (a.d & 3) == 0)
         h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
     tiles_from_bitmap<ET, ALIGNED>(bm, wsum, wpref, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
                                    count, logits, cpitch, partials, ppitch);

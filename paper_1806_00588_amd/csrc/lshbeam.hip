@@ -229,15 +229,30 @@ bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
     return possible && wanted;
 }
 
+// LDS words for the staged hidden rows of a step: room for all B rows of a sentence (up to
+// kCandStageRows; LSHBEAM_STAGE_ROWS overrides, 0 = never more than the minimum) where LDS has
+// it beside everything else the kernel keeps there, else the minimum stage.
+int stage_words_for(const lsh_tables* t, int B, bool fused_kernel) {
+    const int mn = candidates_min_stage(t->d);
+    const int rows = std::min(B, std::max(0, env_int("LSHBEAM_STAGE_ROWS", kCandStageRows)));
+    const int64_t want = ((int64_t)rows * t->d + 3) & ~(int64_t)3;
+    const size_t other = fused_kernel ? fused_lds_words(t->V, t->P, t->K, 0)
+                                      : candidates_lds_words(t->V, t->P, t->K, 0);
+    const size_t room = kMaxDynLds / sizeof(uint32_t);
+    const int64_t cap = room > other ? (int64_t)((room - other) & ~(size_t)3) : 0;
+    return (int)std::max<int64_t>(mn, std::min(want, cap));
+}
+
 // Rows of a sentence hashed per workgroup when the sentence is cut into parts (t = 1, more beams
-// than one chunk of hashing holds); 0 = the sentence is hashed by one workgroup.
-// LSHBEAM_PART_ROWS forces a part size (for tests and measurements).
-int part_rows_of(const lsh_tables* t, const lsh_step_params* sp) {
+// than one chunk of hashing holds even with the step's stage); 0 = the sentence is hashed by one
+// workgroup.  Parts take the minimum stage.  LSHBEAM_PART_ROWS forces a part size (for tests and
+// measurements).
+int part_rows_of(const lsh_tables* t, const lsh_step_params* sp, int stage_words) {
     if (sp->full_vocab || sp->threshold != 1) return 0;
-    const int rpc = candidates_rows_per_chunk(sp->B, t->d, t->W);
+    const int rpc = candidates_rows_per_chunk(sp->B, t->d, t->W, candidates_min_stage(t->d));
     const int forced = env_int("LSHBEAM_PART_ROWS", 0);
     if (forced > 0) return std::min(forced, rpc);
-    return sp->B > rpc ? rpc : 0;
+    return sp->B > candidates_rows_per_chunk(sp->B, t->d, t->W, stage_words) ? rpc : 0;
 }
 
 template <typename ET, int WAVES>
@@ -688,7 +703,8 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (p->P < 1 || p->bands < 1 || p->P % p->bands != 0) return LSH_ERR_INVALID_ARG;
     const int bits = code_bits(p->K), u = p->P / p->bands;
     if ((int64_t)u * bits > 30) return LSH_ERR_INVALID_ARG;
-    if (candidates_lds_words(p->V, p->d, p->P, p->K) * 4 > kMaxDynLds || p->bands > kCandThreads)
+    if (candidates_lds_words(p->V, p->P, p->K, candidates_min_stage(p->d)) * 4 > kMaxDynLds ||
+        p->bands > kCandThreads)
         return LSH_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)hip_stream;
 
@@ -729,7 +745,8 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (brc == LSH_ERR_BUILD_FAILED) brc = build_on_host(t, st, rng);
     if (brc != LSH_OK) return brc;
 
-    t->wg_candidates_lds = (int)(candidates_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
+    // (with the minimum stage; a step may ask for more)
+    t->wg_candidates_lds = (int)(candidates_lds_words(t->V, t->P, t->K, candidates_min_stage(t->d)) * sizeof(uint32_t));
     {   // LDS plan of k_hit_rows: whatever the counters leave goes to the load list
         const size_t fixed = hit_rows_fixed_lds_words(t->V, t->d, t->P);
         const size_t room = kMaxDynLds / sizeof(uint32_t);
@@ -741,7 +758,7 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
         }
     }
     t->wg_union_logits_lds = (int)(union_logits_lds_words(t->V) * sizeof(uint32_t));
-    t->wg_fused_lds = (int)(fused_lds_words(t->V, t->d, t->P, t->K) * sizeof(uint32_t));
+    t->wg_fused_lds = (int)(fused_lds_words(t->V, t->P, t->K, candidates_min_stage(t->d)) * sizeof(uint32_t));
     HIP_TRY(allow_whole_lds<k_candidates>());
     HIP_TRY(allow_whole_lds<k_hit_rows>());
     HIP_TRY(allow_whole_lds<k_union_compact>());
@@ -782,8 +799,10 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
     hipStream_t st = (hipStream_t)hip_stream;
     const int32_t* cand = nullptr;
     const int32_t* count = nullptr;
-    const CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
-                      t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T, t->cuts_dev};
+    const bool fused = step_is_fused(t, sp);
+    const int stage = stage_words_for(t, sp->B, fused);
+    CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
+                t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T, t->cuts_dev, stage};
     // Bitmaps made by an earlier kernel, to be OR-ed per sentence: one per hidden row when the
     // hit threshold is above 1 (Eq. 9-10), one per part of the sentence when it has many beams.
     const uint32_t* parts = nullptr;
@@ -793,13 +812,13 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
                ca, (int)sp->threshold, t->hit_list_cap, w.row_bitmaps);
         parts = w.row_bitmaps;
         nparts = sp->B;
-    } else if (const int pr = part_rows_of(t, sp)) {
+    } else if (const int pr = part_rows_of(t, sp, stage)) {
         nparts = (sp->B + pr - 1) / pr;
+        ca.stage_words = candidates_min_stage(t->d);
         launch(t, 4, k_part_bitmaps, dim3(sp->S * nparts), dim3(kCandThreads), (size_t)t->wg_candidates_lds,
                st, ca, pr, nparts, w.row_bitmaps);
         parts = w.row_bitmaps;
     }
-    const bool fused = step_is_fused(t, sp);
     if (fused) {
         const int per_sentence = std::max(1, env_int("LSHBEAM_FUSED_GRID", 256) / sp->S);
         const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
@@ -816,7 +835,7 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
             else { if (al) LSH_UNION_LOGITS(uint16_t, true); else LSH_UNION_LOGITS(uint16_t, false); }
 #undef LSH_UNION_LOGITS
         } else {
-            const size_t lds = (size_t)t->wg_fused_lds;
+            const size_t lds = fused_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t);
 #define LSH_CAND_LOGITS(ET, AL)                                                                   \
     launch(t, 1, k_cand_logits<ET, AL>, grid, block, lds, st, ca, (const ET*)t->E, t->ld, sp->S,  \
            w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch)
@@ -835,8 +854,8 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
             cand = w.cand;
             count = w.count;
         } else if (!sp->full_vocab) {
-            launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads), (size_t)t->wg_candidates_lds, st,
-                   ca, w.cand, w.count);
+            launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads),
+                   candidates_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t), st, ca, w.cand, w.count);
             cand = w.cand;
             count = w.count;
         }
