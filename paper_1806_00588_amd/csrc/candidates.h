@@ -372,14 +372,17 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         p_pref[tid] = incl - len;
         __syncthreads();
         // Algorithm 1 lines 3-6 as a flat walk over all spans of the chunk: element e belongs
-        // to the last pair whose exclusive prefix is <= e.  Two span reads in flight per thread.
+        // to the last pair whose exclusive prefix is <= e.  Two span reads in flight per thread
+        // (four were slower: every thread then searches four times even when the chunk has fewer
+        // elements than that).  An index past the end is clamped for the load and skipped for
+        // the mark: hundreds of atomics on the last element's word would serialise.
         for (uint32_t e0 = tid; e0 < total; e0 += 2 * kCandThreads) {
             const uint32_t ea = e0, eb = min(e0 + (uint32_t)kCandThreads, total - 1);
             const int la = last_not_above(p_pref, ea), lb = last_not_above(p_pref, eb);
             const int32_t ida = words[(size_t)p_band[la] * V + p_start[la] + (ea - p_pref[la])];
             const int32_t idb = words[(size_t)p_band[lb] * V + p_start[lb] + (eb - p_pref[lb])];
             atomicOr(&bm[ida >> 5], 1u << (ida & 31));
-            atomicOr(&bm[idb >> 5], 1u << (idb & 31));  // a clamped duplicate sets a set bit again
+            if (e0 + (uint32_t)kCandThreads < total) atomicOr(&bm[idb >> 5], 1u << (idb & 31));
         }
         __syncthreads();
         LSH_TRACE(0, 5);
@@ -396,12 +399,16 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
 // made dense; the paper's Fig. 5 step).  Each wave owns a contiguous range of bitmap words (a
 // multiple of 64 of them); popcount + wave prefix sum give every lane the output offset of its
 // word's ids.  A sparse word is expanded by its own lane (neighbouring lanes write neighbouring
-// addresses).  Dense words -- the top-frequent ids usually fill whole words -- would make each
-// lane write a long private run, 128 bytes apart from its neighbour's; they are expanded two at
-// a time by 32 lanes each, one lane per bit, so that their stores are contiguous.
-// Called by all kCandThreads threads; wsum is LDS scratch of >= kCandWaves words.
+// addresses).  Dense words -- the top-frequent ids usually fill whole words, and they sit next
+// to each other, in one wave's range -- would make each lane write a long private run, 128 bytes
+// apart from its neighbour's, and that one wave would expand them all: they are put on a list
+// in LDS instead (word, output offset) and, after a barrier, expanded by ALL waves, 32 lanes per
+// word, one lane per bit, so that the stores are contiguous.  Dense words beyond the list's
+// capacity are expanded by their own wave, two at a time.
+// Called by all kCandThreads threads; wsum is LDS scratch of >= kCandWaves + 1 words, dlist LDS
+// room for dcap entries.
 __device__ __forceinline__ void compact_bitmap(const uint32_t* bm, int nwords, uint32_t* wsum,
-                                               int32_t* __restrict__ out,
+                                               uint2* dlist, int dcap, int32_t* __restrict__ out,
                                                int32_t* __restrict__ count_out) {
     const int tid = threadIdx.x, wv = wave_id(), ln = lane_id();
     int per_wave = (nwords + kCandWaves - 1) / kCandWaves;
@@ -412,6 +419,7 @@ __device__ __forceinline__ void compact_bitmap(const uint32_t* bm, int nwords, u
     for (int i = wbeg + ln; i < wend; i += kWave) cnt += __popc(bm[i]);
     cnt = wave_sum(cnt);
     if (ln == 0) wsum[wv] = cnt;
+    if (tid == 0) wsum[kCandWaves] = 0;  // entries on the dense list
     __syncthreads();
     uint32_t running = 0, total = 0;
     for (int i = 0; i < kCandWaves; ++i) {
@@ -435,7 +443,16 @@ __device__ __forceinline__ void compact_bitmap(const uint32_t* bm, int nwords, u
                 b &= b - 1;
             }
         }
-        while (dmask) {  // wave-uniform
+        if (dmask) {  // wave-uniform
+            uint32_t base = 0;
+            if (ln == 0) base = atomicAdd(&wsum[kCandWaves], (uint32_t)__popcll(dmask));
+            base = wave_read_lane(base, 0);
+            const uint32_t pos = base + lanes_below(dmask);
+            const bool listed = dense && pos < (uint32_t)dcap;
+            if (listed) dlist[pos] = make_uint2((uint32_t)i, off);
+            dmask = __ballot(dense && !listed);
+        }
+        while (dmask) {  // wave-uniform: what the list had no room for
             const int la = __ffsll((unsigned long long)dmask) - 1;
             dmask &= dmask - 1;
             const int lb = dmask ? __ffsll((unsigned long long)dmask) - 1 : la;
@@ -447,14 +464,28 @@ __device__ __forceinline__ void compact_bitmap(const uint32_t* bm, int nwords, u
             const uint32_t woff = half ? ob : oa;
             const int wlane = half ? lb : la;
             const bool set = ((wbits >> hbit) & 1u) && (half == 0 || have_b);
-            const uint64_t bal = __ballot(set);
-            const uint32_t hm = half ? (uint32_t)(bal >> 32) : (uint32_t)bal;
-            const uint32_t pos = __popc(hm & ((1u << hbit) - 1u));
+            const uint32_t pos = __popc(wbits & ((1u << hbit) - 1u));
             if (set) out[woff + pos] = ((i0 + wlane) << 5) + hbit;
         }
         running += wave_read_lane(incl, kWave - 1);
     }
     if (tid == 0) *count_out = (int32_t)total;
+    __syncthreads();
+    // the listed dense words: half a wave per word, all waves
+    const int nlisted = (int)min(wsum[kCandWaves], (uint32_t)dcap);
+    for (int k = 2 * wv + half; k < nlisted; k += 2 * kCandWaves) {
+        const uint2 ent = dlist[k];
+        const uint32_t wbits = bm[ent.x];
+        const uint32_t pos = __popc(wbits & ((1u << hbit) - 1u));
+        if ((wbits >> hbit) & 1u) out[ent.y + pos] = (int32_t)((ent.x << 5) + (uint32_t)hbit);
+    }
+}
+
+// LDS of k_union_compact: the bitmap (rounded to an even number of words), 64 words of scan
+// scratch, the dense-word list of compact_bitmap.
+constexpr int kUnionDenseCap = 2048;
+__host__ __device__ inline size_t union_compact_lds_words(int V) {
+    return (size_t)bitmap_words_padded(V) + 64 + 2 * (size_t)kUnionDenseCap;
 }
 
 // One workgroup per sentence.  Requires W <= kCandThreads.
@@ -465,7 +496,9 @@ k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count
     const int nwords = (a.V + 31) >> 5;
     uint32_t* wsum = smem + candidates_lds_words(a.V, a.P, a.K, a.stage_words) - 64;
     build_presence_bitmap(a, s, smem);
-    compact_bitmap(smem, nwords, wsum, cand + (size_t)s * a.V, count + s);
+    // (the staged hidden rows are no longer needed: their room takes the dense-word list)
+    uint2* dlist = reinterpret_cast<uint2*>(smem + bitmap_words_padded(a.V));
+    compact_bitmap(smem, nwords, wsum, dlist, a.stage_words / 2, cand + (size_t)s * a.V, count + s);
     LSH_TRACE(0, 6);
 }
 
@@ -710,17 +743,18 @@ __global__ void __launch_bounds__(kCandThreads)
 k_union_compact(const uint32_t* __restrict__ row_bitmaps, int B, int V,
                 const int32_t* __restrict__ topfreq, int T, int32_t* __restrict__ cand,
                 int32_t* __restrict__ count) {
-    extern __shared__ uint32_t smem[];  // nwords + 64 words
+    extern __shared__ uint32_t smem[];  // union_compact_lds_words(V)
     const int s = blockIdx.x, tid = threadIdx.x;
     const int nwords = (V + 31) >> 5;
     uint32_t* bm = smem;
-    uint32_t* wsum = smem + nwords;
+    uint32_t* wsum = smem + bitmap_words_padded(V);
+    uint2* dlist = reinterpret_cast<uint2*>(wsum + 64);
     const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
     union_row_bitmaps(row_bitmaps + (size_t)s * B * nwords, B, nwords, bm);
     __syncthreads();
     mark_id_list(bm, V, topfreq, T, tf_first);
     __syncthreads();
-    compact_bitmap(bm, nwords, wsum, cand + (size_t)s * V, count + s);
+    compact_bitmap(bm, nwords, wsum, dlist, kUnionDenseCap, cand + (size_t)s * V, count + s);
 }
 
 }  // namespace lshbeam

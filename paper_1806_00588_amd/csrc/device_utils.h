@@ -43,6 +43,11 @@ __device__ __forceinline__ uint32_t wave_read_lane(uint32_t v, int lane) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
 }
 
+// Position of this lane among the set lanes of a ballot mask.
+__device__ __forceinline__ uint32_t lanes_below(uint64_t bal) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+}
+
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
     return wave_read_lane(wave_incl_scan(v), kWave - 1);
 }

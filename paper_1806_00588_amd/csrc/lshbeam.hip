@@ -849,7 +849,7 @@ lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float
         if (parts) {
             // union of the sentence's bitmaps + top-frequent words + compaction
             launch(t, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
-                   (size_t)(((t->V + 31) / 32 + 64) * sizeof(uint32_t)), st, parts, nparts, t->V,
+                   union_compact_lds_words(t->V) * sizeof(uint32_t), st, parts, nparts, t->V,
                    topfreq_dev, sp->T, w.cand, w.count);
             cand = w.cand;
             count = w.count;

@@ -96,11 +96,6 @@ __device__ __forceinline__ uint32_t wave_kth_largest_sort(uint32_t v, int k) {
     return wave_read_lane(x, k - 1);
 }
 
-// Position of this lane among the set lanes of a ballot mask.
-__device__ __forceinline__ uint32_t lanes_below(uint64_t bal) {
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
-}
-
 // One wave's LDS operations complete in program order; this only keeps the compiler from moving
 // them across the point.
 __device__ __forceinline__ void wave_lds_sync() {
