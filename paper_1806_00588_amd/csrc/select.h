@@ -360,7 +360,6 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     } else {
         tau = block_kth_largest_lb(lmax, B, &sh);
     }
-    if ((size_t)B * C <= (size_t)kSelRankCap) tau = 0;  // few scores: take them all
     LSH_TRACE(2, 2);
 
     // ---- second pass: tiles whose maximum reaches tau are opened, 16 lanes per tile ----
