@@ -394,11 +394,15 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
         if (__ballot(f32_sortable(bsi + (best - lse) + 0.0f) >= tau) == 0) continue;
         uint64_t bal[kSelBatch];
         uint32_t n_mine = 0;
+        const int nq = slots_of(bt);  // slots of the batch that hold tiles at all (wave-uniform)
 #pragma unroll
         for (int q = 0; q < kSelBatch; ++q) {
-            const int t = t0 + ln + q * kWave;
-            bal[q] = __ballot(t < ntiles && f32_sortable(bsi + (px[q] - lse) + 0.0f) >= tau);
-            n_mine += (uint32_t)__popcll(bal[q]);
+            bal[q] = 0;
+            if (q < nq) {
+                const int t = t0 + ln + q * kWave;
+                bal[q] = __ballot(t < ntiles && f32_sortable(bsi + (px[q] - lse) + 0.0f) >= tau);
+                n_mine += (uint32_t)__popcll(bal[q]);
+            }
         }
         if (n_mine) {  // wave-uniform
             uint32_t base = 0;
@@ -406,6 +410,7 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
             base = wave_read_lane(base, 0);
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q) {
+                if (bal[q] == 0) continue;  // wave-uniform
                 const uint32_t pos = base + lanes_below(bal[q]);
                 if (((bal[q] >> ln) & 1ull) && pos < (uint32_t)kSelOpenCap)
                     sh.open_list[pos] = ((uint32_t)i << 20) | (uint32_t)(t0 + ln + q * kWave);
