@@ -266,6 +266,60 @@ def test_paper_shape_as_the_benchmark_runs_it():
         assert_topb_matches(b[i], w[i], sc[i], ref, bs)
 
 
+@pytest.mark.parametrize("name,S,B,t", [("paper", 16, 10, 1),     # candidates, wave-per-tile contraction
+                                        ("paper", 2, 40, 1),      # parts, union, candidate rows through LDS
+                                        ("paper", 1, 24, 1),      # the larger hashing stage, fused
+                                        ("paper", 3, 12, 3),      # hit counts, union inside the contraction
+                                        ("largevocab", 8, 10, 1)])  # bf16 rows, bf16 planes
+def test_other_launch_plans_replayed_as_a_graph(name, S, B, t):
+    """Four chained steps of the launch plans the paper shape does not take, captured as one HIP
+    graph: three replays (with eager work and synchronisations between them) equal the eager
+    run bit for bit, and the eager run's first step matches the oracle."""
+    import dataclasses
+    import torch
+    import paper_1806_00588_amd as lsh
+    from paper_1806_00588_amd import binding
+    cfg, gc = case(name)
+    n = 4
+    H = workloads.make_hidden(dataclasses.replace(cfg, S=S, B=B), gc.E, seed=3, steps=n)
+    H_dev = to_dev(H)
+    R = S * B
+    sp = binding.step_params(S, B, gc.topfreq.size, t)
+    ws = torch.empty(lsh.step_workspace_bytes(gc.tables, sp), dtype=torch.uint8, device="cuda")
+    call = binding.make_step_caller(gc.tables, sp, ws, gc.topfreq_dev)
+    zero = torch.zeros(R, device="cuda")
+    ob = torch.empty((n, R), dtype=torch.int32, device="cuda")
+    ow = torch.empty((n, R), dtype=torch.int32, device="cuda")
+    osc = torch.empty((n, R), device="cuda")
+
+    def run(stream):
+        for i in range(n):
+            prev = zero if i == 0 else osc[i - 1]
+            call(H_dev[i].data_ptr(), prev.data_ptr(), ob[i].data_ptr(), ow[i].data_ptr(),
+                 osc[i].data_ptr(), stream)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run(side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    eager = (ob.clone(), ow.clone(), osc.clone())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        run(torch.cuda.current_stream().cuda_stream)
+    for _ in range(3):
+        ob.fill_(-9); ow.fill_(-9); osc.fill_(0)
+        ws.fill_(0xA5)                                   # eager work between the replays
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(ob, eager[0]) and torch.equal(ow, eager[1]) and torch.equal(osc, eager[2])
+    b, w, sc = (x.cpu().numpy().reshape(n, S, B) for x in eager)
+    for s in range(min(S, 3)):
+        Hs = H[0].reshape(S, B, -1)[s]
+        ref = gc.oracle_sentence(Hs, np.zeros(B), B, threshold=t)
+        assert_topb_matches(b[0, s], w[0, s], sc[0, s], ref, np.zeros(B))
+
+
 def test_paper_shape_full_vocab():
     cfg, gc = case("paper")
     H = hidden(cfg, gc, 1)
