@@ -250,10 +250,12 @@ def build_tables(E, perms, K: int, bands: int, seed: int = 0, stream=None) -> Ta
         dt = LSH_BF16
     else:
         raise ValueError(f"E: unsupported dtype {E.dtype}")
-    _require_cuda(E, "E", (E.dtype,))
     _require_cuda(perms, "perms", (torch.int32,))
     if E.dim() != 2 or perms.dim() != 2 or int(perms.shape[1]) != K:
         raise ValueError("E must be [V, d] and perms [P, K]")
+    # rows may be pitched (a [:, a:b] view of a wider matrix): unit stride inside a row only
+    if not E.is_cuda or int(E.stride(1)) != 1 or int(E.stride(0)) < int(E.shape[1]):
+        raise ValueError("E must be a device tensor with contiguous rows (row pitch >= d)")
     bp = BuildParams(int(E.shape[0]), int(E.shape[1]), int(E.stride(0)), dt, K,
                      int(perms.shape[0]), bands, seed)
     out = ctypes.c_void_p(0)

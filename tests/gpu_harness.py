@@ -27,7 +27,9 @@ def to_dev(a: np.ndarray):
 class GpuCase:
     """Inputs of one configuration resident on the device + tables + the oracle index."""
 
-    def __init__(self, E, perms, topfreq, W, seed=0):
+    def __init__(self, E, perms, topfreq, W, seed=0, E_dev=None):
+        """E_dev: the device tensor to hand to the library instead of a plain upload of E (a
+        pitched or offset view holding the same values)."""
         import torch
         import paper_1806_00588_amd as lsh
         self.lsh = lsh
@@ -36,7 +38,7 @@ class GpuCase:
         self.V, self.d = E.shape
         self.P, self.K = perms.shape
         self.W = W
-        self.E_dev = to_dev(E)
+        self.E_dev = to_dev(E) if E_dev is None else E_dev
         self.perms_dev = to_dev(perms)
         self.topfreq_dev = to_dev(self.topfreq) if self.topfreq.size else None
         self.tables = lsh.build_tables(self.E_dev, self.perms_dev, self.K, W, seed=seed)

@@ -521,6 +521,36 @@ def test_unaligned_hidden_size_uses_scalar_loads():
         run_and_check(None, gc, H, np.zeros(10, np.float32), 2, 5, full_vocab=True)
 
 
+@pytest.mark.parametrize("pad,off,bf16", [(8, 0, False), (3, 0, False), (4, 1, False), (0, 4, False),
+                                          (16, 0, True), (5, 3, True)])
+def test_pitched_and_offset_embedding_rows(pad, off, bf16):
+    # E handed over as a view [:, off : off + d] of a wider matrix: row pitch d + pad + off, base
+    # pointer off elements into an allocation.  Pitches and offsets that keep 16-byte alignment
+    # take the vector loads, the others the element-wise path; all agree with the oracle.
+    import torch
+    rng = np.random.default_rng(pad * 16 + off)
+    V, d, K, P, W = 1200, 96, 8, 16, 4
+    E = (rng.standard_normal((V, d)) / np.sqrt(d)).astype(np.float32)
+    if bf16:
+        E = workloads.f32_to_bf16_bits(E)
+    wide = np.zeros((V, d + pad + off), dtype=E.dtype)
+    wide[:] = 77 if bf16 else 1e30                 # what lies between the rows must never be read as data
+    wide[:, off:off + d] = E
+    wide_dev = to_dev(wide)
+    E_dev = wide_dev[:, off:off + d]
+    assert int(E_dev.stride(0)) == d + pad + off and not E_dev.is_contiguous() or pad + off == 0
+    perms = np.stack([rng.permutation(d)[:K] for _ in range(P)]).astype(np.int32)
+    gc = GpuCase(E, perms, np.arange(60, dtype=np.int32), W, E_dev=E_dev)
+    want = oracle.band_codes(oracle.wta_codes(E, perms), W, K)
+    assert np.array_equal(gc.tables.debug_embedding_codes(), want)
+    H = rng.standard_normal((64, d)).astype(np.float32)
+    for S, B in [(1, 4), (2, 12), (1, 40), (16, 4)]:
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        run_and_check(None, gc, H[:S * B], bs, S, B)
+    run_and_check(None, gc, H[:8], np.zeros(8, np.float32), 2, 4, full_vocab=True)
+    run_and_check(None, gc, H[:8], np.zeros(8, np.float32), 2, 4, threshold=2)
+
+
 def test_step_is_deterministic():
     cfg, gc = case("paper")
     H = hidden(cfg, gc, 1)[0]
