@@ -51,8 +51,9 @@ class GpuCase:
                    workloads.make_topfreq(cfg), cfg.W, seed)
 
     def step(self, H: np.ndarray, beam_scores: np.ndarray, S: int, B: int, full_vocab=False,
-             T=None, topfreq_dev=None, threshold=1):
-        """One lsh_decode_step; returns (beam, word, score) numpy [S,B] plus (sp, workspace)."""
+             T=None, topfreq_dev=None, threshold=1, h_misalign=0):
+        """One lsh_decode_step; returns (beam, word, score) numpy [S,B] plus (sp, workspace).
+        h_misalign: the hidden rows start that many floats into their allocation."""
         from paper_1806_00588_amd import binding
         torch = self.torch
         T = self.topfreq.size if T is None else T
@@ -64,6 +65,10 @@ class GpuCase:
             self._ws[key] = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
         ws = self._ws[key]
         H_dev = to_dev(np.ascontiguousarray(H, dtype=np.float32))
+        if h_misalign:
+            buf = torch.zeros(H_dev.numel() + h_misalign, dtype=torch.float32, device="cuda")
+            buf[h_misalign:] = H_dev.reshape(-1)
+            H_dev = buf[h_misalign:].view(H_dev.shape)
         bs_dev = to_dev(np.ascontiguousarray(beam_scores, dtype=np.float32))
         ob = torch.full((S, B), -7, dtype=torch.int32, device="cuda")
         ow = torch.full((S, B), -7, dtype=torch.int32, device="cuda")

@@ -551,6 +551,27 @@ def test_pitched_and_offset_embedding_rows(pad, off, bf16):
     run_and_check(None, gc, H[:8], np.zeros(8, np.float32), 2, 4, threshold=2)
 
 
+@pytest.mark.parametrize("name", ["tiny", "paper"])
+def test_hidden_rows_not_16_byte_aligned(name):
+    # H starting 4 (12) bytes into its allocation: no 16-byte loads of hidden rows anywhere
+    cfg, gc = case(name)
+    H = hidden(cfg, gc, 4).reshape(-1, cfg.d)
+    rng = np.random.default_rng(4)
+    for S, B, t in [(1, cfg.B, 1), (3, 4, 1), (1, 40, 1), (2, 3, 2)]:
+        if S * B > len(H):
+            continue
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        gb, gw, gs, sp, ws = gc.step(H[:S * B], bs, S, B, threshold=t, h_misalign=1)
+        for s in range(S):
+            ref = gc.oracle_sentence(H[s * B:(s + 1) * B], bs[s * B:(s + 1) * B], B, threshold=t)
+            assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), ref.cand)
+            assert_topb_matches(gb[s], gw[s], gs[s], ref, bs[s * B:(s + 1) * B])
+    gb, gw, gs, sp, ws = gc.step(H[:8], np.zeros(8, np.float32), 2, 4, full_vocab=True, h_misalign=3)
+    for s in range(2):
+        ref = gc.oracle_sentence(H[s * 4:(s + 1) * 4], np.zeros(4), 4, full_vocab=True)
+        assert_topb_matches(gb[s], gw[s], gs[s], ref, np.zeros(4))
+
+
 def test_step_is_deterministic():
     cfg, gc = case("paper")
     H = hidden(cfg, gc, 1)[0]
