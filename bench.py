@@ -30,7 +30,7 @@ def log(*a):
 
 def measured_traffic(workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary."""
-    for kernel in ("k_cand_logits", "k_logits_hlds", "k_logits_wave"):
+    for kernel in ("k_cand_logits", "k_union_logits", "k_logits_hlds", "k_logits_estage", "k_logits_wave"):
         path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.md")
         try:
             for line in open(path):
