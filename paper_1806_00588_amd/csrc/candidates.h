@@ -20,6 +20,7 @@
 // prefix-summed across all (row, band) pairs and the flat element range is dealt to threads
 // evenly, each finding its span by binary search.
 #pragma once
+#include <type_traits>
 #include "device_utils.h"
 
 namespace lshbeam {
@@ -372,18 +373,32 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         p_pref[tid] = incl - len;
         __syncthreads();
         // Algorithm 1 lines 3-6 as a flat walk over all spans of the chunk: element e belongs
-        // to the last pair whose exclusive prefix is <= e.  Two span reads in flight per thread
-        // (four were slower: every thread then searches four times even when the chunk has fewer
-        // elements than that).  An index past the end is clamped for the load and skipped for
-        // the mark: hundreds of atomics on the last element's word would serialise.
-        for (uint32_t e0 = tid; e0 < total; e0 += 2 * kCandThreads) {
-            const uint32_t ea = e0, eb = min(e0 + (uint32_t)kCandThreads, total - 1);
-            const int la = last_not_above(p_pref, ea), lb = last_not_above(p_pref, eb);
-            const int32_t ida = words[(size_t)p_band[la] * V + p_start[la] + (ea - p_pref[la])];
-            const int32_t idb = words[(size_t)p_band[lb] * V + p_start[lb] + (eb - p_pref[lb])];
-            atomicOr(&bm[ida >> 5], 1u << (ida & 31));
-            if (e0 + (uint32_t)kCandThreads < total) atomicOr(&bm[idb >> 5], 1u << (idb & 31));
-        }
+        // to the last pair whose exclusive prefix is <= e.  An index past the end is clamped for
+        // the load and skipped for the mark: hundreds of atomics on the last element's word
+        // would serialise.  Long walks (several elements per thread) keep four span reads in
+        // flight per thread, short ones two: with four, every thread searches four times even
+        // when the chunk has fewer elements than that.
+        auto walk = [&](auto width_tag) {
+            constexpr int NW = decltype(width_tag)::value;
+            for (uint32_t e0 = tid; e0 < total; e0 += NW * kCandThreads) {
+                uint32_t e[NW];
+                int l[NW];
+                int32_t id[NW];
+#pragma unroll
+                for (int q = 0; q < NW; ++q) e[q] = min(e0 + (uint32_t)(q * kCandThreads), total - 1);
+#pragma unroll
+                for (int q = 0; q < NW; ++q) l[q] = last_not_above(p_pref, e[q]);
+#pragma unroll
+                for (int q = 0; q < NW; ++q)
+                    id[q] = words[(size_t)p_band[l[q]] * V + p_start[l[q]] + (e[q] - p_pref[l[q]])];
+#pragma unroll
+                for (int q = 0; q < NW; ++q)
+                    if (e0 + (uint32_t)(q * kCandThreads) < total)
+                        atomicOr(&bm[id[q] >> 5], 1u << (id[q] & 31));
+            }
+        };
+        if (total > 4u * kCandThreads) walk(std::integral_constant<int, 4>{});
+        else walk(std::integral_constant<int, 2>{});
         __syncthreads();
         LSH_TRACE(0, 5);
         LSH_TRACE_WG(3);
