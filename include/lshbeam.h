@@ -186,6 +186,32 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
                               const lsh_step_params* sp, int32_t s, float* lp_host, int32_t cap,
                               int32_t* n_out);
 
+/* ---- launch-plan options (for tests and measurements; no effect on results) -------------------
+ *
+ * A step chooses its kernels from the shape (few sentences: one fused kernel; many: separate
+ * candidate, contraction and selection kernels; ...).  Every rule can be overridden per handle.
+ * `value` >= 0 forces, LSH_OPTION_AUTO restores the library's rule.  When a handle is built, each
+ * option takes the value of the environment variable LSHBEAM_<NAME IN CAPITALS> if that is set
+ * (read once, inside lsh_build_tables); lsh_decode_step never reads the environment.  Not
+ * synchronised with steps running on the handle from other threads: set options between steps.
+ *   "fused"          1 / 0: candidate generation inside the contraction kernel, or separate kernels
+ *   "fused_grid"     workgroups of the fused kernel (default 256)
+ *   "logits_grid"    workgroups (or waves' worth of them) of the separate contraction kernels
+ *   "logits_waves"   1 / 4 / 16: contraction driver (a wave per tile; k split over 4 or 16 waves)
+ *   "logits_hlds"    0: the wave-per-tile driver keeps the hidden rows in global memory, not LDS
+ *   "logits_estage"  0: 33..64 beams take the grouped driver instead of candidate rows through LDS
+ *   "hlds_rem"       n: a last round of tiles filling at most 1/n of the waves is split over k (4)
+ *   "logits_planes"  0: bf16 rows are widened to fp32 instead of meeting bf16 planes of H
+ *   "hlds_rows"      16 / 32: hidden rows per group of the LDS-staged driver
+ *   "part_rows"      n: sentences are hashed in parts of n rows, a workgroup each
+ *   "stage_rows"     n: the hashing stage in LDS is sized for at most n rows (0: the minimum)
+ * Two more are read from the environment by lsh_build_tables only: LSHBEAM_HOST_BUILD=1 (bucket and
+ * cuckoo tables built on the host) and LSHBEAM_CUCKOO_CHAIN=n (eviction chains of the device
+ * build cut at n; for tests of its retry path). */
+#define LSH_OPTION_AUTO (-1)
+lsh_status lsh_set_option(lsh_tables* t, const char* name, int32_t value);
+lsh_status lsh_get_option(const lsh_tables* t, const char* name, int32_t* value_out);
+
 /* ---- per-kernel timing -------------------------------------------------------------------- */
 
 #define LSH_NUM_KERNELS 5 /* 0 candidates (hash+probe+merge, or union of earlier bitmaps +
@@ -198,15 +224,28 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
  * the kernels separately. */
 int32_t lsh_step_is_fused(const lsh_tables* t, const lsh_step_params* sp);
 
+/* A profiler owns device start/stop events for up to max_launches launches of each kernel.  The
+ * caller owns it and hands it to the steps it wants timed; the tables handle holds no timing
+ * state, so steps on different streams can be timed with different profilers.  One profiler must
+ * not be used by two steps at the same time. */
+typedef struct lsh_profiler lsh_profiler;
+lsh_status lsh_profiler_create(int32_t max_launches, lsh_profiler** out);
+void lsh_profiler_destroy(lsh_profiler* p); /* NULL-safe */
 
-/* Start recording the device start/stop time of every kernel launch of the next steps (at most
- * max_steps launches per kernel) on this handle; lsh_profile_end synchronises the device, writes
- * the mean duration in milliseconds per launch of each kernel and the number of recorded
- * launches, and stops.  A step launches each kernel at most once; callers that compute
- * time per step as mean x launches / steps stay correct should that change. */
-lsh_status lsh_profile_begin(lsh_tables* t, int32_t max_steps);
-lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
-                           int32_t launches_out[LSH_NUM_KERNELS]);
+/* lsh_decode_step with the device start/stop time of each of its kernel launches recorded in
+ * `prof` (NULL: exactly lsh_decode_step).  Launches beyond max_launches are not recorded. */
+lsh_status lsh_decode_step_timed(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
+                                 const int32_t* topfreq_dev, const lsh_step_params* sp,
+                                 void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
+                                 int32_t* out_word_dev, float* out_score_dev, void* hip_stream,
+                                 lsh_profiler* prof);
+
+/* Synchronises the device, writes the mean duration in milliseconds per launch of each kernel and
+ * the number of recorded launches, and empties the profiler for reuse.  A step launches each
+ * kernel at most once; callers that compute time per step as mean x launches / steps stay correct
+ * should that change. */
+lsh_status lsh_profiler_read(lsh_profiler* p, double mean_ms_out[LSH_NUM_KERNELS],
+                             int32_t launches_out[LSH_NUM_KERNELS]);
 const char* lsh_kernel_name(int32_t which);
 
 const char* lsh_status_string(lsh_status s);

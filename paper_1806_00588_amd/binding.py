@@ -17,10 +17,15 @@ NUM_KERNELS = 5
 EXPORTED_SYMBOLS = (
     "lsh_build_tables", "lsh_free_tables", "lsh_step_workspace_bytes", "lsh_decode_step",
     "lsh_debug_codes", "lsh_debug_embedding_codes", "lsh_debug_bucket", "lsh_debug_csr",
-    "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profile_begin",
-    "lsh_profile_end", "lsh_kernel_name", "lsh_status_string", "lsh_step_is_fused",
-    "lsh_debug_build_info", "lsh_beam_advance", "lsh_beam_backtrace",
+    "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profiler_create",
+    "lsh_profiler_destroy", "lsh_profiler_read", "lsh_decode_step_timed", "lsh_kernel_name",
+    "lsh_status_string", "lsh_step_is_fused", "lsh_debug_build_info", "lsh_beam_advance",
+    "lsh_beam_backtrace", "lsh_set_option", "lsh_get_option",
 )
+
+OPTION_AUTO = -1
+OPTION_NAMES = ("fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
+                "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows")
 
 
 class LshBeamError(RuntimeError):
@@ -85,8 +90,13 @@ def load_library():
     lib.lsh_debug_candidates.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32, i32p, i32, i32p]
     lib.lsh_debug_logprobs.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32,
                                        ctypes.POINTER(ctypes.c_float), i32, i32p]
-    lib.lsh_profile_begin.argtypes = [vp, i32]
-    lib.lsh_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_double), i32p]
+    lib.lsh_decode_step_timed.argtypes = lib.lsh_decode_step.argtypes + [vp]
+    lib.lsh_profiler_create.argtypes = [i32, ctypes.POINTER(vp)]
+    lib.lsh_profiler_destroy.argtypes = [vp]
+    lib.lsh_profiler_destroy.restype = None
+    lib.lsh_profiler_read.argtypes = [vp, ctypes.POINTER(ctypes.c_double), i32p]
+    lib.lsh_set_option.argtypes = [vp, ctypes.c_char_p, i32]
+    lib.lsh_get_option.argtypes = [vp, ctypes.c_char_p, i32p]
     lib.lsh_step_is_fused.argtypes = [vp, ctypes.POINTER(StepParams)]
     lib.lsh_kernel_name.argtypes = [i32]
     lib.lsh_kernel_name.restype = ctypes.c_char_p
@@ -143,6 +153,7 @@ class Tables:
         self.E = E
         self.V, self.d = int(E.shape[0]), int(E.shape[1])
         self.K, self.P, self.W, self.e_dtype = K, P, W, e_dtype
+        self._prof = None          # lsh_profiler* while profile_begin .. profile_end is open
 
     @property
     def handle(self) -> int:
@@ -151,9 +162,32 @@ class Tables:
         return self._h
 
     def close(self):
+        if self._prof:
+            load_library().lsh_profiler_destroy(self._prof)
+            self._prof = None
         if self._h:
             load_library().lsh_free_tables(self._h)
             self._h = None
+
+    # ---- launch-plan options ------------------------------------------------------------------
+    def set_option(self, name: str, value: int = OPTION_AUTO):
+        """lsh_set_option: force a launch-plan rule (value >= 0) or restore it (OPTION_AUTO)."""
+        _check(load_library().lsh_set_option(self.handle, name.encode(), int(value)),
+               f"lsh_set_option({name})")
+
+    def get_option(self, name: str) -> int:
+        v = ctypes.c_int32(0)
+        _check(load_library().lsh_get_option(self.handle, name.encode(), ctypes.byref(v)),
+               f"lsh_get_option({name})")
+        return v.value
+
+    def set_options(self, **kw):
+        for k, v in kw.items():
+            self.set_option(k, v)
+
+    def reset_options(self):
+        for k in OPTION_NAMES:
+            self.set_option(k, OPTION_AUTO)
 
     def __del__(self):
         try:
@@ -230,12 +264,27 @@ class Tables:
 
     # ---- per-kernel timing ------------------------------------------------------------------
     def profile_begin(self, max_steps: int):
-        _check(load_library().lsh_profile_begin(self.handle, max_steps), "lsh_profile_begin")
+        """Steps made through this object (decode_step, make_step_caller) from now on are timed
+        per kernel (lsh_decode_step_timed with a profiler this object owns), up to max_steps."""
+        lib = load_library()
+        if self._prof:
+            lib.lsh_profiler_destroy(self._prof)
+            self._prof = None
+        out = ctypes.c_void_p(0)
+        _check(lib.lsh_profiler_create(max_steps, ctypes.byref(out)), "lsh_profiler_create")
+        self._prof = out.value
 
     def profile_end(self):
+        """{kernel name: (mean ms per launch, launches)}; ends the timing."""
+        lib = load_library()
+        if not self._prof:
+            raise ValueError("profile_end without profile_begin")
         ms = (ctypes.c_double * NUM_KERNELS)()
         n = (ctypes.c_int32 * NUM_KERNELS)()
-        _check(load_library().lsh_profile_end(self.handle, ms, n), "lsh_profile_end")
+        rc = lib.lsh_profiler_read(self._prof, ms, n)
+        lib.lsh_profiler_destroy(self._prof)
+        self._prof = None
+        _check(rc, "lsh_profiler_read")
         return {name: (ms[i], n[i]) for i, name in enumerate(kernel_names())}
 
 
@@ -296,10 +345,13 @@ def decode_step(tables: Tables, H, beam_scores, topfreq, sp: StepParams, workspa
         if topfreq.numel() < sp.T:
             raise ValueError("topfreq shorter than T")
         tf_ptr = topfreq.data_ptr()
-    _check(load_library().lsh_decode_step(
-        tables.handle, H.data_ptr(), beam_scores.data_ptr(), tf_ptr, ctypes.byref(sp),
-        workspace.data_ptr(), workspace.numel() * workspace.element_size(), out_beam.data_ptr(),
-        out_word.data_ptr(), out_score.data_ptr(), _stream_ptr(stream)), "lsh_decode_step")
+    args = (tables.handle, H.data_ptr(), beam_scores.data_ptr(), tf_ptr, ctypes.byref(sp),
+            workspace.data_ptr(), workspace.numel() * workspace.element_size(), out_beam.data_ptr(),
+            out_word.data_ptr(), out_score.data_ptr(), _stream_ptr(stream))
+    if tables._prof:
+        _check(load_library().lsh_decode_step_timed(*args, tables._prof), "lsh_decode_step_timed")
+    else:
+        _check(load_library().lsh_decode_step(*args), "lsh_decode_step")
 
 
 def make_step_caller(tables: Tables, sp: StepParams, workspace, topfreq):
@@ -308,7 +360,7 @@ def make_step_caller(tables: Tables, sp: StepParams, workspace, topfreq):
     all arguments raw device addresses (ints).  Same entry point, same kernels; only the Python
     argument checking is hoisted out of the loop."""
     lib = load_library()
-    fn = lib.lsh_decode_step
+    fn, fn_timed = lib.lsh_decode_step, lib.lsh_decode_step_timed
     h = ctypes.c_void_p(tables.handle)
     spp = ctypes.pointer(sp)
     ws = ctypes.c_void_p(workspace.data_ptr())
@@ -317,7 +369,11 @@ def make_step_caller(tables: Tables, sp: StepParams, workspace, topfreq):
     keep = (tables, sp, workspace, topfreq)
 
     def call(H_ptr, bs_ptr, ob_ptr, ow_ptr, osc_ptr, stream_ptr, _keep=keep):
-        rc = fn(h, H_ptr, bs_ptr, tf, spp, ws, wsn, ob_ptr, ow_ptr, osc_ptr, stream_ptr)
+        if tables._prof:
+            rc = fn_timed(h, H_ptr, bs_ptr, tf, spp, ws, wsn, ob_ptr, ow_ptr, osc_ptr, stream_ptr,
+                          tables._prof)
+        else:
+            rc = fn(h, H_ptr, bs_ptr, tf, spp, ws, wsn, ob_ptr, ow_ptr, osc_ptr, stream_ptr)
         if rc:
             raise LshBeamError(rc, "lsh_decode_step")
 

@@ -13,7 +13,9 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <cctype>
 #include <new>
+#include <string>
 #include <type_traits>
 #include <vector>
 
@@ -44,14 +46,24 @@ struct HostBand {
     BandMeta meta{};
 };
 
-struct Profiler {
-    bool on = false;
-    int max_steps = 0;
+// Launch-plan options of a handle (lsh_set_option); kAuto = the library's own rule.
+enum Opt {
+    kOptFused, kOptFusedGrid, kOptLogitsGrid, kOptLogitsWaves, kOptLogitsHlds, kOptLogitsEstage,
+    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kNumOpts
+};
+constexpr int kAuto = -1;
+const char* const kOptNames[kNumOpts] = {
+    "fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
+    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows"};
+
+}  // namespace
+
+// Device start/stop events of the kernels of the steps it is handed to (lsh_decode_step_timed).
+struct lsh_profiler {
+    int max_launches = 0;
     std::vector<hipEvent_t> ev[LSH_NUM_KERNELS];  // start/stop pairs
     int used[LSH_NUM_KERNELS] = {0, 0, 0, 0, 0};
 };
-
-}  // namespace
 
 struct lsh_tables {
     int device = 0;
@@ -71,7 +83,8 @@ struct lsh_tables {
     int hit_list_cap = 0;
     int wg_union_logits_lds = 0;
     int built_on_device = 0, build_attempts = 0;  // how the tables came about (inspection)
-    Profiler prof;
+    int opt[kNumOpts];                            // launch-plan options, kAuto unless set
+    int option(int which, int dflt) const { return opt[which] == kAuto ? dflt : opt[which]; }
 };
 
 namespace {
@@ -147,14 +160,22 @@ lsh_status build_cuckoo(HostBand& hb, SplitMix64& rng, std::vector<Slot>& out, u
     return LSH_ERR_BUILD_FAILED;
 }
 
+// What a step's launches share: the (read-only) tables, the stream, and the caller's profiler.
+struct StepCtx {
+    const lsh_tables* t;
+    hipStream_t st;
+    lsh_profiler* prof;
+};
+
 template <typename... KArgs, typename... Args>
-void launch(lsh_tables* t, int which, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem,
-            hipStream_t stream, Args... args) {
-    Profiler& pf = t->prof;
-    if (pf.on && which >= 0 && pf.used[which] < pf.max_steps) {
-        const int i = pf.used[which]++;
-        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, stream, pf.ev[which][2 * i],
-                              pf.ev[which][2 * i + 1], 0, args...);
+void launch(const StepCtx& cx, int which, void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t shmem,
+            Args... args) {
+    lsh_profiler* pf = cx.prof;
+    hipStream_t stream = cx.st;
+    if (pf && which >= 0 && pf->used[which] < pf->max_launches) {
+        const int i = pf->used[which]++;
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, stream, pf->ev[which][2 * i],
+                              pf->ev[which][2 * i + 1], 0, args...);
     } else {
         hipLaunchKernelGGL(kernel, grid, block, (uint32_t)shmem, stream, args...);
     }
@@ -225,7 +246,7 @@ bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
     const bool possible = !sp->full_vocab && (size_t)t->wg_fused_lds <= kMaxDynLds && sp->S <= 64;
     // (with three or more groups of 16 beams the separate split-k kernel, one (tile, group) per
     // workgroup at a time, is faster than the fused kernel's all-groups-per-tile loop)
-    const bool wanted = env_int("LSHBEAM_FUSED", (sp->S * MT <= 8 && MT <= 2) ? 1 : 0) != 0;
+    const bool wanted = t->option(kOptFused, (sp->S * MT <= 8 && MT <= 2) ? 1 : 0) != 0;
     return possible && wanted;
 }
 
@@ -234,7 +255,7 @@ bool step_is_fused(const lsh_tables* t, const lsh_step_params* sp) {
 // it beside everything else the kernel keeps there, else the minimum stage.
 int stage_words_for(const lsh_tables* t, int B, bool fused_kernel) {
     const int mn = candidates_min_stage(t->d);
-    const int rows = std::min(B, std::max(0, env_int("LSHBEAM_STAGE_ROWS", kCandStageRows)));
+    const int rows = std::min(B, std::max(0, t->option(kOptStageRows, kCandStageRows)));
     const int64_t want = ((int64_t)rows * t->d + 3) & ~(int64_t)3;
     const size_t other = fused_kernel ? fused_lds_words(t->V, t->P, t->K, 0)
                                       : candidates_lds_words(t->V, t->P, t->K, 0);
@@ -250,39 +271,41 @@ int stage_words_for(const lsh_tables* t, int B, bool fused_kernel) {
 int part_rows_of(const lsh_tables* t, const lsh_step_params* sp, int stage_words) {
     if (sp->full_vocab || sp->threshold != 1) return 0;
     const int rpc = candidates_rows_per_chunk(sp->B, t->d, t->W, candidates_min_stage(t->d));
-    const int forced = env_int("LSHBEAM_PART_ROWS", 0);
+    const int forced = t->option(kOptPartRows, 0);
     if (forced > 0) return std::min(forced, rpc);
     return sp->B > candidates_rows_per_chunk(sp->B, t->d, t->W, stage_words) ? rpc : 0;
 }
 
 template <typename ET, int WAVES>
-void launch_logits_w(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
+void launch_logits_w(const StepCtx& cx, int grid, bool aligned, const float* H,
                      const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
                      const Workspace& w) {
+    const lsh_tables* t = cx.t;
     constexpr int UNROLL = (WAVES >= 16) ? 4 : 8;
     const ET* E = (const ET*)t->E;
     if (aligned)
-        launch(t, 1, k_logits<ET, WAVES, UNROLL, true>, dim3(grid), dim3(WAVES * kWave), 0, st, E,
+        launch(cx, 1, k_logits<ET, WAVES, UNROLL, true>, dim3(grid), dim3(WAVES * kWave), 0, E,
                t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials,
                w.ppitch);
     else
-        launch(t, 1, k_logits<ET, WAVES, UNROLL, false>, dim3(grid), dim3(WAVES * kWave), 0, st, E,
+        launch(cx, 1, k_logits<ET, WAVES, UNROLL, false>, dim3(grid), dim3(WAVES * kWave), 0, E,
                t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials,
                w.ppitch);
 }
 
 template <typename ET, int MT>
-void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, const float* H,
+void launch_logits_wave(const StepCtx& cx, int grid, bool aligned, const float* H,
                         const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
                         const Workspace& w) {
+    const lsh_tables* t = cx.t;
     // loads in flight per lane: 32 (fp32) / 64 (bf16) bytes of E per step, plus MT times that of H
     constexpr int UNROLL = ((MT == 1) ? 8 : 4) / (ElemTraits<ET>::VEC / 4);
     const ET* E = (const ET*)t->E;
     if (aligned)
-        launch(t, 1, k_logits_wave<ET, MT, UNROLL, true>, dim3(grid), dim3(256), 0, st, E, t->ld, t->d,
+        launch(cx, 1, k_logits_wave<ET, MT, UNROLL, true>, dim3(grid), dim3(256), 0, E, t->ld, t->d,
                H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
     else
-        launch(t, 1, k_logits_wave<ET, MT, UNROLL, false>, dim3(grid), dim3(256), 0, st, E, t->ld, t->d,
+        launch(cx, 1, k_logits_wave<ET, MT, UNROLL, false>, dim3(grid), dim3(256), 0, E, t->ld, t->d,
                H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
 }
 
@@ -291,8 +314,8 @@ void launch_logits_wave(lsh_tables* t, hipStream_t st, int grid, bool aligned, c
 // if even one 16-row group does not fit (very large d): the caller then keeps the hidden rows
 // in global memory.
 constexpr size_t kHldsHalf = 78 * 1024;
-inline int hlds_group_rows(int S, int B, int d) {
-    const int forced = env_int("LSHBEAM_HLDS_ROWS", 0);  // 16 or 32 (measurements)
+inline int hlds_group_rows(const lsh_tables* t, int S, int B, int d) {
+    const int forced = t->option(kOptHldsRows, 0);  // 16 or 32 (measurements)
     if (forced == 16 || forced == 32)
         return hlds_lds_bytes(S, std::min(forced, B), d, 16) <= kMaxDynLds ? std::min(forced, B) : 0;
     // up to 32 beams: one group; more: groups of 16, a workgroup each (measured at S = 4: B = 50,
@@ -305,9 +328,10 @@ inline int hlds_group_rows(int S, int B, int d) {
 }
 
 template <typename ET>
-void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool aligned, const float* H,
+void launch_logits_hlds(const StepCtx& cx, int64_t tiles_n, bool aligned, const float* H,
                         const lsh_step_params* sp, const int32_t* cand, const int32_t* count,
                         const Workspace& w, int group_rows) {
+    const lsh_tables* t = cx.t;
     constexpr int U1 = 8 / (ElemTraits<ET>::VEC / 4), U2 = 4 / (ElemTraits<ET>::VEC / 4);
     // (1024-thread workgroups have 128 registers per lane: one load less in flight)
     constexpr int U2W = (U2 > 2) ? U2 - 1 : U2;
@@ -319,12 +343,11 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
     do {                                                                                             \
         auto kfn = k_logits_hlds<ET, MTV, WV, UV, AL, PL>;                                           \
         const size_t lds = hlds_lds_bytes(sp->S, rows, t->d, WV, PL);                                \
-        (void)allow_whole_lds<k_logits_hlds<ET, MTV, WV, UV, AL, PL>>();                             \
         const int gx = (int)std::min<int64_t>(                                                       \
-            tiles_n, std::max(1, env_int("LSHBEAM_LOGITS_GRID", 4096 / WV) / ngroups));              \
+            tiles_n, std::max(1, t->option(kOptLogitsGrid, 4096 / WV) / ngroups));              \
         const int grid = ((gx + 7) / 8 * 8) * ngroups;                                               \
-        launch(t, 1, kfn, dim3(grid), dim3(WV * kWave), lds, st, E, t->ld, t->d, H, sp->S, sp->B,   \
-               rows, gx, ngroups, env_int("LSHBEAM_HLDS_REM", 4), cand, count, t->V, w.logits,      \
+        launch(cx, 1, kfn, dim3(grid), dim3(WV * kWave), lds, E, t->ld, t->d, H, sp->S, sp->B,   \
+               rows, gx, ngroups, t->option(kOptHldsRem, 4), cand, count, t->V, w.logits,      \
                w.cpitch, w.partials, w.ppitch);                                                      \
     } while (0)
     // bf16 rows, up to 16 hidden rows per group, two workgroups per CU: the hidden rows go to LDS
@@ -332,7 +355,7 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
     // (LSHBEAM_LOGITS_PLANES=0: widened to fp32 as for every other shape)
     if constexpr (std::is_same<ET, uint16_t>::value) {
         if (aligned && rows <= kTileM && hlds_lds_bytes(sp->S, rows, t->d, 8, true) <= kHldsHalf &&
-            env_int("LSHBEAM_LOGITS_PLANES", 1)) {
+            t->option(kOptLogitsPlanes, 1)) {
             LSH_HLDS(1, 8, U1, true, true);
             return;
         }
@@ -351,18 +374,18 @@ void launch_logits_hlds(lsh_tables* t, hipStream_t st, int64_t tiles_n, bool ali
 
 // k_logits_estage: 33..64 beams, fp32 rows of at most 1024 values, 16-byte aligned operands, at
 // most 256 sentences.  About one workgroup per CU, dealt evenly to the sentences.
-void launch_logits_estage(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
+void launch_logits_estage(const StepCtx& cx, const float* H, const lsh_step_params* sp,
                           const int32_t* cand, const int32_t* count, const Workspace& w) {
+    const lsh_tables* t = cx.t;
     const float* E = (const float*)t->E;
     const int MT = (sp->B + kTileM - 1) / kTileM;
     const size_t lds = estage_lds_bytes();
-    const int per_sentence = std::max(1, env_int("LSHBEAM_LOGITS_GRID", 256) / sp->S);
+    const int per_sentence = std::max(1, t->option(kOptLogitsGrid, 256) / sp->S);
     const dim3 grid((unsigned)(per_sentence * sp->S)), block(1024);
 #define LSH_ESTAGE(MTV)                                                                              \
     do {                                                                                             \
         auto kfn = k_logits_estage<MTV>;                                                             \
-        (void)allow_whole_lds<k_logits_estage<MTV>>();                                               \
-        launch(t, 1, kfn, grid, block, lds, st, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, \
+        launch(cx, 1, kfn, grid, block, lds, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, \
                w.logits, w.cpitch, w.partials, w.ppitch);                                            \
     } while (0)
     if (MT <= 3) LSH_ESTAGE(3); else LSH_ESTAGE(4);
@@ -370,8 +393,9 @@ void launch_logits_estage(lsh_tables* t, hipStream_t st, const float* H, const l
 }
 
 template <typename ET>
-void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step_params* sp,
+void launch_logits(const StepCtx& cx, const float* H, const lsh_step_params* sp,
                    const int32_t* cand, const int32_t* count, const Workspace& w) {
+    const lsh_tables* t = cx.t;
     constexpr int VEC = ElemTraits<ET>::VEC;
     const bool aligned = (t->d % VEC == 0) && (t->ld % VEC == 0) && ((uintptr_t)t->E % 16 == 0) &&
                          (t->d % 4 == 0) && ((uintptr_t)H % 16 == 0);
@@ -384,34 +408,52 @@ void launch_logits(lsh_tables* t, hipStream_t st, const float* H, const lsh_step
     // (the full-vocabulary mode has V / 16 tiles per sentence, known here: thousands of tiles
     // are "many" even for one sentence -- 29.9 against 37.1 us at V = 40000)
     const bool few = sp->S * MT <= 8 && !(count == nullptr && tiles_n >= 1024);
-    const int mode = env_int("LSHBEAM_LOGITS_WAVES", few ? 16 : 1);
+    const int mode = t->option(kOptLogitsWaves, few ? 16 : 1);
     // one wave per tile with the sentence's hidden rows staged in LDS, more than 32 rows in
     // groups; LSHBEAM_LOGITS_HLDS=0 keeps the rows in global memory (k_logits_wave)
-    const int group_rows = hlds_group_rows(sp->S, sp->B, t->d);
+    const int group_rows = hlds_group_rows(t, sp->S, sp->B, t->d);
     // 33..64 beams: hidden rows in registers, candidate rows through LDS (LSHBEAM_LOGITS_ESTAGE=0:
     // the other drivers)
     const bool estage_ok = std::is_same<ET, float>::value && aligned && sp->B > 2 * kTileM &&
                            sp->B <= 4 * kTileM && t->d <= kEsSlices * kEsSlice && sp->S <= 256 &&
                            estage_lds_bytes() <= kMaxDynLds;
-    if (estage_ok && env_int("LSHBEAM_LOGITS_ESTAGE", 1) && !env_int("LSHBEAM_LOGITS_WAVES", 0)) {
-        launch_logits_estage(t, st, H, sp, cand, count, w);
-    } else if (mode == 1 && group_rows > 0 && env_int("LSHBEAM_LOGITS_HLDS", 1)) {
-        launch_logits_hlds<ET>(t, st, tiles_n, aligned, H, sp, cand, count, w, group_rows);
+    if (estage_ok && t->option(kOptLogitsEstage, 1) && !t->option(kOptLogitsWaves, 0)) {
+        launch_logits_estage(cx, H, sp, cand, count, w);
+    } else if (mode == 1 && group_rows > 0 && t->option(kOptLogitsHlds, 1)) {
+        launch_logits_hlds<ET>(cx, tiles_n, aligned, H, sp, cand, count, w, group_rows);
     } else if (mode == 1 && MT <= 4) {
-        const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, env_int("LSHBEAM_LOGITS_GRID", 1024));
+        const int grid = (int)std::min<int64_t>((tiles_n + 3) / 4, t->option(kOptLogitsGrid, 1024));
         switch (MT) {
-            case 1: launch_logits_wave<ET, 1>(t, st, grid, aligned, H, sp, cand, count, w); break;
-            case 2: launch_logits_wave<ET, 2>(t, st, grid, aligned, H, sp, cand, count, w); break;
-            case 3: launch_logits_wave<ET, 3>(t, st, grid, aligned, H, sp, cand, count, w); break;
-            default: launch_logits_wave<ET, 4>(t, st, grid, aligned, H, sp, cand, count, w); break;
+            case 1: launch_logits_wave<ET, 1>(cx, grid, aligned, H, sp, cand, count, w); break;
+            case 2: launch_logits_wave<ET, 2>(cx, grid, aligned, H, sp, cand, count, w); break;
+            case 3: launch_logits_wave<ET, 3>(cx, grid, aligned, H, sp, cand, count, w); break;
+            default: launch_logits_wave<ET, 4>(cx, grid, aligned, H, sp, cand, count, w); break;
         }
     } else if (mode >= 16) {
-        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 256));
-        launch_logits_w<ET, 16>(t, st, grid, aligned, H, sp, cand, count, w);
+        const int grid = (int)std::min<int64_t>(max_tiles, t->option(kOptLogitsGrid, 256));
+        launch_logits_w<ET, 16>(cx, grid, aligned, H, sp, cand, count, w);
     } else {
-        const int grid = (int)std::min<int64_t>(max_tiles, env_int("LSHBEAM_LOGITS_GRID", 2048));
-        launch_logits_w<ET, 4>(t, st, grid, aligned, H, sp, cand, count, w);
+        const int grid = (int)std::min<int64_t>(max_tiles, t->option(kOptLogitsGrid, 2048));
+        launch_logits_w<ET, 4>(cx, grid, aligned, H, sp, cand, count, w);
     }
+}
+
+template <typename ET>
+hipError_t allow_logits_lds() {
+    constexpr int U1 = 8 / (ElemTraits<ET>::VEC / 4), U2 = 4 / (ElemTraits<ET>::VEC / 4);
+    constexpr int U2W = (U2 > 2) ? U2 - 1 : U2;
+    hipError_t e = hipSuccess;
+#define LSH_ALLOW(...)                                                   \
+    do {                                                                 \
+        if (e == hipSuccess) e = allow_whole_lds<k_logits_hlds<ET, __VA_ARGS__>>(); \
+    } while (0)
+    LSH_ALLOW(1, 8, U1, true, false);  LSH_ALLOW(1, 8, U1, false, false);
+    LSH_ALLOW(2, 8, U2, true, false);  LSH_ALLOW(2, 8, U2, false, false);
+    LSH_ALLOW(1, 16, U1, true, false); LSH_ALLOW(1, 16, U1, false, false);
+    LSH_ALLOW(2, 16, U2W, true, false); LSH_ALLOW(2, 16, U2W, false, false);
+    if constexpr (std::is_same<ET, uint16_t>::value) LSH_ALLOW(1, 8, U1, true, true);
+#undef LSH_ALLOW
+    return e;
 }
 
 #define HIP_TRY(expr)                                   \
@@ -648,6 +690,95 @@ lsh_status build_on_device(lsh_tables* t, hipStream_t st, SplitMix64& rng) {
     return LSH_OK;
 }
 
+// The decode step behind every public variant of it: validation, launch plan, launches.
+lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
+                            const int32_t* topfreq_dev, const lsh_step_params* sp,
+                            void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
+                            int32_t* out_word_dev, float* out_score_dev, void* hip_stream,
+                            lsh_profiler* prof) {
+    if (!t || !H_dev || !beam_scores_dev || !sp || !workspace_dev || !out_beam_dev ||
+        !out_word_dev || !out_score_dev)
+        return LSH_ERR_INVALID_ARG;
+    if (!step_params_ok(t, sp)) return LSH_ERR_INVALID_ARG;
+    if (!sp->full_vocab && sp->T > 0 && !topfreq_dev) return LSH_ERR_INVALID_ARG;
+    if (!sp->full_vocab && sp->threshold < 1) return LSH_ERR_INVALID_ARG;
+    if (!sp->full_vocab && sp->threshold > 1 && t->wg_hit_rows_lds == 0) return LSH_ERR_UNSUPPORTED;
+    if ((uintptr_t)workspace_dev % kAlign) return LSH_ERR_INVALID_ARG;
+    const Workspace w = carve(t, sp, workspace_dev);
+    if (workspace_bytes < w.bytes) return LSH_ERR_WORKSPACE_TOO_SMALL;
+    const StepCtx cx{t, (hipStream_t)hip_stream, prof};
+    const int32_t* cand = nullptr;
+    const int32_t* count = nullptr;
+    const bool fused = step_is_fused(t, sp);
+    const int stage = stage_words_for(t, sp->B, fused);
+    CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
+                t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T, t->cuts_dev, stage};
+    // Bitmaps made by an earlier kernel, to be OR-ed per sentence: one per hidden row when the
+    // hit threshold is above 1 (Eq. 9-10), one per part of the sentence when it has many beams.
+    const uint32_t* parts = nullptr;
+    int nparts = 0;
+    if (!sp->full_vocab && sp->threshold > 1) {
+        launch(cx, 3, k_hit_rows, dim3(sp->S * sp->B * kHitSlices), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds,
+               ca, (int)sp->threshold, t->hit_list_cap, w.row_bitmaps);
+        parts = w.row_bitmaps;
+        nparts = sp->B;
+    } else if (const int pr = part_rows_of(t, sp, stage)) {
+        nparts = (sp->B + pr - 1) / pr;
+        ca.stage_words = candidates_min_stage(t->d);
+        launch(cx, 4, k_part_bitmaps, dim3(sp->S * nparts), dim3(kCandThreads), (size_t)t->wg_candidates_lds,
+               ca, pr, nparts, w.row_bitmaps);
+        parts = w.row_bitmaps;
+    }
+    if (fused) {
+        const int per_sentence = std::max(1, t->option(kOptFusedGrid, 256) / sp->S);
+        const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
+        const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
+        const bool f32 = t->dtype == LSH_F32;
+        const bool al = f32 ? (aligned16 && t->ld % 4 == 0) : (aligned16 && t->ld % 8 == 0 && t->d % 8 == 0);
+        if (parts) {
+            const size_t lds = (size_t)t->wg_union_logits_lds;
+#define LSH_UNION_LOGITS(ET, AL)                                                                  \
+    launch(cx, 1, k_union_logits<ET, AL>, grid, block, lds, parts, nparts, topfreq_dev, sp->T, \
+           (const ET*)t->E, t->ld, t->d, H_dev, sp->S, sp->B, t->V, w.cand, w.count, w.logits,    \
+           w.cpitch, w.partials, w.ppitch)
+            if (f32) { if (al) LSH_UNION_LOGITS(float, true); else LSH_UNION_LOGITS(float, false); }
+            else { if (al) LSH_UNION_LOGITS(uint16_t, true); else LSH_UNION_LOGITS(uint16_t, false); }
+#undef LSH_UNION_LOGITS
+        } else {
+            const size_t lds = fused_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t);
+#define LSH_CAND_LOGITS(ET, AL)                                                                   \
+    launch(cx, 1, k_cand_logits<ET, AL>, grid, block, lds, ca, (const ET*)t->E, t->ld, sp->S,  \
+           w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch)
+            if (f32) { if (al) LSH_CAND_LOGITS(float, true); else LSH_CAND_LOGITS(float, false); }
+            else { if (al) LSH_CAND_LOGITS(uint16_t, true); else LSH_CAND_LOGITS(uint16_t, false); }
+#undef LSH_CAND_LOGITS
+        }
+        cand = w.cand;
+        count = w.count;
+    } else {
+        if (parts) {
+            // union of the sentence's bitmaps + top-frequent words + compaction
+            launch(cx, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
+                   union_compact_lds_words(t->V) * sizeof(uint32_t), parts, nparts, t->V,
+                   topfreq_dev, sp->T, w.cand, w.count);
+            cand = w.cand;
+            count = w.count;
+        } else if (!sp->full_vocab) {
+            launch(cx, 0, k_candidates, dim3(sp->S), dim3(kCandThreads),
+                   candidates_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t), ca, w.cand, w.count);
+            cand = w.cand;
+            count = w.count;
+        }
+        if (t->dtype == LSH_F32) launch_logits<float>(cx, H_dev, sp, cand, count, w);
+        else launch_logits<uint16_t>(cx, H_dev, sp, cand, count, w);
+    }
+    launch(cx, 2, k_select, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits, w.cpitch,
+           (const float2*)w.partials, w.ppitch, cand, count, t->V, sp->B, beam_scores_dev, w.lse,
+           out_beam_dev, out_word_dev, out_score_dev);
+    HIP_TRY(hipGetLastError());
+    return LSH_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -688,8 +819,6 @@ void lsh_free_tables(lsh_tables* t) {
     (void)hipFree(t->slots_dev);
     (void)hipFree(t->cuts_dev);
     (void)hipFree(t->bands_dev);
-    for (int k = 0; k < LSH_NUM_KERNELS; ++k)
-        for (hipEvent_t e : t->prof.ev[k]) (void)hipEventDestroy(e);
     delete t;
 }
 
@@ -712,6 +841,13 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (!t) return LSH_ERR_OOM;
     struct Guard { lsh_tables* t; ~Guard() { if (t) lsh_free_tables(t); } } guard{t};
     HIP_TRY(hipGetDevice(&t->device));
+    // launch-plan options: the library's own rules unless LSHBEAM_<NAME> is set in the environment
+    // at this point (read once, here) or lsh_set_option changes them later
+    for (int i = 0; i < kNumOpts; ++i) {
+        std::string name = "LSHBEAM_";
+        for (const char* c = kOptNames[i]; *c; ++c) name += (char)std::toupper((unsigned char)*c);
+        t->opt[i] = env_int(name.c_str(), kAuto);
+    }
     t->E = E_dev; t->V = p->V; t->d = p->d; t->ld = p->ld_e; t->dtype = p->e_dtype;
     t->K = p->K; t->P = p->P; t->W = p->bands; t->u = u; t->bits = bits;
     const size_t V = t->V, W = t->W, PK = (size_t)t->P * t->K;
@@ -771,6 +907,10 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     HIP_TRY((allow_whole_lds<k_cand_logits<float, false>>()));
     HIP_TRY((allow_whole_lds<k_cand_logits<uint16_t, true>>()));
     HIP_TRY((allow_whole_lds<k_cand_logits<uint16_t, false>>()));
+    HIP_TRY(allow_logits_lds<float>());
+    HIP_TRY(allow_logits_lds<uint16_t>());
+    HIP_TRY(allow_whole_lds<k_logits_estage<3>>());
+    HIP_TRY(allow_whole_lds<k_logits_estage<4>>());
     guard.t = nullptr;
     *out = t;
     return LSH_OK;
@@ -781,92 +921,35 @@ size_t lsh_step_workspace_bytes(const lsh_tables* t, const lsh_step_params* sp) 
     return carve(t, sp, nullptr).bytes;
 }
 
-lsh_status lsh_decode_step(const lsh_tables* tc, const float* H_dev, const float* beam_scores_dev,
+lsh_status lsh_decode_step(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
                            const int32_t* topfreq_dev, const lsh_step_params* sp,
                            void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
                            int32_t* out_word_dev, float* out_score_dev, void* hip_stream) {
-    if (!tc || !H_dev || !beam_scores_dev || !sp || !workspace_dev || !out_beam_dev ||
-        !out_word_dev || !out_score_dev)
-        return LSH_ERR_INVALID_ARG;
-    if (!step_params_ok(tc, sp)) return LSH_ERR_INVALID_ARG;
-    if (!sp->full_vocab && sp->T > 0 && !topfreq_dev) return LSH_ERR_INVALID_ARG;
-    if (!sp->full_vocab && sp->threshold < 1) return LSH_ERR_INVALID_ARG;
-    if (!sp->full_vocab && sp->threshold > 1 && tc->wg_hit_rows_lds == 0) return LSH_ERR_UNSUPPORTED;
-    if ((uintptr_t)workspace_dev % kAlign) return LSH_ERR_INVALID_ARG;
-    lsh_tables* t = const_cast<lsh_tables*>(tc);  // only the profiler state is touched
-    const Workspace w = carve(t, sp, workspace_dev);
-    if (workspace_bytes < w.bytes) return LSH_ERR_WORKSPACE_TOO_SMALL;
-    hipStream_t st = (hipStream_t)hip_stream;
-    const int32_t* cand = nullptr;
-    const int32_t* count = nullptr;
-    const bool fused = step_is_fused(t, sp);
-    const int stage = stage_words_for(t, sp->B, fused);
-    CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
-                t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T, t->cuts_dev, stage};
-    // Bitmaps made by an earlier kernel, to be OR-ed per sentence: one per hidden row when the
-    // hit threshold is above 1 (Eq. 9-10), one per part of the sentence when it has many beams.
-    const uint32_t* parts = nullptr;
-    int nparts = 0;
-    if (!sp->full_vocab && sp->threshold > 1) {
-        launch(t, 3, k_hit_rows, dim3(sp->S * sp->B * kHitSlices), dim3(kCandThreads), (size_t)t->wg_hit_rows_lds, st,
-               ca, (int)sp->threshold, t->hit_list_cap, w.row_bitmaps);
-        parts = w.row_bitmaps;
-        nparts = sp->B;
-    } else if (const int pr = part_rows_of(t, sp, stage)) {
-        nparts = (sp->B + pr - 1) / pr;
-        ca.stage_words = candidates_min_stage(t->d);
-        launch(t, 4, k_part_bitmaps, dim3(sp->S * nparts), dim3(kCandThreads), (size_t)t->wg_candidates_lds,
-               st, ca, pr, nparts, w.row_bitmaps);
-        parts = w.row_bitmaps;
-    }
-    if (fused) {
-        const int per_sentence = std::max(1, env_int("LSHBEAM_FUSED_GRID", 256) / sp->S);
-        const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
-        const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
-        const bool f32 = t->dtype == LSH_F32;
-        const bool al = f32 ? (aligned16 && t->ld % 4 == 0) : (aligned16 && t->ld % 8 == 0 && t->d % 8 == 0);
-        if (parts) {
-            const size_t lds = (size_t)t->wg_union_logits_lds;
-#define LSH_UNION_LOGITS(ET, AL)                                                                  \
-    launch(t, 1, k_union_logits<ET, AL>, grid, block, lds, st, parts, nparts, topfreq_dev, sp->T, \
-           (const ET*)t->E, t->ld, t->d, H_dev, sp->S, sp->B, t->V, w.cand, w.count, w.logits,    \
-           w.cpitch, w.partials, w.ppitch)
-            if (f32) { if (al) LSH_UNION_LOGITS(float, true); else LSH_UNION_LOGITS(float, false); }
-            else { if (al) LSH_UNION_LOGITS(uint16_t, true); else LSH_UNION_LOGITS(uint16_t, false); }
-#undef LSH_UNION_LOGITS
-        } else {
-            const size_t lds = fused_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t);
-#define LSH_CAND_LOGITS(ET, AL)                                                                   \
-    launch(t, 1, k_cand_logits<ET, AL>, grid, block, lds, st, ca, (const ET*)t->E, t->ld, sp->S,  \
-           w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch)
-            if (f32) { if (al) LSH_CAND_LOGITS(float, true); else LSH_CAND_LOGITS(float, false); }
-            else { if (al) LSH_CAND_LOGITS(uint16_t, true); else LSH_CAND_LOGITS(uint16_t, false); }
-#undef LSH_CAND_LOGITS
-        }
-        cand = w.cand;
-        count = w.count;
-    } else {
-        if (parts) {
-            // union of the sentence's bitmaps + top-frequent words + compaction
-            launch(t, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
-                   union_compact_lds_words(t->V) * sizeof(uint32_t), st, parts, nparts, t->V,
-                   topfreq_dev, sp->T, w.cand, w.count);
-            cand = w.cand;
-            count = w.count;
-        } else if (!sp->full_vocab) {
-            launch(t, 0, k_candidates, dim3(sp->S), dim3(kCandThreads),
-                   candidates_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t), st, ca, w.cand, w.count);
-            cand = w.cand;
-            count = w.count;
-        }
-        if (t->dtype == LSH_F32) launch_logits<float>(t, st, H_dev, sp, cand, count, w);
-        else launch_logits<uint16_t>(t, st, H_dev, sp, cand, count, w);
-    }
-    launch(t, 2, k_select, dim3(sp->S), dim3(kSelThreads), 0, st, (const float*)w.logits, w.cpitch,
-           (const float2*)w.partials, w.ppitch, cand, count, t->V, sp->B, beam_scores_dev, w.lse,
-           out_beam_dev, out_word_dev, out_score_dev);
-    HIP_TRY(hipGetLastError());
-    return LSH_OK;
+    return decode_step_impl(t, H_dev, beam_scores_dev, topfreq_dev, sp, workspace_dev, workspace_bytes,
+                            out_beam_dev, out_word_dev, out_score_dev, hip_stream, nullptr);
+}
+
+lsh_status lsh_decode_step_timed(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
+                                 const int32_t* topfreq_dev, const lsh_step_params* sp,
+                                 void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
+                                 int32_t* out_word_dev, float* out_score_dev, void* hip_stream,
+                                 lsh_profiler* prof) {
+    return decode_step_impl(t, H_dev, beam_scores_dev, topfreq_dev, sp, workspace_dev, workspace_bytes,
+                            out_beam_dev, out_word_dev, out_score_dev, hip_stream, prof);
+}
+
+lsh_status lsh_set_option(lsh_tables* t, const char* name, int32_t value) {
+    if (!t || !name || value < kAuto) return LSH_ERR_INVALID_ARG;
+    for (int i = 0; i < kNumOpts; ++i)
+        if (std::strcmp(name, kOptNames[i]) == 0) { t->opt[i] = value; return LSH_OK; }
+    return LSH_ERR_INVALID_ARG;
+}
+
+lsh_status lsh_get_option(const lsh_tables* t, const char* name, int32_t* value_out) {
+    if (!t || !name || !value_out) return LSH_ERR_INVALID_ARG;
+    for (int i = 0; i < kNumOpts; ++i)
+        if (std::strcmp(name, kOptNames[i]) == 0) { *value_out = t->opt[i]; return LSH_OK; }
+    return LSH_ERR_INVALID_ARG;
 }
 
 /* ---- inspection ----------------------------------------------------------------------------- */
@@ -991,38 +1074,47 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
 
 /* ---- per-kernel timing ---------------------------------------------------------------------- */
 
-lsh_status lsh_profile_begin(lsh_tables* t, int32_t max_steps) {
-    if (!t || max_steps < 1 || max_steps > (1 << 16)) return LSH_ERR_INVALID_ARG;
-    Profiler& pf = t->prof;
-    for (int k = 0; k < LSH_NUM_KERNELS; ++k) {
-        while ((int)pf.ev[k].size() < 2 * max_steps) {
+void lsh_profiler_destroy(lsh_profiler* pf) {
+    if (!pf) return;
+    for (int k = 0; k < LSH_NUM_KERNELS; ++k)
+        for (hipEvent_t e : pf->ev[k]) (void)hipEventDestroy(e);
+    delete pf;
+}
+
+lsh_status lsh_profiler_create(int32_t max_launches, lsh_profiler** out) {
+    if (!out || max_launches < 1 || max_launches > (1 << 16)) return LSH_ERR_INVALID_ARG;
+    *out = nullptr;
+    lsh_profiler* pf = new (std::nothrow) lsh_profiler();
+    if (!pf) return LSH_ERR_OOM;
+    pf->max_launches = max_launches;
+    for (int k = 0; k < LSH_NUM_KERNELS; ++k)
+        for (int i = 0; i < 2 * max_launches; ++i) {
             hipEvent_t e;
-            HIP_TRY(hipEventCreate(&e));
-            pf.ev[k].push_back(e);
+            if (hipEventCreate(&e) != hipSuccess) {
+                (void)hipGetLastError();
+                lsh_profiler_destroy(pf);
+                return LSH_ERR_HIP;
+            }
+            pf->ev[k].push_back(e);
         }
-        pf.used[k] = 0;
-    }
-    pf.max_steps = max_steps;
-    pf.on = true;
+    *out = pf;
     return LSH_OK;
 }
 
-lsh_status lsh_profile_end(lsh_tables* t, double mean_ms_out[LSH_NUM_KERNELS],
-                           int32_t launches_out[LSH_NUM_KERNELS]) {
-    if (!t || !mean_ms_out || !launches_out) return LSH_ERR_INVALID_ARG;
-    Profiler& pf = t->prof;
-    if (!pf.on) return LSH_ERR_INVALID_ARG;
-    pf.on = false;
+lsh_status lsh_profiler_read(lsh_profiler* pf, double mean_ms_out[LSH_NUM_KERNELS],
+                             int32_t launches_out[LSH_NUM_KERNELS]) {
+    if (!pf || !mean_ms_out || !launches_out) return LSH_ERR_INVALID_ARG;
     HIP_TRY(hipDeviceSynchronize());
     for (int k = 0; k < LSH_NUM_KERNELS; ++k) {
         double total = 0.0;
-        for (int i = 0; i < pf.used[k]; ++i) {
+        for (int i = 0; i < pf->used[k]; ++i) {
             float ms = 0.f;
-            HIP_TRY(hipEventElapsedTime(&ms, pf.ev[k][2 * i], pf.ev[k][2 * i + 1]));
+            HIP_TRY(hipEventElapsedTime(&ms, pf->ev[k][2 * i], pf->ev[k][2 * i + 1]));
             total += ms;
         }
-        launches_out[k] = pf.used[k];
-        mean_ms_out[k] = pf.used[k] ? total / pf.used[k] : 0.0;
+        launches_out[k] = pf->used[k];
+        mean_ms_out[k] = pf->used[k] ? total / pf->used[k] : 0.0;
+        pf->used[k] = 0;
     }
     return LSH_OK;
 }
@@ -1068,19 +1160,5 @@ lsh_status lsh_beam_backtrace(const lsh_beam_params* bp, int32_t n_steps, const 
     HIP_TRY(hipGetLastError());
     return LSH_OK;
 }
-
-#ifdef LSHBEAM_TRACE
-// Development builds only: copy the in-kernel phase timestamps (100 MHz ticks) to the host.
-int lsh_trace_read(unsigned long long* out_host) {
-    if (hipDeviceSynchronize() != hipSuccess) return 1;
-    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace),
-                               sizeof(unsigned long long) * kTraceKernels * kTraceSlots) != hipSuccess;
-}
-int lsh_trace_read_wg(unsigned long long* out_host) {
-    if (hipDeviceSynchronize() != hipSuccess) return 1;
-    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace_wg),
-                               sizeof(unsigned long long) * kTraceWgs * kTraceWgSlots) != hipSuccess;
-}
-#endif
 
 }  // extern "C"

@@ -28,6 +28,17 @@ __device__ unsigned long long g_trace_wg[kTraceWgs][kTraceWgSlots];  // per work
         if (threadIdx.x == 0 && blockIdx.x < lshbeam::kTraceWgs)                  \
             lshbeam::g_trace_wg[blockIdx.x][slot] = wall_clock64();               \
     } while (0)
+// Development builds only: copy the phase timestamps (100 MHz ticks) to the host.
+extern "C" inline int lsh_trace_read(unsigned long long* out_host) {
+    if (hipDeviceSynchronize() != hipSuccess) return 1;
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace),
+                               sizeof(unsigned long long) * lshbeam::kTraceKernels * lshbeam::kTraceSlots) != hipSuccess;
+}
+extern "C" inline int lsh_trace_read_wg(unsigned long long* out_host) {
+    if (hipDeviceSynchronize() != hipSuccess) return 1;
+    return hipMemcpyFromSymbol(out_host, HIP_SYMBOL(lshbeam::g_trace_wg),
+                               sizeof(unsigned long long) * lshbeam::kTraceWgs * lshbeam::kTraceWgSlots) != hipSuccess;
+}
 #else
 #define LSH_TRACE_WG(slot) do { } while (0)
 #define LSH_TRACE(kernel, slot) do { } while (0)

@@ -24,6 +24,20 @@ def hidden(cfg, gc, steps):
     return workloads.make_hidden(cfg, gc.E, seed=0, steps=steps)
 
 
+@pytest.fixture
+def force():
+    """force(gc, name=value, ...): launch-plan options (lsh_set_option) on a case's tables for the
+    rest of the test; every option is restored to the library's own rule afterwards."""
+    touched = []
+
+    def _force(gc, **opts):
+        touched.append(gc)
+        gc.tables.set_options(**opts)
+    yield _force
+    for gc in touched:
+        gc.tables.reset_options()
+
+
 # ---------------------------------------------------------------------------------------------
 # build: codes, buckets, cuckoo
 # ---------------------------------------------------------------------------------------------
@@ -405,21 +419,19 @@ def test_largevocab_bf16_shape():
 
 
 @pytest.mark.parametrize("planes", ["1", "0"])
-def test_bf16_rows_with_hidden_rows_as_three_bf16_planes(planes, monkeypatch):
+def test_bf16_rows_with_hidden_rows_as_three_bf16_planes(planes, force):
     # bf16 rows, up to 16 beams, many tiles: the hidden rows are staged as hi + mid + lo bf16
     # planes (an exact split of every fp32 value) and contracted with bf16 matrix instructions;
-    # LSHBEAM_LOGITS_PLANES=0 widens the rows to fp32 instead.  Hidden values span 40 binades,
+    # option logits_planes = 0 widens the rows to fp32 instead.  Hidden values span 40 binades,
     # with full 24-bit significands, signed zeros and tiny values; d = 264 leaves a last k-step
     # of which only a quarter lies inside the row.
-    monkeypatch.setenv("LSHBEAM_FUSED", "0")
-    monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
-    monkeypatch.setenv("LSHBEAM_LOGITS_PLANES", planes)
     rng = np.random.default_rng(264)
     V, d, K, P, W = 3000, 264, 8, 16, 4
     E32 = (rng.standard_normal((V, d)) / np.sqrt(d)).astype(np.float32)
     E = workloads.f32_to_bf16_bits(E32)
     perms = np.stack([rng.permutation(d)[:K] for _ in range(P)]).astype(np.int32)
     gc = GpuCase(E, perms, np.arange(100, dtype=np.int32), W)
+    force(gc, fused=0, logits_waves=1, logits_planes=int(planes))
     H = rng.standard_normal((64, d)).astype(np.float32)
     H *= np.exp2(rng.integers(-20, 21, size=(64, 1))).astype(np.float32)   # per-row scale
     H[:, ::7] *= np.float32(1.0 + 2.0 ** -23)                               # low significand bits set
@@ -589,8 +601,8 @@ def test_step_is_deterministic():
 @pytest.mark.parametrize("name,S,B,t", [("paper", 1, 12, 1), ("tiny", 2, 4, 1), ("tiny", 1, 20, 1),
                                         ("tiny", 2, 4, 2), ("paperscale", 1, 12, 5),
                                         ("paper", 1, 30, 1)])
-def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypatch):
-    # few sentences: candidates are regenerated inside the logits kernel; LSHBEAM_FUSED=0 forces
+def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, force):
+    # few sentences: candidates are regenerated inside the logits kernel; option fused = 0 forces
     # the general three-kernel path.  Same arithmetic, same order: every output must be identical.
     from paper_1806_00588_amd import binding
     cfg, gc = case(name)
@@ -598,7 +610,7 @@ def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypat
     bs = np.linspace(-1, 0, S * B).astype(np.float32)
     res = {}
     for mode in ("1", "0"):
-        monkeypatch.setenv("LSHBEAM_FUSED", mode)
+        force(gc, fused=int(mode))
         gb, gw, gs, sp, ws = gc.step(H, bs, S, B, threshold=t)
         assert binding.step_is_fused(gc.tables, sp) == (mode == "1")
         cands = [gc.tables.debug_candidates(ws, sp, s) for s in range(S)]
@@ -613,11 +625,11 @@ def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, monkeypat
 
 
 @pytest.mark.parametrize("part_rows", [1, 3, 5])
-def test_sentence_hashed_in_parts(part_rows, monkeypatch):
+def test_sentence_hashed_in_parts(part_rows, force):
     # sentences with many beams are hashed by several workgroups, each leaving a bitmap that the
-    # consumer ORs; LSHBEAM_PART_ROWS forces small parts so that the tiny shape takes this plan
-    monkeypatch.setenv("LSHBEAM_PART_ROWS", str(part_rows))
+    # consumer ORs; option part_rows forces small parts so that the tiny shape takes this plan
     cfg, gc = case("tiny")
+    force(gc, part_rows=part_rows)
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)
     rng = np.random.default_rng(part_rows)
@@ -641,20 +653,17 @@ def test_paper_shape_wide_beams():
 
 
 @pytest.mark.parametrize("hlds,rows", [("0", "0"), ("1", "0"), ("1", "32"), ("1", "16")])
-def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, rows, monkeypatch):
+def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, rows, force):
     # many-tile steps stage the sentence's hidden rows in LDS (more than 32 beams: in groups of 16
-    # rows along the grid's second dimension; LSHBEAM_HLDS_ROWS forces a group size);
-    # LSHBEAM_LOGITS_HLDS=0 reads them from global memory
+    # rows, a workgroup each; option hlds_rows forces a group size); option logits_hlds = 0 reads
+    # them from global memory
     cfg, gc = case("tiny")
-    monkeypatch.setenv("LSHBEAM_FUSED", "0")
-    monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
-    monkeypatch.setenv("LSHBEAM_LOGITS_HLDS", hlds)
-    monkeypatch.setenv("LSHBEAM_HLDS_ROWS", rows)
+    force(gc, fused=0, logits_waves=1, logits_hlds=int(hlds), hlds_rows=int(rows))
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)
     rng = np.random.default_rng(3)
     for grid in ("1", "3", "512"):
-        monkeypatch.setenv("LSHBEAM_LOGITS_GRID", grid)
+        force(gc, logits_grid=int(grid))
         for S, B in [(5, 16), (2, 17), (3, 40), (2, 70), (1, 33), (7, 4)]:
             bs = rng.standard_normal(S * B).astype(np.float32)
             run_and_check(cfg, gc, H[:S * B], bs, S, B)
@@ -662,18 +671,19 @@ def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, rows, mon
 
 
 @pytest.mark.parametrize("grid", ["256", "4", "1"])
-def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_lds(grid, monkeypatch):
+def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_lds(grid, force):
     # 33..64 beams, fp32 rows: the workgroup keeps the hidden rows in registers and double-buffers
     # the tiles' candidate rows through LDS.  Small grids give a workgroup many tiles (both
     # buffers in use, the last tile ragged); d = 1000 leaves 24 zeroed pad columns, d = 64 leaves 960.
-    monkeypatch.setenv("LSHBEAM_LOGITS_GRID", grid)
     cfg, gc = case("paper")
+    force(gc, logits_grid=int(grid))
     H = hidden(cfg, gc, 12).reshape(-1, cfg.d)                    # 144 rows
     rng = np.random.default_rng(int(grid))
     for S, B in [(2, 50), (1, 33), (2, 64), (3, 48)]:
         bs = rng.standard_normal(S * B).astype(np.float32)
         run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(B == 33))
     cfg, gc = case("tiny")
+    force(gc, logits_grid=int(grid))
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     H = np.concatenate([H, H[::-1] * 0.5 + 0.1, H * 0.25 - 0.1], axis=0)
     for S, B in [(3, 40), (2, 64), (1, 33), (4, 49)]:
@@ -688,15 +698,12 @@ def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_ld
 
 @pytest.mark.parametrize("rem", ["4", "0"])
 @pytest.mark.parametrize("grid", [1, 2, 3, 5, 8, 16])
-def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, rem, monkeypatch):
+def test_wave_kernel_remainder_tiles_split_over_workgroups(grid, rem, force):
     # one wave per tile for whole rounds of the (here artificially small) grid; a short last
-    # round (at most a quarter of the waves; LSHBEAM_HLDS_REM=0: any) is dealt to whole
+    # round (at most a quarter of the waves; option hlds_rem = 0: any) is dealt to whole
     # workgroups that split k.  Every grid size moves the boundary.
     cfg, gc = case("tiny")
-    monkeypatch.setenv("LSHBEAM_FUSED", "0")
-    monkeypatch.setenv("LSHBEAM_LOGITS_WAVES", "1")
-    monkeypatch.setenv("LSHBEAM_HLDS_REM", rem)
-    monkeypatch.setenv("LSHBEAM_LOGITS_GRID", str(grid))
+    force(gc, fused=0, logits_waves=1, hlds_rem=int(rem), logits_grid=grid)
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     rng = np.random.default_rng(grid)
     for S, B in [(3, 4), (2, 20), (1, 40), (4, 7)]:

@@ -36,7 +36,27 @@ def test_null_arguments_are_rejected_without_a_gpu():
     assert lib.lsh_build_tables(None, None, None, None, None) == 1
     assert lib.lsh_decode_step(None, None, None, None, None, None, 0, None, None, None, None) == 1
     assert lib.lsh_step_workspace_bytes(None, None) == 0
+    assert lib.lsh_decode_step_timed(None, None, None, None, None, None, 0, None, None, None, None,
+                                     None) == 1
+    assert lib.lsh_set_option(None, b"fused", 1) == 1
+    assert lib.lsh_get_option(None, b"fused", None) == 1
+    assert lib.lsh_profiler_create(0, None) == 1
+    lib.lsh_profiler_destroy(None)
     lib.lsh_free_tables(None)
+
+
+def test_decode_step_sources_never_read_the_environment():
+    # launch-plan knobs are parsed once, when a handle is built; the step itself must not call
+    # getenv (it is a hot call, and the environment is process-global state)
+    src = open(os.path.join(ROOT, "paper_1806_00588_amd", "csrc", "lshbeam.hip")).read()
+    assert src.count("std::getenv") == 1                      # inside env_int
+    users = [m.start() for m in re.finditer(r"env_int\(", src)]
+    step = src.index("lsh_status decode_step_impl(")
+    step_end = src.index("}  // namespace", step)
+    assert not any(step <= u < step_end for u in users)
+    for name in os.listdir(os.path.join(ROOT, "paper_1806_00588_amd", "csrc")):
+        if name.endswith(".h"):
+            assert "getenv" not in open(os.path.join(ROOT, "paper_1806_00588_amd", "csrc", name)).read()
 
 
 def test_product_package_does_not_import_the_oracle():
