@@ -38,7 +38,8 @@ typedef enum {
     LSH_ERR_BUILD_FAILED = 3,
     LSH_ERR_OOM = 4,
     LSH_ERR_HIP = 5,
-    LSH_ERR_WORKSPACE_TOO_SMALL = 6
+    LSH_ERR_WORKSPACE_TOO_SMALL = 6,
+    LSH_ERR_SCRATCH_TOO_SMALL = 7 /* lsh_decode_step_static: the step needs more than the built-in buffer */
 } lsh_status;
 
 typedef enum { LSH_F32 = 0, LSH_BF16 = 1 } lsh_dtype;
@@ -105,6 +106,25 @@ lsh_status lsh_decode_step(const lsh_tables* t, const float* H_dev, const float*
                            const int32_t* topfreq_dev, const lsh_step_params* sp,
                            void* workspace_dev, size_t workspace_bytes, int32_t* out_beam_dev,
                            int32_t* out_word_dev, float* out_score_dev, void* hip_stream);
+
+/* The decode step for callers that cannot allocate device memory or bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results as lsh_decode_step, but the working memory is a buffer built into the
+ * library: a static device array of lsh_static_scratch_bytes() = 32 MiB that every GPU the library
+ * runs on holds until the process ends (its address on a GPU is looked up once, when the first
+ * handle is built there).  The call allocates and frees nothing, on the device or through any
+ * allocating library routine.
+ *   - LSH_ERR_SCRATCH_TOO_SMALL if lsh_step_workspace_bytes(t, sp) exceeds the buffer (V = 40000:
+ *     about 150 hidden rows per call); nothing is launched and the outputs are untouched.
+ *   - All calls on one GPU share that GPU's buffer, across handles and streams: calls that overlap
+ *     in time race.  Serialise them (one stream, or events), or give lsh_decode_step workspaces.
+ *   - The buffer keeps the last call's contents; no step depends on them (every kernel of a step
+ *     writes what a later kernel of the same step reads). */
+size_t lsh_static_scratch_bytes(void);
+lsh_status lsh_decode_step_static(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
+                                  const int32_t* topfreq_dev, const lsh_step_params* sp,
+                                  int32_t* out_beam_dev, int32_t* out_word_dev, float* out_score_dev,
+                                  void* hip_stream);
 
 /* ---- beam bookkeeping around the step (Introduction, "Beam expansion"; Table 1, row "Hidden
  *      states reorder") ----------------------------------------------------------------------- */

@@ -20,7 +20,8 @@ EXPORTED_SYMBOLS = (
     "lsh_debug_cuckoo_shape", "lsh_debug_candidates", "lsh_debug_logprobs", "lsh_profiler_create",
     "lsh_profiler_destroy", "lsh_profiler_read", "lsh_decode_step_timed", "lsh_kernel_name",
     "lsh_status_string", "lsh_step_is_fused", "lsh_debug_build_info", "lsh_beam_advance",
-    "lsh_beam_backtrace", "lsh_set_option", "lsh_get_option",
+    "lsh_beam_backtrace", "lsh_set_option", "lsh_get_option", "lsh_decode_step_static",
+    "lsh_static_scratch_bytes",
 )
 
 OPTION_AUTO = -1
@@ -91,6 +92,9 @@ def load_library():
     lib.lsh_debug_logprobs.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32,
                                        ctypes.POINTER(ctypes.c_float), i32, i32p]
     lib.lsh_decode_step_timed.argtypes = lib.lsh_decode_step.argtypes + [vp]
+    lib.lsh_decode_step_static.argtypes = [vp, vp, vp, vp, ctypes.POINTER(StepParams), vp, vp, vp, vp]
+    lib.lsh_static_scratch_bytes.argtypes = []
+    lib.lsh_static_scratch_bytes.restype = sz
     lib.lsh_profiler_create.argtypes = [i32, ctypes.POINTER(vp)]
     lib.lsh_profiler_destroy.argtypes = [vp]
     lib.lsh_profiler_destroy.restype = None
@@ -352,6 +356,35 @@ def decode_step(tables: Tables, H, beam_scores, topfreq, sp: StepParams, workspa
         _check(load_library().lsh_decode_step_timed(*args, tables._prof), "lsh_decode_step_timed")
     else:
         _check(load_library().lsh_decode_step(*args), "lsh_decode_step")
+
+
+def static_scratch_bytes() -> int:
+    return int(load_library().lsh_static_scratch_bytes())
+
+
+def decode_step_static(tables: Tables, H, beam_scores, topfreq, sp: StepParams, out_beam, out_word,
+                       out_score, stream=None):
+    """lsh_decode_step_static: the step in the library's built-in scratch buffer (no workspace)."""
+    import torch
+    for x, name, dt in ((H, "H", torch.float32), (beam_scores, "beam_scores", torch.float32),
+                        (out_beam, "out_beam", torch.int32), (out_word, "out_word", torch.int32),
+                        (out_score, "out_score", torch.float32)):
+        _require_cuda(x, name, (dt,))
+    R = sp.S * sp.B
+    if H.numel() != R * tables.d or beam_scores.numel() != R:
+        raise ValueError("H must be [S*B, d] and beam_scores [S*B]")
+    if min(out_beam.numel(), out_word.numel(), out_score.numel()) < R:
+        raise ValueError("outputs must hold S*B elements")
+    tf_ptr = 0
+    if topfreq is not None:
+        _require_cuda(topfreq, "topfreq", (torch.int32,))
+        if topfreq.numel() < sp.T:
+            raise ValueError("topfreq shorter than T")
+        tf_ptr = topfreq.data_ptr()
+    _check(load_library().lsh_decode_step_static(
+        tables.handle, H.data_ptr(), beam_scores.data_ptr(), tf_ptr, ctypes.byref(sp),
+        out_beam.data_ptr(), out_word.data_ptr(), out_score.data_ptr(), _stream_ptr(stream)),
+        "lsh_decode_step_static")
 
 
 def make_step_caller(tables: Tables, sp: StepParams, workspace, topfreq):

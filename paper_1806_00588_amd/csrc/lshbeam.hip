@@ -30,7 +30,33 @@
 
 using namespace lshbeam;
 
+// Working memory of lsh_decode_step_static, the variant of the decode step for callers that
+// cannot allocate: one array per GPU, part of the loaded code object, held until the process
+// ends.  In host code `scratch` only names the symbol; the memory of the current device's copy is
+// found once per device by scratch_of_device() and kernels are handed that address.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_addr[kMaxDevices];   // device address of `scratch` on each GPU, or null
+
+// Address of the current device's copy of `scratch` (the device must be current: each GPU holds
+// its own copy at its own address).
+hipError_t scratch_of_device(int dev, void** out) {
+    *out = nullptr;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void* p = g_scratch_addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_addr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return hipSuccess;
+}
 
 constexpr int kMaxV = 1 << 24;
 constexpr int kMaxB = 256;
@@ -83,6 +109,7 @@ struct lsh_tables {
     int hit_list_cap = 0;
     int wg_union_logits_lds = 0;
     int built_on_device = 0, build_attempts = 0;  // how the tables came about (inspection)
+    void* scratch_dev = nullptr;                  // this device's copy of the static scratch array
     int opt[kNumOpts];                            // launch-plan options, kAuto unless set
     int option(int which, int dflt) const { return opt[which] == kAuto ? dflt : opt[which]; }
 };
@@ -792,6 +819,7 @@ const char* lsh_status_string(lsh_status s) {
         case LSH_ERR_OOM: return "out of device memory";
         case LSH_ERR_HIP: return "HIP runtime error";
         case LSH_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case LSH_ERR_SCRATCH_TOO_SMALL: return "step too large for the built-in scratch buffer";
     }
     return "unknown status";
 }
@@ -841,6 +869,7 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     if (!t) return LSH_ERR_OOM;
     struct Guard { lsh_tables* t; ~Guard() { if (t) lsh_free_tables(t); } } guard{t};
     HIP_TRY(hipGetDevice(&t->device));
+    HIP_TRY(scratch_of_device(t->device, &t->scratch_dev));
     // launch-plan options: the library's own rules unless LSHBEAM_<NAME> is set in the environment
     // at this point (read once, here) or lsh_set_option changes them later
     for (int i = 0; i < kNumOpts; ++i) {
@@ -936,6 +965,20 @@ lsh_status lsh_decode_step_timed(const lsh_tables* t, const float* H_dev, const 
                                  lsh_profiler* prof) {
     return decode_step_impl(t, H_dev, beam_scores_dev, topfreq_dev, sp, workspace_dev, workspace_bytes,
                             out_beam_dev, out_word_dev, out_score_dev, hip_stream, prof);
+}
+
+size_t lsh_static_scratch_bytes(void) { return kScratchBytes; }
+
+lsh_status lsh_decode_step_static(const lsh_tables* t, const float* H_dev, const float* beam_scores_dev,
+                                  const int32_t* topfreq_dev, const lsh_step_params* sp,
+                                  int32_t* out_beam_dev, int32_t* out_word_dev, float* out_score_dev,
+                                  void* hip_stream) {
+    if (!step_params_ok(t, sp)) return LSH_ERR_INVALID_ARG;
+    if (!t->scratch_dev) return LSH_ERR_HIP;
+    if (carve(t, sp, nullptr).bytes > kScratchBytes) return LSH_ERR_SCRATCH_TOO_SMALL;
+    // (nothing in the workspace has to start from zero: every kernel writes what a later one reads)
+    return decode_step_impl(t, H_dev, beam_scores_dev, topfreq_dev, sp, t->scratch_dev, kScratchBytes,
+                            out_beam_dev, out_word_dev, out_score_dev, hip_stream, nullptr);
 }
 
 lsh_status lsh_set_option(lsh_tables* t, const char* name, int32_t value) {

@@ -1,0 +1,73 @@
+"""lsh_decode_step_static -- the decode step in the library's built-in scratch buffer, for callers
+that cannot allocate -- against lsh_decode_step with a caller workspace: same kernels, so every
+output must be identical bit for bit.  Two calls in a row share the buffer, the second on a
+smaller input (the buffer then still holds the first call's data beyond what the second uses)."""
+import numpy as np
+import pytest
+
+import workloads
+from gpu_harness import GpuCase, assert_topb_matches, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def _both(gc, H, bs, S, B, T, threshold=1, full_vocab=False):
+    import torch
+    from paper_1806_00588_amd import binding
+    sp = binding.step_params(S, B, T, threshold, full_vocab)
+    H_dev, bs_dev = to_dev(H), to_dev(bs)
+    out = []
+    for static in (True, False):
+        ob = torch.full((S, B), -7, dtype=torch.int32, device="cuda")
+        ow = torch.full((S, B), -7, dtype=torch.int32, device="cuda")
+        osc = torch.full((S, B), 123.0, dtype=torch.float32, device="cuda")
+        if static:
+            binding.decode_step_static(gc.tables, H_dev, bs_dev, gc.topfreq_dev, sp, ob, ow, osc)
+        else:
+            ws = torch.empty(gc.lsh.step_workspace_bytes(gc.tables, sp), dtype=torch.uint8, device="cuda")
+            gc.lsh.decode_step(gc.tables, H_dev, bs_dev, gc.topfreq_dev, sp, ws, ob, ow, osc)
+        torch.cuda.synchronize()
+        out.append((ob.cpu().numpy(), ow.cpu().numpy(), osc.cpu().numpy()))
+    return out
+
+
+def test_static_scratch_step_equals_the_workspace_step():
+    import torch
+    from paper_1806_00588_amd import binding
+    cfg = workloads.CONFIGS["paper"]
+    gc = GpuCase.from_config(cfg)
+    H = workloads.make_hidden(cfg, gc.E, seed=0, steps=3)
+    rng = np.random.default_rng(7)
+    assert binding.static_scratch_bytes() == 32 << 20
+    # the paper shape, then smaller inputs in the same buffer: fewer beams, a hit threshold, the
+    # full-vocabulary mode, several sentences -- and the paper shape once more
+    plan = [(1, 12, 1, False), (1, 5, 1, False), (1, 3, 2, False), (1, 2, 1, True), (3, 4, 1, False),
+            (1, 12, 1, False)]
+    for n, (S, B, t, full) in enumerate(plan):
+        Hs = H[n % 3][:S * B]
+        bs = rng.standard_normal(S * B).astype(np.float32)
+        (sb, sw, ss), (wb, ww, wsc) = _both(gc, Hs, bs, S, B, cfg.T, t, full)
+        assert np.array_equal(sb, wb) and np.array_equal(sw, ww) and np.array_equal(ss, wsc), (S, B, t, full)
+        for s in range(S):      # and both are the oracle's answer
+            ref = gc.oracle_sentence(Hs[s * B:(s + 1) * B], bs[s * B:(s + 1) * B], B, full_vocab=full, threshold=t)
+            assert_topb_matches(sb[s], sw[s], ss[s], ref, bs[s * B:(s + 1) * B])
+    # a step that needs more than the buffer is refused before anything is launched
+    S, B = 32, 10
+    sp = binding.step_params(S, B, cfg.T)
+    assert gc.lsh.step_workspace_bytes(gc.tables, sp) > binding.static_scratch_bytes()
+    ob = torch.full((S, B), 42, dtype=torch.int32, device="cuda")
+    ow = ob.clone()
+    osc = torch.full((S, B), 42.0, device="cuda")
+    with pytest.raises(gc.lsh.LshBeamError) as e:
+        binding.decode_step_static(gc.tables, torch.zeros(S * B, cfg.d, device="cuda"),
+                                   torch.zeros(S * B, device="cuda"), gc.topfreq_dev, sp, ob, ow, osc)
+    assert e.value.status == 7
+    torch.cuda.synchronize()
+    assert torch.all(ob == 42) and torch.all(ow == 42) and torch.all(osc == 42.0)
+    # the tiny shape on its own tables: another handle, the same buffer
+    cfg2 = workloads.CONFIGS["tiny"]
+    gc2 = GpuCase.from_config(cfg2)
+    H2 = workloads.make_hidden(cfg2, gc2.E, seed=0, steps=1)[0]
+    bs2 = np.zeros(cfg2.R, np.float32)
+    (sb, sw, ss), (wb, ww, wsc) = _both(gc2, H2, bs2, 1, cfg2.B, cfg2.T)
+    assert np.array_equal(sb, wb) and np.array_equal(sw, ww) and np.array_equal(ss, wsc)
