@@ -200,6 +200,11 @@ lsh_status lsh_debug_candidates(const lsh_tables* t, const void* workspace_dev,
                                 const lsh_step_params* sp, int32_t s, int32_t* cand_host,
                                 int32_t cap, int32_t* n_out);
 
+/* Candidate counts |V_LSH,s| of all S sentences from the last step on this workspace (V for a
+ * full-vocabulary step); counts_host is int32 [S]. */
+lsh_status lsh_debug_counts(const lsh_tables* t, const void* workspace_dev, const lsh_step_params* sp,
+                            int32_t* counts_host);
+
 /* Log-probabilities of sentence s from the last step on this workspace: lp_host is fp32
  * [B, cap] (row pitch cap), columns in candidate-list order; *n_out = candidate count. */
 lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
@@ -215,6 +220,8 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
  * (read once, inside lsh_build_tables); lsh_decode_step never reads the environment.  Not
  * synchronised with steps running on the handle from other threads: set options between steps.
  *   "fused"          1 / 0: candidate generation inside the contraction kernel, or separate kernels
+ *   "one_launch"     0: the fused kernel is followed by a selection kernel instead of running the
+ *                    selection in its last workgroup
  *   "fused_grid"     workgroups of the fused kernel (default 256)
  *   "logits_grid"    workgroups (or waves' worth of them) of the separate contraction kernels
  *   "logits_waves"   1 / 4 / 16: contraction driver (a wave per tile; k split over 4 or 16 waves)

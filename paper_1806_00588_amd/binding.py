@@ -21,12 +21,12 @@ EXPORTED_SYMBOLS = (
     "lsh_profiler_destroy", "lsh_profiler_read", "lsh_decode_step_timed", "lsh_kernel_name",
     "lsh_status_string", "lsh_step_is_fused", "lsh_debug_build_info", "lsh_beam_advance",
     "lsh_beam_backtrace", "lsh_set_option", "lsh_get_option", "lsh_decode_step_static",
-    "lsh_static_scratch_bytes",
+    "lsh_static_scratch_bytes", "lsh_debug_counts",
 )
 
 OPTION_AUTO = -1
 OPTION_NAMES = ("fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
-                "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows")
+                "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch")
 
 
 class LshBeamError(RuntimeError):
@@ -89,6 +89,7 @@ def load_library():
     lib.lsh_beam_backtrace.restype = i32
     lib.lsh_debug_build_info.restype = i32
     lib.lsh_debug_candidates.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32, i32p, i32, i32p]
+    lib.lsh_debug_counts.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32p]
     lib.lsh_debug_logprobs.argtypes = [vp, vp, ctypes.POINTER(StepParams), i32,
                                        ctypes.POINTER(ctypes.c_float), i32, i32p]
     lib.lsh_decode_step_timed.argtypes = lib.lsh_decode_step.argtypes + [vp]
@@ -255,6 +256,13 @@ class Tables:
                                                    ctypes.byref(sp), s, _i32p(out), self.V,
                                                    ctypes.byref(n)), "lsh_debug_candidates")
         return out[: n.value].copy()
+
+    def debug_counts(self, workspace, sp: StepParams) -> np.ndarray:
+        """Candidate counts of all sentences of the last step on this workspace."""
+        out = np.empty(sp.S, dtype=np.int32)
+        _check(load_library().lsh_debug_counts(self.handle, workspace.data_ptr(), ctypes.byref(sp),
+                                               _i32p(out)), "lsh_debug_counts")
+        return out
 
     def debug_logprobs(self, workspace, sp: StepParams, s: int, cap: Optional[int] = None):
         cap = self.V if cap is None else cap

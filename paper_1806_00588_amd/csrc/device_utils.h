@@ -110,6 +110,14 @@ __device__ __forceinline__ float row16_sum(float v) {
     return v;
 }
 
+__device__ __forceinline__ int row16_min_i32(int v) {
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xf, 0xf, true));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xf, 0xf, true));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x141, 0xf, 0xf, true));
+    v = min(v, __builtin_amdgcn_update_dpp(0, v, 0x140, 0xf, 0xf, true));
+    return v;
+}
+
 // Order-preserving map fp32 -> uint32 (larger float <=> larger integer; -0 is folded into +0 by
 // the caller adding 0.0f first).
 __device__ __forceinline__ uint32_t f32_sortable(float f) {
@@ -127,6 +135,21 @@ __device__ __forceinline__ float elem_f32(const float* p) { return *p; }
 __device__ __forceinline__ float elem_f32(const uint16_t* p) {
     return __uint_as_float((uint32_t)(*p) << 16);
 }
+
+// Stores that other workgroups of the SAME kernel will read (the one-launch plan's last workgroup
+// reads what the others computed): device-scope atomic stores, which go through to memory instead
+// of staying dirty in the L2 of the writer's XCD -- the eight XCDs' L2s are not coherent with each
+// other inside a kernel.  Publishing then needs no cache write-back: wait for the stores to
+// complete (publish_wait), barrier, ticket.  `AGENT` = false gives plain stores (the data is only
+// read by a later kernel).
+template <bool AGENT, typename T>
+__device__ __forceinline__ void store_shared_result(T* p, T v) {
+    static_assert(sizeof(T) == 4 || sizeof(T) == 8, "32- or 64-bit values");
+    if constexpr (AGENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+// All of this wave's stores have completed (been acknowledged by the memory they went through to).
+__device__ __forceinline__ void publish_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Workgroup inclusive scan; `wsum` is LDS with at least blockDim.x/64 + 1 words.  Returns the
 // inclusive prefix of v for this thread and the workgroup total in *total.  Ends with a barrier,

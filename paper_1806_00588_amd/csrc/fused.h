@@ -15,9 +15,19 @@
 // amortised and throughput matters, not latency).  With a hit threshold above 1, or with more
 // beams than one chunk of hashing holds, the hashing stays in a kernel of its own and
 // "rebuilding the bitmap" is the OR of the bitmaps that kernel left (k_union_logits).
+//
+// One launch per step: the log-softmax and the beam expansion run inside these kernels too.  The
+// workgroups that had tiles of sentence s make their stores visible device-wide and take a ticket
+// on a per-sentence counter; the one that draws the last ticket has everything it needs in
+// memory and runs the selection (select.h) for the sentence -- no kernel boundary, no idle
+// launch gap, no barrier across workgroups (nobody waits: a workgroup either finishes the
+// sentence or exits).  The last arriver also puts the counter back to zero, so a captured graph
+// can be replayed without clearing anything.  The tiles leave rich records (logits.h), from which
+// the selection usually finishes without reading logits or candidate ids back.
 #pragma once
 #include "candidates.h"
 #include "logits.h"
+#include "select.h"
 
 namespace lshbeam {
 
@@ -31,17 +41,33 @@ __host__ __device__ inline uint32_t pow2_at_least(uint32_t x) {
 
 // LDS words: candidate generation + prefix array (padded to a power of two, plus one) + the
 // cross-wave reduction buffer of the contraction.
+// (the selection of the one-launch plan reuses the same memory from its start: SelShared)
+constexpr size_t kSelSharedWords = (sizeof(SelShared) + 3) / 4;
 __host__ __device__ inline size_t fused_lds_words(int V, int P, int K, int stage_words) {
     const uint32_t nwords = (uint32_t)(((size_t)V + 31) / 32);
-    return candidates_lds_words(V, P, K, stage_words) + pow2_at_least(nwords) + 1 +
-           (size_t)kFusedWaves * 4 * kWave;
+    const size_t need = candidates_lds_words(V, P, K, stage_words) + pow2_at_least(nwords) + 1 +
+                        (size_t)kFusedWaves * 4 * kWave;
+    return need > kSelSharedWords ? need : kSelSharedWords;
 }
+
+// Outputs and inputs of the step's tail (log-softmax + beam expansion) for the one-launch plan.
+// (ONE_LAUNCH = false: the kernel stops after its tiles, a selection kernel follows, and only ids2
+// is used.)
+struct TailArgs {
+    unsigned int* tickets;       // [S] counters, zero between steps
+    const float* beam_scores;    // [S*B]
+    float* lse;                  // [S*B]
+    int32_t* ids2;               // [R, ppitch] word id of each record's second largest logit
+    int32_t* out_beam;           // [S, B]
+    int32_t* out_word;
+    float* out_score;
+};
 
 // What follows the bitmap in both fused kernels: exclusive prefix of the bitmap words'
 // popcounts, then for each of this workgroup's tiles the 16 candidates by rank and the split-k
 // tile.  `wpref` has pow2_at_least(nwords) + 1 words, `wsum` >= 17, `red` is the cross-wave
 // reduction buffer; h_lds (or null) are the sentence's hidden rows staged in LDS as [B][d].
-template <typename ET, bool ALIGNED>
+template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
 __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* wsum, uint32_t* wpref,
                                                   float (*red)[4][kWave], const float* h_lds,
                                                   const ET* __restrict__ E, int64_t ld, int d,
@@ -49,7 +75,8 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
                                                   int g, int G, int32_t* __restrict__ cand,
                                                   int32_t* __restrict__ count,
                                                   float* __restrict__ logits, int64_t cpitch,
-                                                  float2* __restrict__ partials, int64_t ppitch) {
+                                                  float2* __restrict__ partials, int64_t ppitch,
+                                                  const TailArgs& tail, uint32_t* smem) {
     const int tid = threadIdx.x, ln = lane_id();
     const int nwords = (V + 31) >> 5;
     const uint32_t npow = pow2_at_least((uint32_t)nwords);
@@ -69,7 +96,7 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
     LSH_TRACE(0, 6);
     LSH_TRACE_WG(4);
     const int C = (int)total;
-    if (g == 0 && tid == 0) count[s] = C;
+    if (g == 0 && tid == 0) store_shared_result<ONE_LAUNCH>(&count[s], (int32_t)C);
 
     const int ntiles = (C + kTileN - 1) / kTileN;
     const int col = ln & 15;
@@ -91,20 +118,50 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
             else wbits = low;
         }
         const int32_t id = (int32_t)((lo << 5) + pos);
-        if (tid < kTileN && nt * kTileN + col < C) cand[(size_t)s * V + nt * kTileN + col] = id;
+        if (tid < kTileN && nt * kTileN + col < C)
+            store_shared_result<ONE_LAUNCH>(&cand[(size_t)s * V + nt * kTileN + col], id);
         LSH_TRACE(1, 2);
-        logits_tile_all_rows<ET, kFusedWaves, 64 / kFusedWaves, ALIGNED>(E, ld, d, H, B, s, nt, C, (int64_t)id, logits,
-                                                          cpitch, partials, ppitch, red, h_lds);
+        logits_tile_all_rows<ET, kFusedWaves, 64 / kFusedWaves, ALIGNED, 0, true, ONE_LAUNCH>(
+            E, ld, d, H, B, s, nt, C, (int64_t)id, logits, cpitch, partials, ppitch, red, h_lds, 0, 0, -1,
+            tail.ids2);
     }
+    if constexpr (!ONE_LAUNCH) return;
+
+    // ---- the step's tail, by the last workgroup of the sentence to get here ----
+    SelShared& sh = *reinterpret_cast<SelShared*>(smem);   // (bitmap, prefix, stage: all done with)
+    const int participants = min(G, ntiles);               // workgroups of this sentence with tiles
+    if (ntiles > 0) {
+        if (g >= ntiles) return;
+        // what the finishing workgroup reads of this one (logits, records, ids) went through to
+        // memory (store_shared_result): once every wave's stores have completed, the ticket
+        LSH_TRACE_LATEST(1, 12);
+        publish_wait();
+        __syncthreads();
+        LSH_TRACE_LATEST(1, 13);
+        if (tid == 0) {
+            const unsigned int prev = atomicAdd(tail.tickets + s, 1u);
+            const bool last = prev + 1u == (unsigned int)participants;
+            if (last) atomicExch(tail.tickets + s, 0u);     // ready for the next step / replay
+            sh.misc[7] = last ? 1u : 0u;
+        }
+        __syncthreads();
+        if (sh.misc[7] == 0u) return;
+        LSH_TRACE_ANY(1, 14);
+    } else if (g != 0) {
+        return;                // an empty list: workgroup 0 of the sentence pads the outputs
+    }
+    select_sentence<TileRecord, 1, true>(sh, s, logits, cpitch, reinterpret_cast<const TileRecord*>(partials),
+                                   tail.ids2, ppitch, cand, nullptr, C, V, B, tail.beam_scores, tail.lse,
+                                   tail.out_beam, tail.out_word, tail.out_score);
 }
 
 // grid = S * G workgroups: workgroup b works for sentence b % S and takes that sentence's tiles
 // (b / S), (b / S) + G, ...
-template <typename ET, bool ALIGNED>
+template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
 __global__ void __launch_bounds__(kCandThreads)
 k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* __restrict__ cand,
               int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
-              float2* __restrict__ partials, int64_t ppitch) {
+              float2* __restrict__ partials, int64_t ppitch, TailArgs tail) {
     extern __shared__ uint32_t smem[];
     const int s = blockIdx.x % S;
     const int g = blockIdx.x / S, G = gridDim.x / S;
@@ -121,8 +178,8 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
     const float* h_lds = nullptr;
     if (candidates_rows_per_chunk(B, a.d, a.W, a.stage_words) >= B && (a.d & 3) == 0)
         h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
-    tiles_from_bitmap<ET, ALIGNED>(bm, wsum, wpref, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
-                                   count, logits, cpitch, partials, ppitch);
+    tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, wpref, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
+                                   count, logits, cpitch, partials, ppitch, tail, smem);
     LSH_TRACE_WG(6);
 }
 
@@ -131,17 +188,19 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
 // threshold is above 1, one per part of the sentence by k_part_bitmaps when it has many beams)
 // and the top-frequent words (Eq. 3).
 __host__ __device__ inline size_t union_logits_lds_words(int V) {
-    return (size_t)bitmap_words_padded(V) + 64 + ((pow2_at_least((uint32_t)(((size_t)V + 31) / 32)) + 1 + 3) & ~3u) +
-           (size_t)kFusedWaves * 4 * kWave;
+    const size_t need = (size_t)bitmap_words_padded(V) + 64 +
+                        ((pow2_at_least((uint32_t)(((size_t)V + 31) / 32)) + 1 + 3) & ~3u) +
+                        (size_t)kFusedWaves * 4 * kWave;
+    return need > kSelSharedWords ? need : kSelSharedWords;
 }
 
-template <typename ET, bool ALIGNED>
+template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
 __global__ void __launch_bounds__(kCandThreads)
 k_union_logits(const uint32_t* __restrict__ part_bitmaps, int nparts, const int32_t* __restrict__ topfreq,
                int T, const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S,
                int B, int V, int32_t* __restrict__ cand, int32_t* __restrict__ count,
                float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
-               int64_t ppitch) {
+               int64_t ppitch, TailArgs tail) {
     extern __shared__ uint32_t smem[];
     const int tid = threadIdx.x;
     const int s = blockIdx.x % S;
@@ -158,8 +217,8 @@ k_union_logits(const uint32_t* __restrict__ part_bitmaps, int nparts, const int3
     __syncthreads();
     mark_id_list(bm, V, topfreq, T, tf_first);
     __syncthreads();
-    tiles_from_bitmap<ET, ALIGNED>(bm, wsum, wpref, red, nullptr, E, ld, d, H, B, V, s, g, G, cand,
-                                   count, logits, cpitch, partials, ppitch);
+    tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, wpref, red, nullptr, E, ld, d, H, B, V, s, g, G, cand,
+                                   count, logits, cpitch, partials, ppitch, tail, smem);
 }
 
 }  // namespace lshbeam

@@ -3,8 +3,11 @@
 // of E are gathered straight into the matrix-core operands).
 //
 // Besides the logits every tile leaves, per hidden row, the pair (max, sum exp(logit - max)) over
-// its 16 candidates: the selection kernel combines these into the row's log-sum-exp without
-// touching the exponential of every logit again.
+// its 16 candidates: the selection combines these into the row's log-sum-exp without touching the
+// exponential of every logit again.  The fused kernels (fused.h) leave a richer record per row and
+// tile (TileRecord): also the word id of the maximum, the second largest logit of the tile and
+// its word id -- enough for the selection to finish, in the common case, without reading a
+// single logit or candidate id back.
 //
 // Work unit ("tile"): one sentence s, one group of 16 hidden rows (M-tile) and 16 candidates.
 // A workgroup of WAVES waves splits the hidden dimension between its waves; every wave issues
@@ -55,6 +58,12 @@ template <> struct ElemTraits<uint16_t> {
     }
 };
 
+// Per (hidden row, tile) record of the fused kernels: x = largest logit of the tile's candidates,
+// y = sum exp(logit - x), z = second largest logit (-inf if the tile has one candidate), w = word id
+// of the largest (the lowest column among equals; as bits).  The id of the second largest goes to
+// a parallel int32 array (-1 if none).  The plain kernels store only (x, y) as a float2.
+typedef float4 TileRecord;
+
 constexpr int kTileN = 16;  // candidates per tile
 constexpr int kTileM = 16;  // hidden rows per tile
 constexpr int kMaxSentencesLogits = 4096;
@@ -69,14 +78,15 @@ constexpr int kMaxSentencesLogits = 4096;
 //
 // ALIGNED: E rows and H rows can be read with 16-byte vector loads (pointers 16-byte aligned,
 // d and the pitches multiples of the vector width).  Otherwise elements are read one by one.
-template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int MTB = 1>
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int MTB = 1, bool RICH = false, bool SHARE = false>
 __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld, int d,
                                             const float* __restrict__ H, int B, int s, int mt,
                                             int nt, int C, int64_t j, float* __restrict__ logits,
                                             int64_t cpitch, float2* __restrict__ partials,
                                             int64_t ppitch, float (*red)[4][kWave],
                                             const float* h_lds = nullptr, int h_pitch = 0,
-                                            int row_lo = 0, int row_hi = -1) {
+                                            int row_lo = 0, int row_hi = -1,
+                                            int32_t* __restrict__ ids2 = nullptr) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
     if (h_pitch == 0) h_pitch = d;
@@ -158,13 +168,34 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
             for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
             const int row = row_lo + (mt + m) * kTileM + i, c = n0 + jc;
             const bool valid = row < row_hi && c < C;
-            if (valid) logits[((size_t)s * B + row) * cpitch + c] = sum;
+            // (SHARE: other workgroups of this kernel read the results; see store_shared_result)
+            if (valid) store_shared_result<SHARE>(&logits[((size_t)s * B + row) * cpitch + c], sum);
             // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
             // tile's 16 candidates; the 16 lanes that share a row are one DPP row
             const float mx = row16_max(valid ? sum : -INFINITY);
             const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
-            if (jc == 0 && row < row_hi)
-                partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+            if constexpr (RICH) {
+                // the lowest column that holds the maximum; the largest of the others and its
+                // lowest column (thread tid's own candidate is the one of column jc = lane % 16)
+                const int c1 = row16_min_i32((valid && sum == mx) ? jc : 16);
+                const float mx2 = row16_max((valid && jc != c1) ? sum : -INFINITY);
+                const int c2 = row16_min_i32((valid && jc != c1 && sum == mx2) ? jc : 16);
+                if (row < row_hi) {
+                    const size_t at = ((size_t)s * B + row) * ppitch + nt;
+                    if (jc == (c1 < 16 ? c1 : 0)) {   // (no column equals the maximum: NaN logits)
+                        unsigned long long* rec =
+                            reinterpret_cast<unsigned long long*>(reinterpret_cast<TileRecord*>(partials) + at);
+                        const uint32_t idb = (uint32_t)(c1 < 16 ? (int)j : -1);
+                        store_shared_result<SHARE>(rec, ((unsigned long long)__float_as_uint(se) << 32) | __float_as_uint(mx));
+                        store_shared_result<SHARE>(rec + 1, ((unsigned long long)idb << 32) | __float_as_uint(mx2));
+                    }
+                    if (jc == (c2 < 16 ? c2 : 0))
+                        store_shared_result<SHARE>(&ids2[at], c2 < 16 ? (int32_t)j : (int32_t)-1);
+                }
+            } else {
+                if (jc == 0 && row < row_hi)
+                    partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+            }
         }
         __syncthreads();
     }
@@ -173,7 +204,7 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
 
 // All row groups of one tile of candidates, the candidate rows being read once for up to four
 // groups (64 beams) at a time.
-template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int FIXED_MT = 0>
+template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int FIXED_MT = 0, bool RICH = false, bool SHARE = false>
 __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, int64_t ld, int d,
                                                      const float* __restrict__ H, int B, int s,
                                                      int nt, int C, int64_t j,
@@ -181,7 +212,8 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
                                                      float2* __restrict__ partials, int64_t ppitch,
                                                      float (*red)[4][kWave],
                                                      const float* h_lds = nullptr, int h_pitch = 0,
-                                                     int row_lo = 0, int row_hi = -1) {
+                                                     int row_lo = 0, int row_hi = -1,
+                                                     int32_t* __restrict__ ids2 = nullptr) {
     // loads in flight per row group shrink as the groups grow: the operands of all groups have
     // to fit the register budget of a 1024-thread workgroup
     // (measured: keeping the full unroll in 256-thread workgroups, where registers would allow
@@ -192,19 +224,19 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
     // instantiated, so its registers do not count against the others)
     const int MT = FIXED_MT ? FIXED_MT : ((row_hi < 0 ? B : row_hi - row_lo) + kTileM - 1) / kTileM;
     if (MT == 1) {
-        logits_tile<ET, WAVES, UNROLL, ALIGNED, 1>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
+        logits_tile<ET, WAVES, UNROLL, ALIGNED, 1, RICH, SHARE>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
+                                                         partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
     } else if (MT == 2) {
-        logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                               partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
+        logits_tile<ET, WAVES, U2, ALIGNED, 2, RICH, SHARE>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
+                                                     partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
     } else if (ElemTraits<ET>::VEC > 4) {  // bf16: twice the registers per load, two groups at most
         for (int mt = 0; mt < MT; mt += 2)
-            logits_tile<ET, WAVES, U2, ALIGNED, 2>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
+            logits_tile<ET, WAVES, U2, ALIGNED, 2, RICH, SHARE>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
+                                                         partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
     } else {
         for (int mt = 0; mt < MT; mt += 4)
-            logits_tile<ET, WAVES, U4, ALIGNED, 4>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                   partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi);
+            logits_tile<ET, WAVES, U4, ALIGNED, 4, RICH, SHARE>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
+                                                         partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
     }
 }
 

@@ -13,6 +13,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <cctype>
 #include <new>
 #include <string>
@@ -62,6 +63,8 @@ constexpr int kMaxV = 1 << 24;
 constexpr int kMaxB = 256;
 constexpr size_t kAlign = 256;
 constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
+constexpr int kTicketSlots = 256;   // workspaces per handle that can take the one-launch plan
+constexpr int kTicketBlock = 64;    // counters per workspace = sentences of a fused step at most
 
 inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -75,12 +78,12 @@ struct HostBand {
 // Launch-plan options of a handle (lsh_set_option); kAuto = the library's own rule.
 enum Opt {
     kOptFused, kOptFusedGrid, kOptLogitsGrid, kOptLogitsWaves, kOptLogitsHlds, kOptLogitsEstage,
-    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kNumOpts
+    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kOptOneLaunch, kNumOpts
 };
 constexpr int kAuto = -1;
 const char* const kOptNames[kNumOpts] = {
     "fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
-    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows"};
+    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch"};
 
 }  // namespace
 
@@ -110,6 +113,25 @@ struct lsh_tables {
     int wg_union_logits_lds = 0;
     int built_on_device = 0, build_attempts = 0;  // how the tables came about (inspection)
     void* scratch_dev = nullptr;                  // this device's copy of the static scratch array
+    // Ticket counters of the one-launch plan: kTicketSlots blocks of kTicketBlock counters in
+    // device memory, all zero between steps (the kernel that uses a block leaves it zero).  A
+    // block belongs to one workspace address for the life of the handle, so steps that run at the
+    // same time -- which must use different workspaces -- never share counters.  The table is a
+    // cache behind the const handle: guarded by its own mutex, it changes no result.
+    unsigned int* tickets_dev = nullptr;
+    mutable std::mutex ticket_mu;
+    mutable const void* ticket_owner[kTicketSlots] = {};
+    mutable int ticket_used = 0;
+    // The counters for the step that works in `workspace`, or null when all blocks are taken (the
+    // step then ends with a selection kernel of its own).
+    unsigned int* tickets_for(const void* workspace) const {
+        std::lock_guard<std::mutex> lock(ticket_mu);
+        for (int i = 0; i < ticket_used; ++i)
+            if (ticket_owner[i] == workspace) return tickets_dev + (size_t)i * kTicketBlock;
+        if (!tickets_dev || ticket_used == kTicketSlots) return nullptr;
+        ticket_owner[ticket_used] = workspace;
+        return tickets_dev + (size_t)(ticket_used++) * kTicketBlock;
+    }
     int opt[kNumOpts];                            // launch-plan options, kAuto unless set
     int option(int which, int dflt) const { return opt[which] == kAuto ? dflt : opt[which]; }
 };
@@ -213,7 +235,9 @@ struct Workspace {
     int32_t* cand;       // [S, V]
     int32_t* count;      // [S]
     float* logits;       // [R, cpitch]
-    float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max))
+    float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max)) as float2
+                         //   from the plain kernels, a 16-byte TileRecord from the fused ones
+    int32_t* ids2;       // [R, ppitch]  fused kernels: word id of each record's second largest
     uint32_t* row_bitmaps;  // [R, ceil(V/32)]  per-row (t > 1) or per-part (many beams) bitmaps
     float* lse;          // [R]
     int64_t ppitch;
@@ -231,7 +255,8 @@ Workspace carve(const lsh_tables* t, const lsh_step_params* sp, void* base) {
     w.count = (int32_t*)take(S * sizeof(int32_t));
     w.ppitch = w.cpitch / kTileN;
     w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
-    w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(float2));
+    w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(TileRecord));
+    w.ids2 = (int32_t*)take(R * (size_t)w.ppitch * sizeof(int32_t));
     w.lse = (float*)take(R * sizeof(float));
     w.row_bitmaps = (uint32_t*)take(sp->full_vocab ? 0 : R * ((V + 31) / 32) * sizeof(uint32_t));
     w.bytes = off;
@@ -756,7 +781,14 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
                ca, pr, nparts, w.row_bitmaps);
         parts = w.row_bitmaps;
     }
+    bool selected = false;   // the step's tail already ran inside the fused kernel
     if (fused) {
+        // One launch per step: the last workgroup of each sentence also runs the selection
+        // (option one_launch = 0: a selection kernel follows instead; also when no ticket block
+        // is left for this workspace or the step has more sentences than a block has counters).
+        TailArgs tail{nullptr, beam_scores_dev, w.lse, w.ids2, out_beam_dev, out_word_dev, out_score_dev};
+        if (t->option(kOptOneLaunch, 0) && sp->S <= kTicketBlock) tail.tickets = t->tickets_for(workspace_dev);
+        selected = tail.tickets != nullptr;
         const int per_sentence = std::max(1, t->option(kOptFusedGrid, 256) / sp->S);
         const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
         const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
@@ -764,20 +796,26 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
         const bool al = f32 ? (aligned16 && t->ld % 4 == 0) : (aligned16 && t->ld % 8 == 0 && t->d % 8 == 0);
         if (parts) {
             const size_t lds = (size_t)t->wg_union_logits_lds;
-#define LSH_UNION_LOGITS(ET, AL)                                                                  \
-    launch(cx, 1, k_union_logits<ET, AL>, grid, block, lds, parts, nparts, topfreq_dev, sp->T, \
+#define LSH_UNION_LOGITS(ET, AL, OL)                                                              \
+    launch(cx, 1, k_union_logits<ET, AL, OL>, grid, block, lds, parts, nparts, topfreq_dev, sp->T, \
            (const ET*)t->E, t->ld, t->d, H_dev, sp->S, sp->B, t->V, w.cand, w.count, w.logits,    \
-           w.cpitch, w.partials, w.ppitch)
-            if (f32) { if (al) LSH_UNION_LOGITS(float, true); else LSH_UNION_LOGITS(float, false); }
-            else { if (al) LSH_UNION_LOGITS(uint16_t, true); else LSH_UNION_LOGITS(uint16_t, false); }
+           w.cpitch, w.partials, w.ppitch, tail)
+#define LSH_UNION_LOGITS2(ET, AL) \
+    do { if (selected) LSH_UNION_LOGITS(ET, AL, true); else LSH_UNION_LOGITS(ET, AL, false); } while (0)
+            if (f32) { if (al) LSH_UNION_LOGITS2(float, true); else LSH_UNION_LOGITS2(float, false); }
+            else { if (al) LSH_UNION_LOGITS2(uint16_t, true); else LSH_UNION_LOGITS2(uint16_t, false); }
+#undef LSH_UNION_LOGITS2
 #undef LSH_UNION_LOGITS
         } else {
             const size_t lds = fused_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t);
-#define LSH_CAND_LOGITS(ET, AL)                                                                   \
-    launch(cx, 1, k_cand_logits<ET, AL>, grid, block, lds, ca, (const ET*)t->E, t->ld, sp->S,  \
-           w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch)
-            if (f32) { if (al) LSH_CAND_LOGITS(float, true); else LSH_CAND_LOGITS(float, false); }
-            else { if (al) LSH_CAND_LOGITS(uint16_t, true); else LSH_CAND_LOGITS(uint16_t, false); }
+#define LSH_CAND_LOGITS(ET, AL, OL)                                                               \
+    launch(cx, 1, k_cand_logits<ET, AL, OL>, grid, block, lds, ca, (const ET*)t->E, t->ld, sp->S,  \
+           w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch, tail)
+#define LSH_CAND_LOGITS2(ET, AL) \
+    do { if (selected) LSH_CAND_LOGITS(ET, AL, true); else LSH_CAND_LOGITS(ET, AL, false); } while (0)
+            if (f32) { if (al) LSH_CAND_LOGITS2(float, true); else LSH_CAND_LOGITS2(float, false); }
+            else { if (al) LSH_CAND_LOGITS2(uint16_t, true); else LSH_CAND_LOGITS2(uint16_t, false); }
+#undef LSH_CAND_LOGITS2
 #undef LSH_CAND_LOGITS
         }
         cand = w.cand;
@@ -799,9 +837,16 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
         if (t->dtype == LSH_F32) launch_logits<float>(cx, H_dev, sp, cand, count, w);
         else launch_logits<uint16_t>(cx, H_dev, sp, cand, count, w);
     }
-    launch(cx, 2, k_select, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits, w.cpitch,
-           (const float2*)w.partials, w.ppitch, cand, count, t->V, sp->B, beam_scores_dev, w.lse,
-           out_beam_dev, out_word_dev, out_score_dev);
+    if (!selected) {
+        if (fused)   // the fused kernels leave rich tile records
+            launch(cx, 2, k_select<TileRecord>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits,
+                   w.cpitch, (const TileRecord*)w.partials, (const int32_t*)w.ids2, w.ppitch, cand, count,
+                   t->V, sp->B, beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev);
+        else
+            launch(cx, 2, k_select<float2>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits,
+                   w.cpitch, (const float2*)w.partials, (const int32_t*)nullptr, w.ppitch, cand, count,
+                   t->V, sp->B, beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev);
+    }
     HIP_TRY(hipGetLastError());
     return LSH_OK;
 }
@@ -847,6 +892,7 @@ void lsh_free_tables(lsh_tables* t) {
     (void)hipFree(t->slots_dev);
     (void)hipFree(t->cuts_dev);
     (void)hipFree(t->bands_dev);
+    (void)hipFree(t->tickets_dev);
     delete t;
 }
 
@@ -870,6 +916,9 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     struct Guard { lsh_tables* t; ~Guard() { if (t) lsh_free_tables(t); } } guard{t};
     HIP_TRY(hipGetDevice(&t->device));
     HIP_TRY(scratch_of_device(t->device, &t->scratch_dev));
+    HIP_TRY(hipMalloc((void**)&t->tickets_dev, (size_t)kTicketSlots * kTicketBlock * sizeof(unsigned int)));
+    HIP_TRY(hipMemsetAsync(t->tickets_dev, 0, (size_t)kTicketSlots * kTicketBlock * sizeof(unsigned int),
+                           (hipStream_t)hip_stream));
     // launch-plan options: the library's own rules unless LSHBEAM_<NAME> is set in the environment
     // at this point (read once, here) or lsh_set_option changes them later
     for (int i = 0; i < kNumOpts; ++i) {
@@ -928,14 +977,16 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
     HIP_TRY(allow_whole_lds<k_hit_rows>());
     HIP_TRY(allow_whole_lds<k_union_compact>());
     HIP_TRY(allow_whole_lds<k_part_bitmaps>());
-    HIP_TRY((allow_whole_lds<k_union_logits<float, true>>()));
-    HIP_TRY((allow_whole_lds<k_union_logits<float, false>>()));
-    HIP_TRY((allow_whole_lds<k_union_logits<uint16_t, true>>()));
-    HIP_TRY((allow_whole_lds<k_union_logits<uint16_t, false>>()));
-    HIP_TRY((allow_whole_lds<k_cand_logits<float, true>>()));
-    HIP_TRY((allow_whole_lds<k_cand_logits<float, false>>()));
-    HIP_TRY((allow_whole_lds<k_cand_logits<uint16_t, true>>()));
-    HIP_TRY((allow_whole_lds<k_cand_logits<uint16_t, false>>()));
+#define LSH_ALLOW_FUSED(ET, AL)                                          \
+    HIP_TRY((allow_whole_lds<k_union_logits<ET, AL, false>>()));         \
+    HIP_TRY((allow_whole_lds<k_union_logits<ET, AL, true>>()));          \
+    HIP_TRY((allow_whole_lds<k_cand_logits<ET, AL, false>>()));          \
+    HIP_TRY((allow_whole_lds<k_cand_logits<ET, AL, true>>()))
+    LSH_ALLOW_FUSED(float, true);
+    LSH_ALLOW_FUSED(float, false);
+    LSH_ALLOW_FUSED(uint16_t, true);
+    LSH_ALLOW_FUSED(uint16_t, false);
+#undef LSH_ALLOW_FUSED
     HIP_TRY(allow_logits_lds<float>());
     HIP_TRY(allow_logits_lds<uint16_t>());
     HIP_TRY(allow_whole_lds<k_logits_estage<3>>());
@@ -1088,6 +1139,19 @@ lsh_status lsh_debug_candidates(const lsh_tables* t, const void* workspace_dev,
     if (ncopy)
         HIP_TRY(hipMemcpy(cand_host, w.cand + (size_t)s * t->V, ncopy * sizeof(int32_t),
                           hipMemcpyDeviceToHost));
+    return LSH_OK;
+}
+
+lsh_status lsh_debug_counts(const lsh_tables* t, const void* workspace_dev, const lsh_step_params* sp,
+                            int32_t* counts_host) {
+    if (!t || !workspace_dev || !counts_host || !step_params_ok(t, sp)) return LSH_ERR_INVALID_ARG;
+    if (sp->full_vocab) {
+        for (int s = 0; s < sp->S; ++s) counts_host[s] = t->V;
+        return LSH_OK;
+    }
+    const Workspace w = carve(t, sp, const_cast<void*>(workspace_dev));
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(counts_host, w.count, (size_t)sp->S * sizeof(int32_t), hipMemcpyDeviceToHost));
     return LSH_OK;
 }
 

@@ -242,57 +242,127 @@ __device__ __noinline__ void block_radix_select(ScoreSrc src, int k, SelShared* 
     __syncthreads();
 }
 
-// grid = S workgroups (one per sentence), kSelThreads threads.
-__global__ void __launch_bounds__(kSelThreads)
-k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restrict__ partials,
-         int64_t ppitch, const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-         int B, const float* __restrict__ beam_scores, float* __restrict__ lse_out /*[R]*/,
-         int32_t* __restrict__ out_beam, int32_t* __restrict__ out_word,
-         float* __restrict__ out_score) {
-    __shared__ SelShared sh;
+// What the logits kernels leave per (hidden row, tile): float2 (max, sum exp) from the plain
+// kernels, TileRecord = float4 (max, sum exp, second largest, id of the max) + a parallel array of
+// the second's id from the fused kernels.
+template <typename REC> struct RecTraits;
+template <> struct RecTraits<float2> {
+    static constexpr bool RICH = false;
+    __device__ static __forceinline__ float2 empty() { return make_float2(-INFINITY, 0.f); }
+};
+template <> struct RecTraits<float4> {
+    static constexpr bool RICH = true;
+    __device__ static __forceinline__ float4 empty() {
+        return make_float4(-INFINITY, 0.f, -INFINITY, __int_as_float(-1));
+    }
+};
+
+// Log-softmax and beam expansion of sentence s by one workgroup of kSelThreads threads, once the
+// sentence's logits and per-tile records are in memory (written by an earlier kernel, or by other
+// workgroups of this kernel whose stores have been made visible to this one).  C_known >= 0 is
+// the candidate count; otherwise it is read from count[s] (or is V when count is null) after the
+// first records have been requested.  KEEP = batches of tile maxima a wave keeps in registers
+// between the passes.
+//
+// With rich records (REC = float4) there is a short cut.  Every score >= tau that is the largest
+// or second largest of its (row, tile) is listed straight from the records, with its word id --
+// no logit and no candidate id is read back.  The B best of that list are the answer unless one
+// of them is a SECOND largest: only then can its tile hide a third value that also belongs, and
+// the general path below (open every tile whose maximum reaches tau) decides.  Proof: a hidden
+// value h of (row, tile) has a smaller key than the tile's second largest z (lower score, or equal
+// score and higher column); if z is not among the B best -- unlisted because z < tau <= the B-th
+// best score, or listed and outranked by B keys -- neither is h.
+// Loads of tile records / second ids.  SAME_KERNEL: the data was written by other workgroups of
+// the running kernel (device-scope stores, store_shared_result), so it is read with device-scope
+// loads, which do not hit in this XCD's caches -- cheaper than invalidating them (1.6 us measured
+// for the fence against nothing for the loads, which miss anyway).
+template <bool SAME_KERNEL>
+__device__ __forceinline__ float2 load_record(const float2* p) { return *p; }
+template <bool SAME_KERNEL>
+__device__ __forceinline__ float4 load_record(const float4* p) {
+    if constexpr (SAME_KERNEL) {
+        const unsigned long long* q = reinterpret_cast<const unsigned long long*>(p);
+        const unsigned long long a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return make_float4(__uint_as_float((uint32_t)a), __uint_as_float((uint32_t)(a >> 32)),
+                           __uint_as_float((uint32_t)b), __uint_as_float((uint32_t)(b >> 32)));
+    } else {
+        return *p;
+    }
+}
+template <bool SAME_KERNEL>
+__device__ __forceinline__ int32_t load_id2(const int32_t* p) {
+    if constexpr (SAME_KERNEL) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
+}
+
+template <typename REC, int KEEP, bool SAME_KERNEL = false>
+__device__ __forceinline__ void select_sentence(SelShared& sh, int s, const float* logits, int64_t cpitch,
+                                                const REC* partials, const int32_t* ids2, int64_t ppitch,
+                                                const int32_t* cand, const int32_t* count, int C_known,
+                                                int V, int B, const float* beam_scores, float* lse_out,
+                                                int32_t* out_beam, int32_t* out_word, float* out_score) {
+    constexpr bool RICH = RecTraits<REC>::RICH;
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
-    const int s = blockIdx.x;
-    LSH_TRACE(2, 0);
-    // The first batch of partials of this wave's first row is requested before the candidate
+    LSH_TRACE_ANY(2, 0);
+    // The first batch of records of this wave's first row is requested before the candidate
     // count is known (one memory round trip less): indices are clamped to the row's pitch, which
     // is allocated, and what lies beyond the last tile is masked after the load like any padding.
-    float2 first_batch[kSelBatch] = {};
-    if (wv < B) {
-        const float2* pr = partials + ((size_t)s * B + wv) * ppitch;
+    REC first_batch[kSelBatch];
+    int32_t first_ids2[kSelBatch];
 #pragma unroll
-        for (int q = 0; q < kSelBatch; ++q)
-            first_batch[q] = pr[min((int64_t)(ln + q * kWave), ppitch - 1)];
+    for (int q = 0; q < kSelBatch; ++q) { first_batch[q] = RecTraits<REC>::empty(); first_ids2[q] = -1; }
+    if (wv < B) {
+        const size_t r0 = ((size_t)s * B + wv) * ppitch;
+#pragma unroll
+        for (int q = 0; q < kSelBatch; ++q) {
+            const int64_t at = min((int64_t)(ln + q * kWave), ppitch - 1);
+            first_batch[q] = load_record<SAME_KERNEL>(partials + r0 + at);
+            if constexpr (RICH && KEEP > 0) first_ids2[q] = load_id2<SAME_KERNEL>(ids2 + r0 + at);
+        }
     }
-    const int C = count ? count[s] : V;
+    const int C = C_known >= 0 ? C_known : (count ? count[s] : V);
     const int ntiles = (C + 15) >> 4;
     const float* lg = logits + (size_t)s * B * cpitch;
-    if (tid == 0) { sh.misc[4] = 0; sh.misc[5] = 0; }
+    if (tid == 0) { sh.misc[4] = 0; sh.misc[5] = 0; sh.misc[6] = 0; }
 
-    // ---- per row: log-sum-exp from the tile partials, and the lane's best tile-maximum score.
+    // ---- per row: log-sum-exp from the tile records, and the lane's best tile-maximum score.
     //      Wave w takes rows w, w + 16, ...; a row is visited in batches of 512 tiles.  The
-    //      partials were written by other XCDs, so every load is a trip to memory: the next
+    //      records were written by other XCDs, so every load is a trip to memory: the next
     //      batch (of this row or of the wave's next row) is requested before the current one is
     //      reduced, and loads are never branched around (indices are clamped, padding is masked
     //      after the load). ----
     uint32_t lmax = 0;
-    // The tile maxima of the wave's first kSelKeep batches stay in registers for the second pass.
-    float keep[kSelKeep][kSelBatch];
+    // The tile maxima of the wave's first KEEP batches stay in registers for the second pass
+    // (rich records: also the second largest and both ids).
+    constexpr int KR = KEEP > 0 ? KEEP : 1;
+    float keep[KR][kSelBatch];
+    float keep_z[RICH ? KR : 1][kSelBatch];
+    int32_t keep_id1[RICH ? KR : 1][kSelBatch], keep_id2[RICH ? KR : 1][kSelBatch];
     constexpr int kBatchTiles = kWave * kSelBatch;
     const int nb = (ntiles + kBatchTiles - 1) / kBatchTiles;                     // batches per row
     const int nit = (wv < B ? (B - wv + kSelWaves - 1) / kSelWaves : 0) * nb;    // of this wave
     // lanes x kSelBatch slots of a batch that hold tiles at all (wave-uniform; the rest is
-    // skipped outright: this kernel runs 16 waves on one CU and is bound by instruction issue)
+    // skipped outright: 16 waves on one CU are bound by instruction issue)
     auto slots_of = [&](int bt) { return min(kSelBatch, (ntiles - bt * kBatchTiles + kWave - 1) / kWave); };
-    auto load_batch = [&](int it, float2 (&p)[kSelBatch]) {
+    auto load_batch = [&](int it, REC (&p)[kSelBatch]) {
         const int r = it / nb, bt = it - r * nb;
         const int nq = slots_of(bt);
-        const float2* pr = partials + ((size_t)s * B + (wv + r * kSelWaves)) * ppitch;
+        const REC* pr = partials + ((size_t)s * B + (wv + r * kSelWaves)) * ppitch;
 #pragma unroll
         for (int q = 0; q < kSelBatch; ++q)
-            if (q < nq) p[q] = pr[min(bt * kBatchTiles + ln + q * kWave, ntiles - 1)];
+            if (q < nq) p[q] = load_record<SAME_KERNEL>(pr + min(bt * kBatchTiles + ln + q * kWave, ntiles - 1));
+    };
+    auto load_ids2 = [&](int it, int32_t (&p)[kSelBatch]) {
+        const int r = it / nb, bt = it - r * nb;
+        const int nq = slots_of(bt);
+        const int32_t* pr = ids2 + ((size_t)s * B + (wv + r * kSelWaves)) * ppitch;
+#pragma unroll
+        for (int q = 0; q < kSelBatch; ++q)
+            if (q < nq) p[q] = load_id2<SAME_KERNEL>(pr + min(bt * kBatchTiles + ln + q * kWave, ntiles - 1));
     };
     {
-        float2 cur[kSelBatch], nxt[kSelBatch];
+        REC cur[kSelBatch], nxt[kSelBatch];
 #pragma unroll
         for (int q = 0; q < kSelBatch; ++q) cur[q] = first_batch[q];
         float m = -INFINITY, sum = 0.f, lmx = -INFINITY, bsi = 0.f;
@@ -308,13 +378,21 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q)
                 if (q >= nq || bt * kBatchTiles + ln + q * kWave >= ntiles)
-                    cur[q] = make_float2(-INFINITY, 0.f);
+                    cur[q] = RecTraits<REC>::empty();
+            if constexpr (KEEP > 0) {
 #pragma unroll
-            for (int k = 0; k < kSelKeep; ++k)  // registers cannot be indexed at run time
-                if (k == it) {
+                for (int k = 0; k < KEEP; ++k)  // registers cannot be indexed at run time
+                    if (k == it) {
 #pragma unroll
-                    for (int q = 0; q < kSelBatch; ++q) keep[k][q] = cur[q].x;
-                }
+                        for (int q = 0; q < kSelBatch; ++q) {
+                            keep[k][q] = cur[q].x;
+                            if constexpr (RICH) {
+                                keep_z[k][q] = cur[q].z;
+                                keep_id1[k][q] = __float_as_int(cur[q].w);
+                            }
+                        }
+                    }
+            }
             float bm = cur[0].x;
 #pragma unroll
             for (int q = 1; q < kSelBatch; ++q)
@@ -337,13 +415,19 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
             for (int q = 0; q < kSelBatch; ++q) cur[q] = nxt[q];
         }
     }
+    if constexpr (RICH && KEEP > 0) {
+        // (only batch 0 of the wave's first row can be in first_ids2; KEEP is 1 for rich records)
+        static_assert(KEEP == 1, "rich records keep one batch");
+#pragma unroll
+        for (int q = 0; q < kSelBatch; ++q) keep_id2[0][q] = first_ids2[q];
+    }
     if (nb == 0) {  // empty candidate list: every row's log-sum-exp is -inf
         for (int i = wv; i < B; i += kSelWaves)
             if (ln == 0) {
                 sh.lse[i] = -INFINITY; sh.bs[i] = beam_scores[s * B + i]; lse_out[s * B + i] = -INFINITY;
             }
     }
-    LSH_TRACE(2, 1);
+    LSH_TRACE_ANY(2, 1);
 
     // ---- threshold tau: a lower bound of the B-th best score from the 16 x 64 lane values
     //      (B distinct tile maxima are >= it).  Up to 16 beams every row has its own wave, and
@@ -360,7 +444,172 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
     } else {
         tau = block_kth_largest_lb(lmax, B, &sh);
     }
-    LSH_TRACE(2, 2);
+    LSH_TRACE_ANY(2, 2);
+
+    // Ranks the m <= kSelRankCap keys of sh.list by counting (the inner loop split over the
+    // workgroup: thread t compares key e = t % m with one of `parts` slices of the list); ends
+    // with a barrier, ranks in sh.rank.
+    auto rank_list = [&](int m) {
+        if (tid < m) sh.rank[tid] = 0;
+        __syncthreads();
+        if (m > 0) {
+            const int parts = kSelThreads / m;
+            const int e = tid % m, p = tid / m;
+            if (p < parts) {
+                const int chunk = (m + parts - 1) / parts;
+                const int j0 = p * chunk, j1 = min(m, j0 + chunk);
+                const uint64_t mine = sh.list[e];
+                uint32_t rank = 0;
+#pragma unroll 8
+                for (int j = j0; j < j1; ++j) rank += (sh.list[j] > mine) ? 1u : 0u;
+                if (rank) atomicAdd(&sh.rank[e], rank);
+            }
+        }
+        __syncthreads();
+    };
+    // Results from the ranked list: rank r < B goes to slot r; slots beyond the number of finite
+    // scores are (-1, -1, -inf).  The low 24 bits of a key's index are a word id (ids_in_keys) or
+    // a column of the candidate list.
+    const size_t o0 = (size_t)s * B;
+    auto emit = [&](int m, bool ids_in_keys) {
+        for (int e = tid + min(m, B); e < B; e += kSelThreads) {
+            out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
+        }
+        if (tid < m && sh.rank[tid] < (uint32_t)B) {
+            const uint64_t k = sh.list[tid];
+            const size_t o = o0 + sh.rank[tid];
+            const float score = key_value(k);
+            const uint32_t idx = key_index(k);
+            if (score == -INFINITY || score != score) {
+                out_beam[o] = -1; out_word[o] = -1; out_score[o] = -INFINITY;
+            } else {
+                const int c = (int)(idx & 0xFFFFFFu);
+                out_beam[o] = (int)(idx >> 24);
+                out_word[o] = (ids_in_keys || !cand) ? c : cand[(size_t)s * V + c];
+                out_score[o] = score;
+            }
+        }
+    };
+
+    if constexpr (RICH) {
+        // ---- the short cut: every largest / second largest score >= tau, from the records ----
+        // (no barrier needed here: the counters were cleared before the barriers of the tau
+        // computation, and a wave reads back only the lse / beam score of its own rows)
+        wave_lds_sync();
+        for (int it = 0; it < nit; ++it) {
+            const int r = it / nb, bt = it - r * nb;
+            const int i = wv + r * kSelWaves;
+            const int t0 = bt * kBatchTiles;
+            const float lse = sh.lse[i], bsi = sh.bs[i];
+            float x1[kSelBatch], x2[kSelBatch];
+            int32_t i1[kSelBatch], i2[kSelBatch];
+            bool have = false;
+            if constexpr (KEEP > 0) {
+                if (it < KEEP) {
+                    have = true;
+#pragma unroll
+                    for (int k = 0; k < KEEP; ++k)
+                        if (k == it) {
+#pragma unroll
+                            for (int q = 0; q < kSelBatch; ++q) {
+                                x1[q] = keep[k][q]; x2[q] = keep_z[k][q];
+                                i1[q] = keep_id1[k][q]; i2[q] = keep_id2[k][q];
+                            }
+                        }
+                }
+            }
+            if (!have) {
+                REC p[kSelBatch];
+#pragma unroll
+                for (int q = 0; q < kSelBatch; ++q) { p[q] = RecTraits<REC>::empty(); i2[q] = -1; }
+                load_batch(it, p);
+                load_ids2(it, i2);
+#pragma unroll
+                for (int q = 0; q < kSelBatch; ++q) {
+                    x1[q] = p[q].x; x2[q] = p[q].z; i1[q] = __float_as_int(p[q].w);
+                }
+            }
+            const int nq = slots_of(bt);
+#pragma unroll
+            for (int q = 0; q < kSelBatch; ++q) {
+                if (q >= nq) continue;  // wave-uniform
+                const bool in = t0 + ln + q * kWave < ntiles;
+                const float s1 = bsi + (x1[q] - lse), s2 = bsi + (x2[q] - lse);
+                if (in && i1[q] >= 0 && f32_sortable(s1 + 0.0f) >= tau) {
+                    const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
+                    if (pos < (uint32_t)kSelListCap) {
+                        sh.list[pos] = make_key(s1, ((uint32_t)i << 24) | (uint32_t)i1[q]);
+                        sh.open_list[pos] = 0u;
+                    }
+                }
+                if (in && i2[q] >= 0 && f32_sortable(s2 + 0.0f) >= tau) {
+                    const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
+                    if (pos < (uint32_t)kSelListCap) {
+                        sh.list[pos] = make_key(s2, ((uint32_t)i << 24) | (uint32_t)i2[q]);
+                        sh.open_list[pos] = 1u;   // a second largest
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        LSH_TRACE_ANY(2, 6);
+        const int mr = (int)sh.misc[4];
+        if (mr <= kWave) {
+            // The usual case, a few dozen keys: wave 0 ranks the whole list by itself (lane e
+            // holds key e; the others come by lane broadcast), writes the results unless a
+            // second largest is among the B best, and tells the others, who only wait.  (All 16
+            // waves ranking redundantly, to save this barrier, measured slower: they share four
+            // instruction issuers.)
+            if (wv == 0) {
+                const uint64_t mine = (ln < mr) ? sh.list[ln] : 0ull;
+                const bool second = (ln < mr) && sh.open_list[ln] != 0u;
+                const uint32_t lo = (uint32_t)mine, hi = (uint32_t)(mine >> 32);
+                uint32_t rank = 0;
+                for (int j = 0; j < mr; ++j) {   // (j is wave-uniform)
+                    const uint64_t other = ((uint64_t)wave_read_lane(hi, j) << 32) | wave_read_lane(lo, j);
+                    rank += (other > mine) ? 1u : 0u;
+                }
+                const bool hidden = __ballot(ln < mr && rank < (uint32_t)B && second) != 0ull;
+                if (ln == 0) sh.misc[6] = hidden ? 1u : 0u;
+                if (!hidden) {
+                    for (int e = ln + min(mr, B); e < B; e += kWave) {
+                        out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
+                    }
+                    if (ln < mr && rank < (uint32_t)B) {
+                        const size_t o = o0 + rank;
+                        const float score = key_value(mine);
+                        const uint32_t idx = key_index(mine);
+                        const bool none = score == -INFINITY || score != score;
+                        out_beam[o] = none ? -1 : (int)(idx >> 24);
+                        out_word[o] = none ? -1 : (int)(idx & 0xFFFFFFu);
+                        out_score[o] = none ? -INFINITY : score;
+                    }
+                }
+            }
+            LSH_TRACE_ANY(2, 4);
+            __syncthreads();
+            if (sh.misc[6] == 0u) {
+                LSH_TRACE_ANY(2, 5);
+                return;
+            }
+        } else if (mr <= kSelRankCap) {   // (workgroup-uniform)
+            rank_list(mr);
+            if (tid < mr && sh.rank[tid] < (uint32_t)B && sh.open_list[tid]) sh.misc[6] = 1u;
+            __syncthreads();
+            if (sh.misc[6] == 0u) {
+                LSH_TRACE_ANY(2, 4);
+                emit(mr, true);
+                LSH_TRACE_ANY(2, 5);
+                return;
+            }
+        }
+        __syncthreads();
+        if (tid == 0) sh.misc[4] = 0;
+        // (logits and candidate ids are read with plain loads below: none of them may come from
+        // a cache line fetched before the other workgroups' stores)
+        if constexpr (SAME_KERNEL) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        __syncthreads();
+    }
 
     // ---- second pass: tiles whose maximum reaches tau are opened, 16 lanes per tile ----
     const ScoreSrc src{lg, cpitch, B, C, sh.lse, sh.bs};
@@ -373,21 +622,28 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
         const int t0 = bt * kBatchTiles;
         const float lse = sh.lse[i], bsi = sh.bs[i];
         float px[kSelBatch];  // the batch's tile maxima
-        if (it < kSelKeep) {
+        bool have = false;
+        if constexpr (KEEP > 0) {
+            if (it < KEEP) {
+                have = true;
 #pragma unroll
-            for (int k = 0; k < kSelKeep; ++k)
-                if (k == it) {
+                for (int k = 0; k < KEEP; ++k)
+                    if (k == it) {
 #pragma unroll
-                    for (int q = 0; q < kSelBatch; ++q) px[q] = keep[k][q];
-                }
-        } else {
-            float2 p[kSelBatch];
+                        for (int q = 0; q < kSelBatch; ++q) px[q] = keep[k][q];
+                    }
+            }
+        }
+        if (!have) {
+            REC p[kSelBatch];
+#pragma unroll
+            for (int q = 0; q < kSelBatch; ++q) p[q] = RecTraits<REC>::empty();
             load_batch(it, p);
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q) px[q] = p[q].x;
         }
         // most batches hold no qualifying tile: one test on the lane's best of the batch
-        // settles that (this kernel is bound by instruction issue, 16 waves on one CU)
+        // settles that (bound by instruction issue, 16 waves on one CU)
         float best = px[0];
 #pragma unroll
         for (int q = 1; q < kSelBatch; ++q) best = fmaxf(best, px[q]);
@@ -418,9 +674,9 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
             }
         }
     }
-    LSH_TRACE(2, 6);
+    LSH_TRACE_ANY(2, 6);
     __syncthreads();
-    LSH_TRACE(2, 7);
+    LSH_TRACE_ANY(2, 7);
     // (b) 16 lanes per tile, 64 tiles per sweep of the workgroup, four sweeps in flight
     const uint32_t n_open = sh.misc[5];
     if (n_open <= (uint32_t)kSelOpenCap) {
@@ -448,15 +704,15 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
                 }
             }
         }
-        LSH_TRACE(2, 8);
+        LSH_TRACE_ANY(2, 8);
     } else if (tid == 0) {
         sh.misc[4] = kSelListCap + 1;  // too many qualifying tiles (heavy ties): exact select below
     }
     __syncthreads();
     int m = (int)sh.misc[4];
-    LSH_TRACE(2, 3);
+    LSH_TRACE_ANY(2, 3);
 #ifdef LSHBEAM_TRACE
-    if (blockIdx.x == 0 && tid == 0) {
+    if (tid == 0) {
         g_trace[2][10] = g_trace[2][0] + n_open;  // counts, printed as offsets from slot 0
         g_trace[2][11] = g_trace[2][0] + (unsigned)m;
     }
@@ -491,48 +747,25 @@ k_select(const float* __restrict__ logits, int64_t cpitch, const float2* __restr
         block_radix_select(src, B, &sh);
         m = B;
     }
+    rank_list(m);
+    LSH_TRACE_ANY(2, 4);
+    emit(m, false);
+    LSH_TRACE_ANY(2, 5);
+}
 
-    // ---- rank the m listed keys by counting; the inner loop is split over the workgroup:
-    //      thread t compares key e = t % m with one of `parts` slices of the list ----
-    if (tid < m) sh.rank[tid] = 0;
-    __syncthreads();
-    if (m > 0) {
-        const int parts = kSelThreads / m;
-        const int e = tid % m, p = tid / m;
-        if (p < parts) {
-            const int chunk = (m + parts - 1) / parts;
-            const int j0 = p * chunk, j1 = min(m, j0 + chunk);
-            const uint64_t mine = sh.list[e];
-            uint32_t rank = 0;
-#pragma unroll 8
-            for (int j = j0; j < j1; ++j) rank += (sh.list[j] > mine) ? 1u : 0u;
-            if (rank) atomicAdd(&sh.rank[e], rank);
-        }
-    }
-    __syncthreads();
-    LSH_TRACE(2, 4);
-
-    // ---- results: rank r < B goes to slot r; slots beyond the number of finite scores are
-    //      (-1, -1, -inf) ----
-    const size_t o0 = (size_t)s * B;
-    for (int e = tid + min(m, B); e < B; e += kSelThreads) {
-        out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
-    }
-    if (tid < m && sh.rank[tid] < (uint32_t)B) {
-        const uint64_t k = sh.list[tid];
-        const size_t o = o0 + sh.rank[tid];
-        const float score = key_value(k);
-        const uint32_t idx = key_index(k);
-        if (score == -INFINITY || score != score) {
-            out_beam[o] = -1; out_word[o] = -1; out_score[o] = -INFINITY;
-        } else {
-            const int c = (int)(idx & 0xFFFFFFu);
-            out_beam[o] = (int)(idx >> 24);
-            out_word[o] = cand ? cand[(size_t)s * V + c] : c;
-            out_score[o] = score;
-        }
-    }
-    LSH_TRACE(2, 5);
+// grid = S workgroups (one per sentence), kSelThreads threads: the selection as a kernel of its
+// own, after kernels that left plain (float2) or rich (float4 + ids2) tile records.
+template <typename REC>
+__global__ void __launch_bounds__(kSelThreads)
+k_select(const float* __restrict__ logits, int64_t cpitch, const REC* __restrict__ partials,
+         const int32_t* __restrict__ ids2, int64_t ppitch, const int32_t* __restrict__ cand,
+         const int32_t* __restrict__ count, int V, int B, const float* __restrict__ beam_scores,
+         float* __restrict__ lse_out /*[R]*/, int32_t* __restrict__ out_beam,
+         int32_t* __restrict__ out_word, float* __restrict__ out_score) {
+    __shared__ SelShared sh;
+    select_sentence<REC, RecTraits<REC>::RICH ? 1 : kSelKeep>(sh, (int)blockIdx.x, logits, cpitch, partials, ids2,
+                                                             ppitch, cand, count, -1, V, B, beam_scores,
+                                                             lse_out, out_beam, out_word, out_score);
 }
 
 // lp[i, c] = logit[i, c] - lse[i] for one sentence, for inspection.

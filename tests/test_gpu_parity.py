@@ -600,28 +600,72 @@ def test_step_is_deterministic():
 
 @pytest.mark.parametrize("name,S,B,t", [("paper", 1, 12, 1), ("tiny", 2, 4, 1), ("tiny", 1, 20, 1),
                                         ("tiny", 2, 4, 2), ("paperscale", 1, 12, 5),
-                                        ("paper", 1, 30, 1)])
-def test_fused_and_three_kernel_paths_agree_bit_for_bit(name, S, B, t, force):
-    # few sentences: candidates are regenerated inside the logits kernel; option fused = 0 forces
-    # the general three-kernel path.  Same arithmetic, same order: every output must be identical.
+                                        ("paper", 1, 30, 1), ("paper", 4, 12, 1), ("tiny", 8, 16, 1)])
+def test_one_launch_two_launch_and_three_kernel_plans_agree_bit_for_bit(name, S, B, t, force):
+    # few sentences: candidates are regenerated inside the logits kernel, whose last workgroup per
+    # sentence also runs the selection (one launch).  Option one_launch = 0 ends the step with a
+    # selection kernel instead; option fused = 0 forces the general three-kernel path.  Same
+    # arithmetic, same order: every output must be identical.
     from paper_1806_00588_amd import binding
     cfg, gc = case(name)
-    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)[:S * B]
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    if len(H) < S * B:
+        H = np.concatenate([H, H[::-1] * 0.5 + 0.1], axis=0)
+    H = H[:S * B]
     bs = np.linspace(-1, 0, S * B).astype(np.float32)
     res = {}
-    for mode in ("1", "0"):
-        force(gc, fused=int(mode))
+    for mode, opts in (("one", dict(fused=1, one_launch=1)), ("two", dict(fused=1, one_launch=0)),
+                       ("three", dict(fused=0))):
+        gc.tables.reset_options()
+        force(gc, **opts)
         gb, gw, gs, sp, ws = gc.step(H, bs, S, B, threshold=t)
-        assert binding.step_is_fused(gc.tables, sp) == (mode == "1")
+        assert binding.step_is_fused(gc.tables, sp) == (mode != "three")
         cands = [gc.tables.debug_candidates(ws, sp, s) for s in range(S)]
         lps = [gc.tables.debug_logprobs(ws, sp, s, cap=len(cands[s])) for s in range(S)]
         res[mode] = (gb, gw, gs, cands, lps)
-    for x, y in zip(res["1"][:3], res["0"][:3]):
-        assert np.array_equal(x, y)
+    for other in ("two", "three"):
+        for x, y in zip(res["one"][:3], res[other][:3]):
+            assert np.array_equal(x, y), other
+        for s in range(S):
+            assert np.array_equal(res["one"][3][s], res[other][3][s])
+            assert np.array_equal(res["one"][4][s], res[other][4][s])
     for s in range(S):
-        assert np.array_equal(res["1"][3][s], res["0"][3][s])
-        assert np.array_equal(res["1"][4][s], res["0"][4][s])
-        assert np.array_equal(res["1"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq, t))
+        assert np.array_equal(res["one"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq, t))
+
+
+@pytest.mark.parametrize("one_launch", [1, 0])
+def test_winners_that_share_a_tile(one_launch, force):
+    # The selection of the fused plans works from per-tile records (largest and second largest
+    # logit of each row and tile) and must notice when a tile hides a third winner.  Here the
+    # candidate list is all of V in id order (every id is "top-frequent"), so tile = id / 16, and
+    # the words of one tile are near copies of the hidden direction: for the dominant beam all B
+    # winners sit in that one tile; other steps put two winners into one tile, or one per tile.
+    rng = np.random.default_rng(16)
+    V, d, K, P, W = 640, 32, 4, 8, 2
+    E = rng.standard_normal((V, d)).astype(np.float32)
+    base = rng.standard_normal(d).astype(np.float32)
+    for k in range(16):
+        E[96 + k] = base * np.float32(1.0 - 0.01 * k)          # tile 6: scores fall slowly with k
+    E[200] = base * np.float32(0.97)                             # lone near-winners in other tiles
+    E[333] = base * np.float32(0.955)
+    perms = np.stack([rng.permutation(d)[:K] for _ in range(P)]).astype(np.int32)
+    gc = GpuCase(E, perms, np.arange(V, dtype=np.int32), W)
+    force(gc, fused=1, one_launch=one_launch)
+    for B in (4, 6, 12, 16, 20):
+        H = rng.standard_normal((B, d)).astype(np.float32) * 0.05
+        H[0] += base * 3.0
+        if B > 4:
+            H[3] += base * 2.9
+        for bs0 in (0.0, -50.0):
+            bs = np.full(B, -60.0, np.float32)
+            bs[0] = 0.0
+            if B > 4:
+                bs[3] = bs0
+            gb, gw, gs, swaps = run_and_check(None, gc, H, bs, 1, B)
+            assert swaps == 0
+            assert gb[0, 0] == 0 and gw[0, 0] == 96
+        # and with every beam alive: winners spread over rows
+        run_and_check(None, gc, H, np.zeros(B, np.float32), 1, B)
 
 
 @pytest.mark.parametrize("part_rows", [1, 3, 5])
