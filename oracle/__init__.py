@@ -30,13 +30,27 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized() -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (g++ -O1 -g).  A process
+    that loads it needs libasan first in its library list (LD_PRELOAD) and names it in the
+    environment variable LSH_ORACLE_LIB; tests/test_oracle_sanitized.py does both."""
+    out = os.path.join(_HERE, "liblsh_oracle_asan.so")
+    if not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+        tmp = out + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-Wall",
+                               "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                               "-o", tmp, _SRC])
+        os.replace(tmp, out)
+    return out
+
+
 _lib = None
 
 
 def _L():
     global _lib
     if _lib is None:
-        lib = ctypes.CDLL(build())
+        lib = ctypes.CDLL(os.environ.get("LSH_ORACLE_LIB") or build())
         vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
         lib.orc_wta_codes.argtypes = [vp, i64, i32, i64, i32, _c_i32p, i32, i32, _c_i32p]
         lib.orc_band_codes.argtypes = [_c_i32p, i64, i32, i32, i32, _c_i32p]

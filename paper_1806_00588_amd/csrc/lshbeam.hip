@@ -28,6 +28,7 @@
 #include "fused.h"
 #include "logits.h"
 #include "select.h"
+#include "workspace.h"
 
 using namespace lshbeam;
 
@@ -61,12 +62,10 @@ hipError_t scratch_of_device(int dev, void** out) {
 
 constexpr int kMaxV = 1 << 24;
 constexpr int kMaxB = 256;
-constexpr size_t kAlign = 256;
 constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
 constexpr int kTicketSlots = 256;   // workspaces per handle that can take the one-launch plan
 constexpr int kTicketBlock = 64;    // counters per workspace = sentences of a fused step at most
 
-inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct HostBand {
     std::vector<int32_t> keys;     // distinct band codes, ascending
@@ -230,37 +229,8 @@ void launch(const StepCtx& cx, int which, void (*kernel)(KArgs...), dim3 grid, d
     }
 }
 
-// Workspace layout of one step.
-struct Workspace {
-    int32_t* cand;       // [S, V]
-    int32_t* count;      // [S]
-    float* logits;       // [R, cpitch]
-    float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max)) as float2
-                         //   from the plain kernels, a 16-byte TileRecord from the fused ones
-    int32_t* ids2;       // [R, ppitch]  fused kernels: word id of each record's second largest
-    uint32_t* row_bitmaps;  // [R, ceil(V/32)]  per-row (t > 1) or per-part (many beams) bitmaps
-    float* lse;          // [R]
-    int64_t ppitch;
-    int64_t cpitch;
-    size_t bytes;
-};
-
 Workspace carve(const lsh_tables* t, const lsh_step_params* sp, void* base) {
-    Workspace w{};
-    const size_t S = sp->S, B = sp->B, R = S * B, V = t->V;
-    w.cpitch = (int64_t)((V + 63) / 64 * 64);
-    size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return (char*)base + o; };
-    w.cand = (int32_t*)take(sp->full_vocab ? 0 : S * V * sizeof(int32_t));
-    w.count = (int32_t*)take(S * sizeof(int32_t));
-    w.ppitch = w.cpitch / kTileN;
-    w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
-    w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(TileRecord));
-    w.ids2 = (int32_t*)take(R * (size_t)w.ppitch * sizeof(int32_t));
-    w.lse = (float*)take(R * sizeof(float));
-    w.row_bitmaps = (uint32_t*)take(sp->full_vocab ? 0 : R * ((V + 31) / 32) * sizeof(uint32_t));
-    w.bytes = off;
-    return w;
+    return carve_workspace(sp->S, sp->B, t->V, sp->full_vocab != 0, base);
 }
 
 bool step_params_ok(const lsh_tables* t, const lsh_step_params* sp) {

@@ -45,9 +45,12 @@ def force():
 @pytest.mark.parametrize("name", ["tiny", "paper", "widebeam", "largevocab"])
 def test_embedding_band_codes_bit_exact(name):
     cfg, gc = case(name)
-    n = min(cfg.V, 50000)
-    want = oracle.band_codes(oracle.wta_codes(gc.E[:n], gc.perms), cfg.W, cfg.K)
-    assert np.array_equal(gc.tables.debug_embedding_codes(0, n), want)
+    got = gc.tables.debug_embedding_codes()                      # every row of E
+    assert got.shape == (cfg.V, cfg.W)
+    for r0 in range(0, cfg.V, 50000):                            # (the oracle, a slab at a time)
+        r1 = min(cfg.V, r0 + 50000)
+        want = oracle.band_codes(oracle.wta_codes(gc.E[r0:r1], gc.perms), cfg.W, cfg.K)
+        assert np.array_equal(got[r0:r1], want), (r0, r1)
 
 
 @pytest.mark.parametrize("name", ["tiny", "paper", "widebeam", "largevocab"])
@@ -67,7 +70,10 @@ def test_buckets_through_cuckoo_bit_exact(name, max_keys):
         keys, offs, words = gc.tables.debug_csr(w)
         assert np.array_equal(keys, okeys)                       # distinct codes, ascending
         assert offs[0] == 0 and offs[-1] == cfg.V and np.all(np.diff(offs) > 0)
-        assert np.array_equal(np.sort(words), np.arange(cfg.V))  # a partition of 0..V-1
+        # the whole flat array, span by span: the oracle's buckets concatenated in key order
+        obuckets = [gc.index.bucket(w, int(code)) for code in okeys]
+        assert np.array_equal(np.diff(offs), [len(b) for b in obuckets])
+        assert np.array_equal(words, np.concatenate(obuckets))
         cap, nk = gc.tables.debug_cuckoo_shape(w)
         assert nk == len(keys) and cap >= 2 * nk and cap & (cap - 1) == 0
         probe = okeys if max_keys is None else rng.choice(okeys, size=min(max_keys, len(okeys)),
@@ -394,26 +400,38 @@ def test_paper_banding_with_hit_threshold():
 def test_batched_shape():
     cfg, gc0 = case("paper")                       # same E / perms / top-freq as the paper shape
     cfg = workloads.CONFIGS["batched"]
-    H = workloads.make_hidden(cfg, gc0.E, seed=0, steps=2)
+    H = workloads.make_hidden(cfg, gc0.E, seed=0, steps=3)
     rng = np.random.default_rng(3)
-    run_and_check(cfg, gc0, H[1], -rng.random(cfg.R).astype(np.float32), cfg.S, cfg.B)
+    # every sentence of two steps in full (candidate lists, log-probabilities, top-B) ...
+    for step in (1, 2):
+        run_and_check(cfg, gc0, H[step], -rng.random(cfg.R).astype(np.float32), cfg.S, cfg.B)
 
 
 def test_widebeam_shape():
     cfg, gc = case("widebeam")
-    H = hidden(cfg, gc, 1)
+    H = hidden(cfg, gc, 2)
     run_and_check(cfg, gc, H[0], np.zeros(cfg.R, np.float32), cfg.S, cfg.B)
+    # a second step with spread-out beam scores: candidate lists and top-B of every sentence
+    rng = np.random.default_rng(50)
+    run_and_check(cfg, gc, H[1], (rng.standard_normal(cfg.R) * 3).astype(np.float32), cfg.S, cfg.B,
+                  check_lp=False)
 
 
 def test_largevocab_bf16_shape():
     cfg, gc = case("largevocab")
     H = hidden(cfg, gc, 1)
-    nS = 12                                         # oracle time: 12 of the 64 sentences
     gb, gw, gs, sp, ws = gc.step(H[0], np.zeros(cfg.R, np.float32), cfg.S, cfg.B)
-    for s in list(range(nS - 1)) + [cfg.S - 1]:
+    counts = gc.tables.debug_counts(ws, sp)
+    # candidate lists: all 64 sentences, bit for bit (cheap for the oracle)
+    for s in range(cfg.S):
+        Hs = H[0][s * cfg.B:(s + 1) * cfg.B]
+        want = gc.index.candidates(Hs, gc.topfreq)
+        assert counts[s] == len(want)
+        assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), want), s
+    # log-probabilities and top-B: 12 of the 64 sentences (the oracle's fp64 products take time)
+    for s in list(range(11)) + [cfg.S - 1]:
         Hs = H[0][s * cfg.B:(s + 1) * cfg.B]
         ref = gc.oracle_sentence(Hs, np.zeros(cfg.B), cfg.B)
-        assert np.array_equal(gc.tables.debug_candidates(ws, sp, s), ref.cand)
         assert_close_logprobs(gc.tables.debug_logprobs(ws, sp, s, cap=len(ref.cand)), ref)
         assert_topb_matches(gb[s], gw[s], gs[s], ref, np.zeros(cfg.B))
 
