@@ -30,11 +30,12 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
-def build_sanitized() -> str:
-    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (g++ -O1 -g).  A process
-    that loads it needs libasan first in its library list (LD_PRELOAD) and names it in the
-    environment variable LSH_ORACLE_LIB; tests/test_oracle_sanitized.py does both."""
-    out = os.path.join(_HERE, "liblsh_oracle_asan.so")
+def build_sanitized(out_dir: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (g++ -O1 -g), built
+    into out_dir.  A process that loads it needs libasan first in its library list (LD_PRELOAD)
+    and names it in the environment variable LSH_ORACLE_LIB; tests/test_oracle_sanitized.py does
+    both."""
+    out = os.path.join(out_dir, "liblsh_oracle_asan.so")
     if not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
         tmp = out + ".tmp.%d" % os.getpid()
         subprocess.check_call(["g++", "-std=c++17", "-O1", "-g", "-fPIC", "-shared", "-Wall",

@@ -11,8 +11,8 @@ import oracle
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_oracle_tests_pass_under_asan_and_ubsan():
-    lib = oracle.build_sanitized()
+def test_oracle_tests_pass_under_asan_and_ubsan(tmp_path):
+    lib = oracle.build_sanitized(str(tmp_path))
     libasan = subprocess.check_output(["g++", "-print-file-name=libasan.so"], text=True).strip()
     assert os.path.isabs(libasan) and os.path.exists(libasan), libasan
     env = dict(os.environ)
