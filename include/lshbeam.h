@@ -223,6 +223,7 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
  *   "one_launch"     0: the fused kernel is followed by a selection kernel instead of running the
  *                    selection in its last workgroup
  *   "fused_grid"     workgroups of the fused kernel (default 256)
+ *   "fused_tile"     n = 1..15: candidates per tile of the fused kernel instead of 16
  *   "logits_grid"    workgroups (or waves' worth of them) of the separate contraction kernels
  *   "logits_waves"   1 / 4 / 16: contraction driver (a wave per tile; k split over 4 or 16 waves)
  *   "logits_hlds"    0: the wave-per-tile driver keeps the hidden rows in global memory, not LDS

@@ -33,98 +33,105 @@ namespace lshbeam {
 
 constexpr int kFusedWaves = kCandThreads / kWave;  // 16: the split-k width of the contraction
 
-__host__ __device__ inline uint32_t pow2_at_least(uint32_t x) {
-    uint32_t p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
+constexpr int kFusedRound = 16;                             // tiles of a workgroup looked up at a time
+constexpr int kFusedTileIdWords = kFusedRound * kTileN;     // their candidate ids in LDS
 
-// LDS words: candidate generation + prefix array (padded to a power of two, plus one) + the
-// cross-wave reduction buffer of the contraction.
+// LDS words: candidate generation + the candidate ids of a round of tiles + the cross-wave
+// reduction buffer of the contraction.
 // (the selection of the one-launch plan reuses the same memory from its start: SelShared)
 constexpr size_t kSelSharedWords = (sizeof(SelShared) + 3) / 4;
 __host__ __device__ inline size_t fused_lds_words(int V, int P, int K, int stage_words) {
-    const uint32_t nwords = (uint32_t)(((size_t)V + 31) / 32);
-    const size_t need = candidates_lds_words(V, P, K, stage_words) + pow2_at_least(nwords) + 1 +
+    const size_t need = candidates_lds_words(V, P, K, stage_words) + kFusedTileIdWords +
                         (size_t)kFusedWaves * 4 * kWave;
     return need > kSelSharedWords ? need : kSelSharedWords;
 }
 
 // Outputs and inputs of the step's tail (log-softmax + beam expansion) for the one-launch plan.
-// (ONE_LAUNCH = false: the kernel stops after its tiles, a selection kernel follows, and only ids2
-// is used.)
+// (ONE_LAUNCH = false: the kernel stops after its tiles and a selection kernel follows.)
 struct TailArgs {
     unsigned int* tickets;       // [S] counters, zero between steps
     const float* beam_scores;    // [S*B]
     float* lse;                  // [S*B]
-    int32_t* ids2;               // [R, ppitch] word id of each record's second largest logit
     int32_t* out_beam;           // [S, B]
     int32_t* out_word;
     float* out_score;
+    int tile_forced;             // 1..15: candidates per tile instead of 16 (option fused_tile)
 };
 
-// What follows the bitmap in both fused kernels: exclusive prefix of the bitmap words'
-// popcounts, then for each of this workgroup's tiles the 16 candidates by rank and the split-k
-// tile.  `wpref` has pow2_at_least(nwords) + 1 words, `wsum` >= 17, `red` is the cross-wave
-// reduction buffer; h_lds (or null) are the sentence's hidden rows staged in LDS as [B][d].
+// What follows the bitmap in both fused kernels.  Thread t owns a contiguous run of bitmap words;
+// a workgroup scan of the runs' popcounts tells it which output positions of the ascending
+// candidate list its set bits are.  The workgroup's tiles (g, g + G, ...) are taken kFusedRound at
+// a time: every thread whose positions fall into one of them writes those ids to a small LDS
+// table -- usually one or two threads per tile, walking at most 16 set bits -- and after a barrier
+// the lanes of each tile read their candidate from it.  (Finding each lane's candidate by a
+// search of a prefix array over all words -- a dozen dependent LDS reads per lane, behind a
+// barrier that waited for the whole array -- cost a microsecond more.)
+// `tile_ids` has kFusedRound * 16 words, `wsum` >= 17, `red` is the cross-wave reduction buffer;
+// h_lds (or null) are the sentence's hidden rows staged in LDS as [B][d].
 template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
-__device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* wsum, uint32_t* wpref,
+__device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* wsum, uint32_t* tile_ids,
                                                   float (*red)[4][kWave], const float* h_lds,
                                                   const ET* __restrict__ E, int64_t ld, int d,
                                                   const float* __restrict__ H, int B, int V, int s,
                                                   int g, int G, int32_t* __restrict__ cand,
                                                   int32_t* __restrict__ count,
                                                   float* __restrict__ logits, int64_t cpitch,
-                                                  float2* __restrict__ partials, int64_t ppitch,
-                                                  const TailArgs& tail, uint32_t* smem) {
+                                                  TileRecords recs, const TailArgs& tail, uint32_t* smem) {
     const int tid = threadIdx.x, ln = lane_id();
     const int nwords = (V + 31) >> 5;
-    const uint32_t npow = pow2_at_least((uint32_t)nwords);
-    // exclusive prefix of the bitmap words' popcounts; entries past the last word hold the total
-    const int per_thread = (int)((npow + kCandThreads - 1) / kCandThreads);
-    const int wbeg = tid * per_thread;
+    const int per_thread = (nwords + kCandThreads - 1) / kCandThreads;
+    const int wbeg = min(tid * per_thread, nwords), wend = min(wbeg + per_thread, nwords);
     uint32_t mine = 0;
-    for (int i = wbeg; i < wbeg + per_thread; ++i) mine += (i < nwords) ? __popc(bm[i]) : 0u;
+    for (int i = wbeg; i < wend; ++i) mine += __popc(bm[i]);
     uint32_t total;
-    uint32_t run = block_incl_scan(mine, wsum, &total) - mine;
-    for (int i = wbeg; i < wbeg + per_thread; ++i) {
-        if (i < (int)npow) wpref[i] = run;
-        run += (i < nwords) ? __popc(bm[i]) : 0u;
-    }
-    if (tid == 0) wpref[npow] = total;
-    __syncthreads();
+    const uint32_t run = block_incl_scan(mine, wsum, &total) - mine;   // first output position of my bits
     LSH_TRACE(0, 6);
     LSH_TRACE_WG(4);
     const int C = (int)total;
-    if (g == 0 && tid == 0) store_shared_result<ONE_LAUNCH>(&count[s], (int32_t)C);
 
-    const int ntiles = (C + kTileN - 1) / kTileN;
+    const int tn = select_tile_width(C, tail.tile_forced, recs.pitch);
+    const int ntiles = (C + tn - 1) / tn;
     const int col = ln & 15;
-    for (int nt = g; nt < ntiles; nt += G) {
-        // this lane's candidate: output position 16 nt + col of the ascending list (clamped onto
-        // the last one past the end; such columns are never stored)
-        const uint32_t jpos = (uint32_t)min(nt * kTileN + col, C - 1);
-        uint32_t lo = 0;
-        for (uint32_t step = npow >> 1; step >= 1; step >>= 1)
-            if (wpref[lo + step] <= jpos) lo += step;  // last word whose prefix is <= jpos
-        uint32_t wbits = bm[lo];
-        uint32_t nth = jpos - wpref[lo];  // rank of the wanted bit inside the word
-        int pos = 0;
-#pragma unroll
-        for (int width = 16; width >= 1; width >>= 1) {
-            const uint32_t low = wbits & ((1u << width) - 1u);
-            const uint32_t c = __popc(low);
-            if (nth >= c) { nth -= c; wbits >>= width; pos += width; }
-            else wbits = low;
+    for (int base = 0; g + base * G < ntiles; base += kFusedRound) {
+        // ids of the tiles g + (base + k) G, k < kFusedRound, into tile_ids[k][16]
+        if (mine) {
+            for (int k = 0; k < kFusedRound; ++k) {
+                const int nt = g + (base + k) * G;
+                if (nt >= ntiles) break;
+                const uint32_t lo = max(run, (uint32_t)(nt * tn));
+                const uint32_t hi = min(min(run + mine, (uint32_t)(nt * tn + tn)), (uint32_t)C);
+                if (lo >= hi) continue;
+                // my (lo - run)-th set bit and the hi - lo - 1 that follow
+                uint32_t skip = lo - run;
+                int i = wbeg;
+                uint32_t bits = bm[i];
+                for (uint32_t c = __popc(bits); skip >= c; c = __popc(bits)) { skip -= c; bits = bm[++i]; }
+                for (; skip; --skip) bits &= bits - 1u;
+                for (uint32_t pos = lo; pos < hi; ++pos) {
+                    while (!bits) bits = bm[++i];
+                    tile_ids[k * kTileN + (int)(pos - (uint32_t)(nt * tn))] = ((uint32_t)i << 5) + (uint32_t)(__ffs(bits) - 1);
+                    bits &= bits - 1u;
+                }
+            }
         }
-        const int32_t id = (int32_t)((lo << 5) + pos);
-        if (tid < kTileN && nt * kTileN + col < C)
-            store_shared_result<ONE_LAUNCH>(&cand[(size_t)s * V + nt * kTileN + col], id);
-        LSH_TRACE(1, 2);
-        logits_tile_all_rows<ET, kFusedWaves, 64 / kFusedWaves, ALIGNED, 0, true, ONE_LAUNCH>(
-            E, ld, d, H, B, s, nt, C, (int64_t)id, logits, cpitch, partials, ppitch, red, h_lds, 0, 0, -1,
-            tail.ids2);
+        __syncthreads();
+        for (int k = 0; k < kFusedRound; ++k) {
+            const int nt = g + (base + k) * G;
+            if (nt >= ntiles) break;
+            // this lane's candidate: output position 16 nt + col of the ascending list (lanes past
+            // the end of the list take the tile's first candidate; such columns are never stored)
+            const bool in_list = col < tn && nt * tn + col < C;
+            const int32_t id = (int32_t)tile_ids[k * kTileN + (in_list ? col : 0)];
+            if (tid < kTileN && in_list)
+                store_shared_result<ONE_LAUNCH>(&cand[(size_t)s * V + nt * tn + col], id);
+            LSH_TRACE(1, 2);
+            logits_tile_all_rows<ET, kFusedWaves, 64 / kFusedWaves, ALIGNED, 0, true, ONE_LAUNCH>(
+                E, ld, d, H, B, s, nt, C, (int64_t)id, logits, cpitch, recs, red, h_lds, 0, 0, -1, tn);
+        }
+        // (a tile ends with a barrier: the table is free for the next round)
     }
+    // (after the tiles: a barrier waits for the stores issued before it)
+    if (g == 0 && tid == 0) store_shared_result<ONE_LAUNCH>(&count[s], (int32_t)C);
     if constexpr (!ONE_LAUNCH) return;
 
     // ---- the step's tail, by the last workgroup of the sentence to get here ----
@@ -150,9 +157,9 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
     } else if (g != 0) {
         return;                // an empty list: workgroup 0 of the sentence pads the outputs
     }
-    select_sentence<TileRecord, 1, true>(sh, s, logits, cpitch, reinterpret_cast<const TileRecord*>(partials),
-                                   tail.ids2, ppitch, cand, nullptr, C, V, B, tail.beam_scores, tail.lse,
-                                   tail.out_beam, tail.out_word, tail.out_score);
+    select_sentence<true, true>(sh, s, logits, cpitch, recs.rec, recs.id2, recs.pitch, cand, nullptr, C, V, B,
+                          tail.beam_scores, tail.lse, tail.out_beam, tail.out_word, tail.out_score,
+                          tail.tile_forced);
 }
 
 // grid = S * G workgroups: workgroup b works for sentence b % S and takes that sentence's tiles
@@ -161,16 +168,15 @@ template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
 __global__ void __launch_bounds__(kCandThreads)
 k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* __restrict__ cand,
               int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
-              float2* __restrict__ partials, int64_t ppitch, TailArgs tail) {
+              TileRecords recs, TailArgs tail) {
     extern __shared__ uint32_t smem[];
     const int s = blockIdx.x % S;
     const int g = blockIdx.x / S, G = gridDim.x / S;
     const int V = a.V, B = a.B;
-    const uint32_t npow = pow2_at_least((uint32_t)((V + 31) >> 5));
     uint32_t* bm = smem;
     uint32_t* wsum = smem + candidates_lds_words(V, a.P, a.K, a.stage_words) - 64;
-    uint32_t* wpref = smem + candidates_lds_words(V, a.P, a.K, a.stage_words);
-    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + npow + 1);
+    uint32_t* tile_ids = smem + candidates_lds_words(V, a.P, a.K, a.stage_words);
+    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(tile_ids + kFusedTileIdWords);
 
     build_presence_bitmap(a, s, smem);
     // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
@@ -178,8 +184,8 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
     const float* h_lds = nullptr;
     if (candidates_rows_per_chunk(B, a.d, a.W, a.stage_words) >= B && (a.d & 3) == 0)
         h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
-    tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, wpref, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
-                                   count, logits, cpitch, partials, ppitch, tail, smem);
+    tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, tile_ids, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
+                                   count, logits, cpitch, recs, tail, smem);
     LSH_TRACE_WG(6);
 }
 
@@ -188,8 +194,7 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
 // threshold is above 1, one per part of the sentence by k_part_bitmaps when it has many beams)
 // and the top-frequent words (Eq. 3).
 __host__ __device__ inline size_t union_logits_lds_words(int V) {
-    const size_t need = (size_t)bitmap_words_padded(V) + 64 +
-                        ((pow2_at_least((uint32_t)(((size_t)V + 31) / 32)) + 1 + 3) & ~3u) +
+    const size_t need = (size_t)bitmap_words_padded(V) + 64 + kFusedTileIdWords +
                         (size_t)kFusedWaves * 4 * kWave;
     return need > kSelSharedWords ? need : kSelSharedWords;
 }
@@ -199,26 +204,24 @@ __global__ void __launch_bounds__(kCandThreads)
 k_union_logits(const uint32_t* __restrict__ part_bitmaps, int nparts, const int32_t* __restrict__ topfreq,
                int T, const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S,
                int B, int V, int32_t* __restrict__ cand, int32_t* __restrict__ count,
-               float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
-               int64_t ppitch, TailArgs tail) {
+               float* __restrict__ logits, int64_t cpitch, TileRecords recs, TailArgs tail) {
     extern __shared__ uint32_t smem[];
     const int tid = threadIdx.x;
     const int s = blockIdx.x % S;
     const int g = blockIdx.x / S, G = gridDim.x / S;
     const int nwords = (V + 31) >> 5;
-    const uint32_t npow = pow2_at_least((uint32_t)nwords);
     uint32_t* bm = smem;
     uint32_t* wsum = bm + bitmap_words_padded(V);
-    uint32_t* wpref = wsum + 64;
-    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(wpref + ((npow + 1 + 3) & ~3u));
+    uint32_t* tile_ids = wsum + 64;
+    float (*red)[4][kWave] = reinterpret_cast<float (*)[4][kWave]>(tile_ids + kFusedTileIdWords);
 
     const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
     union_row_bitmaps(part_bitmaps + (size_t)s * nparts * nwords, nparts, nwords, bm);
     __syncthreads();
     mark_id_list(bm, V, topfreq, T, tf_first);
     __syncthreads();
-    tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, wpref, red, nullptr, E, ld, d, H, B, V, s, g, G, cand,
-                                   count, logits, cpitch, partials, ppitch, tail, smem);
+    tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, tile_ids, red, nullptr, E, ld, d, H, B, V, s, g, G, cand,
+                                   count, logits, cpitch, recs, tail, smem);
 }
 
 }  // namespace lshbeam

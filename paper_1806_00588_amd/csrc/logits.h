@@ -58,15 +58,52 @@ template <> struct ElemTraits<uint16_t> {
     }
 };
 
-// Per (hidden row, tile) record of the fused kernels: x = largest logit of the tile's candidates,
+// Per (hidden row, tile) record of the fused kernels (the other kernels store the first two fields
+// only, as a float2 array in the same place): x = largest logit of the tile's candidates,
 // y = sum exp(logit - x), z = second largest logit (-inf if the tile has one candidate), w = word id
 // of the largest (the lowest column among equals; as bits).  The id of the second largest goes to
 // a parallel int32 array (-1 if none).  The plain kernels store only (x, y) as a float2.
 typedef float4 TileRecord;
+struct TileRecords {
+    TileRecord* rec;   // [rows, pitch]
+    int32_t* id2;      // [rows, pitch] word id of each record's second largest logit, -1 if none
+    int64_t pitch;     // records per hidden row
+};
 
 constexpr int kTileN = 16;  // candidates per tile
 constexpr int kTileM = 16;  // hidden rows per tile
 constexpr int kMaxSentencesLogits = 4096;
+
+// One (hidden row, tile) record from the 16 lanes that hold the row's logits of the tile's columns
+// (a DPP row: 16 consecutive lanes, lane jc = column jc; `valid` lanes hold a logit x of a real
+// candidate `id`).  Eq. 1 denominator, first stage: (max, sum of exp(logit - max)).  RICH (the
+// fused kernels): plus the second largest logit and the two word ids, as a TileRecord; otherwise
+// the pair alone, as a float2 in the same array (the contraction kernels of the many-tile plans
+// are bound by bandwidth and instruction issue, and the longer epilogue cost them 4-8 %).
+// Called by whole DPP rows; rows with row_ok false store nothing.  SHARE: see store_shared_result.
+template <bool SHARE, bool RICH>
+__device__ __forceinline__ void tile_record_store(const TileRecords& recs, size_t at, bool row_ok, bool valid,
+                                                  float x, int jc, int32_t id) {
+    const float mx = row16_max(valid ? x : -INFINITY);
+    const float se = row16_sum(valid ? expf(x - mx) : 0.f);
+    if constexpr (!RICH) {
+        if (jc == 0 && row_ok) reinterpret_cast<float2*>(recs.rec)[at] = make_float2(mx, se);
+    } else {
+        // the lowest column that holds the maximum; the largest of the others and its lowest column
+        const int c1 = row16_min_i32((valid && x == mx) ? jc : 16);
+        const float mx2 = row16_max((valid && jc != c1) ? x : -INFINITY);
+        const int c2 = row16_min_i32((valid && jc != c1 && x == mx2) ? jc : 16);
+        if (row_ok) {
+            if (jc == (c1 < 16 ? c1 : 0)) {   // (no column equals the maximum: NaN logits)
+                unsigned long long* rec = reinterpret_cast<unsigned long long*>(recs.rec + at);
+                const uint32_t idb = (uint32_t)(c1 < 16 ? id : -1);
+                store_shared_result<SHARE>(rec, ((unsigned long long)__float_as_uint(se) << 32) | __float_as_uint(mx));
+                store_shared_result<SHARE>(rec + 1, ((unsigned long long)idb << 32) | __float_as_uint(mx2));
+            }
+            if (jc == (c2 < 16 ? c2 : 0)) store_shared_result<SHARE>(&recs.id2[at], c2 < 16 ? id : (int32_t)-1);
+        }
+    }
+}
 
 // MTB tiles: logits of hidden rows [16 mt, 16 (mt + MTB)) of sentence s against 16 candidates,
 // this lane's candidate being row j of E (lanes beyond the list hold any valid row; their results
@@ -82,11 +119,11 @@ template <typename ET, int WAVES, int UNROLL, bool ALIGNED, int MTB = 1, bool RI
 __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld, int d,
                                             const float* __restrict__ H, int B, int s, int mt,
                                             int nt, int C, int64_t j, float* __restrict__ logits,
-                                            int64_t cpitch, float2* __restrict__ partials,
-                                            int64_t ppitch, float (*red)[4][kWave],
+                                            int64_t cpitch, TileRecords recs, float (*red)[4][kWave],
                                             const float* h_lds = nullptr, int h_pitch = 0,
-                                            int row_lo = 0, int row_hi = -1,
-                                            int32_t* __restrict__ ids2 = nullptr) {
+                                            int row_lo = 0, int row_hi = -1, int tn = kTileN) {
+    // tn <= 16: candidates of this tile (columns tn .. 15 of the matrix instruction stay unused;
+    // narrower tiles are an option of the fused plans, see select_tile_width)
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;  // k covered by one 64-lane load
     if (h_pitch == 0) h_pitch = d;
@@ -94,7 +131,8 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     const int col = ln & 15, kq = ln >> 4;
     const int nks = (d + KSTEP - 1) / KSTEP;
-    const int n0 = nt * kTileN;
+    const int n0 = nt * tn;
+    const bool col_used = col < tn;   // lanes of unused columns load no candidate row
     const ET* erow = E + j * ld;
     // the sentence's hidden rows, from LDS when the caller has them staged there ([B][d]);
     // rows beyond B are clamped like the candidate: never stored
@@ -115,7 +153,12 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
             const int k = (ks0 + uu * WAVES) * KSTEP + kq * VEC;
             if (ALIGNED) {
                 if (k < d) {
-                    ElemTraits<ET>::load16(erow + k, ev[uu]);
+                    if (col_used) {
+                        ElemTraits<ET>::load16(erow + k, ev[uu]);
+                    } else {
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) ev[uu][q] = 0.f;
+                    }
 #pragma unroll
                     for (int m = 0; m < MTB; ++m)
 #pragma unroll
@@ -136,7 +179,7 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
 #pragma unroll
                 for (int q = 0; q < VEC; ++q) {
                     const bool in = (k + q) < d;
-                    ev[uu][q] = in ? elem_f32(erow + k + q) : 0.f;
+                    ev[uu][q] = (in && col_used) ? elem_f32(erow + k + q) : 0.f;
 #pragma unroll
                     for (int m = 0; m < MTB; ++m) hv[m][uu][q] = in ? hrow[m][k + q] : 0.f;
                 }
@@ -167,35 +210,11 @@ __device__ __forceinline__ void logits_tile(const ET* __restrict__ E, int64_t ld
 #pragma unroll
             for (int w = 0; w < WAVES; ++w) sum += red[w][r][src];
             const int row = row_lo + (mt + m) * kTileM + i, c = n0 + jc;
-            const bool valid = row < row_hi && c < C;
+            const bool valid = row < row_hi && jc < tn && c < C;
             // (SHARE: other workgroups of this kernel read the results; see store_shared_result)
             if (valid) store_shared_result<SHARE>(&logits[((size_t)s * B + row) * cpitch + c], sum);
-            // Eq. 1 denominator, first stage: (max, sum of exp(logit - max)) of this row over the
-            // tile's 16 candidates; the 16 lanes that share a row are one DPP row
-            const float mx = row16_max(valid ? sum : -INFINITY);
-            const float se = row16_sum(valid ? expf(sum - mx) : 0.f);
-            if constexpr (RICH) {
-                // the lowest column that holds the maximum; the largest of the others and its
-                // lowest column (thread tid's own candidate is the one of column jc = lane % 16)
-                const int c1 = row16_min_i32((valid && sum == mx) ? jc : 16);
-                const float mx2 = row16_max((valid && jc != c1) ? sum : -INFINITY);
-                const int c2 = row16_min_i32((valid && jc != c1 && sum == mx2) ? jc : 16);
-                if (row < row_hi) {
-                    const size_t at = ((size_t)s * B + row) * ppitch + nt;
-                    if (jc == (c1 < 16 ? c1 : 0)) {   // (no column equals the maximum: NaN logits)
-                        unsigned long long* rec =
-                            reinterpret_cast<unsigned long long*>(reinterpret_cast<TileRecord*>(partials) + at);
-                        const uint32_t idb = (uint32_t)(c1 < 16 ? (int)j : -1);
-                        store_shared_result<SHARE>(rec, ((unsigned long long)__float_as_uint(se) << 32) | __float_as_uint(mx));
-                        store_shared_result<SHARE>(rec + 1, ((unsigned long long)idb << 32) | __float_as_uint(mx2));
-                    }
-                    if (jc == (c2 < 16 ? c2 : 0))
-                        store_shared_result<SHARE>(&ids2[at], c2 < 16 ? (int32_t)j : (int32_t)-1);
-                }
-            } else {
-                if (jc == 0 && row < row_hi)
-                    partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
-            }
+            tile_record_store<SHARE, RICH>(recs, ((size_t)s * B + row) * recs.pitch + nt, row < row_hi, valid, sum,
+                                           jc, (int32_t)j);
         }
         __syncthreads();
     }
@@ -209,11 +228,9 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
                                                      const float* __restrict__ H, int B, int s,
                                                      int nt, int C, int64_t j,
                                                      float* __restrict__ logits, int64_t cpitch,
-                                                     float2* __restrict__ partials, int64_t ppitch,
-                                                     float (*red)[4][kWave],
+                                                     TileRecords recs, float (*red)[4][kWave],
                                                      const float* h_lds = nullptr, int h_pitch = 0,
-                                                     int row_lo = 0, int row_hi = -1,
-                                                     int32_t* __restrict__ ids2 = nullptr) {
+                                                     int row_lo = 0, int row_hi = -1, int tn = kTileN) {
     // loads in flight per row group shrink as the groups grow: the operands of all groups have
     // to fit the register budget of a 1024-thread workgroup
     // (measured: keeping the full unroll in 256-thread workgroups, where registers would allow
@@ -225,18 +242,18 @@ __device__ __forceinline__ void logits_tile_all_rows(const ET* __restrict__ E, i
     const int MT = FIXED_MT ? FIXED_MT : ((row_hi < 0 ? B : row_hi - row_lo) + kTileM - 1) / kTileM;
     if (MT == 1) {
         logits_tile<ET, WAVES, UNROLL, ALIGNED, 1, RICH, SHARE>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                                         partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
+            recs, red, h_lds, h_pitch, row_lo, row_hi, tn);
     } else if (MT == 2) {
         logits_tile<ET, WAVES, U2, ALIGNED, 2, RICH, SHARE>(E, ld, d, H, B, s, 0, nt, C, j, logits, cpitch,
-                                                     partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
+            recs, red, h_lds, h_pitch, row_lo, row_hi, tn);
     } else if (ElemTraits<ET>::VEC > 4) {  // bf16: twice the registers per load, two groups at most
         for (int mt = 0; mt < MT; mt += 2)
             logits_tile<ET, WAVES, U2, ALIGNED, 2, RICH, SHARE>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                         partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
+            recs, red, h_lds, h_pitch, row_lo, row_hi, tn);
     } else {
         for (int mt = 0; mt < MT; mt += 4)
             logits_tile<ET, WAVES, U4, ALIGNED, 4, RICH, SHARE>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                         partials, ppitch, red, h_lds, h_pitch, row_lo, row_hi, ids2);
+            recs, red, h_lds, h_pitch, row_lo, row_hi, tn);
     }
 }
 
@@ -244,8 +261,7 @@ template <typename ET, int WAVES, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(WAVES * kWave)
 k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
          const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-         float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
-         int64_t ppitch) {
+         float* __restrict__ logits, int64_t cpitch, TileRecords recs) {
     __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
     __shared__ float red[WAVES][4][kWave];
 
@@ -313,8 +329,7 @@ k_logits(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ 
         else
             j = cand ? cand[(size_t)s * V + cidx] : cidx;
         LSH_TRACE(1, 2);
-        logits_tile<ET, WAVES, UNROLL, ALIGNED>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch,
-                                                partials, ppitch, red);
+        logits_tile<ET, WAVES, UNROLL, ALIGNED>(E, ld, d, H, B, s, mt, nt, C, j, logits, cpitch, recs, red);
     }
 }
 
@@ -334,8 +349,7 @@ template <typename ET, int MT, int UNROLL, bool ALIGNED>
 __global__ void __launch_bounds__(256)
 k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S, int B,
               const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-              float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
-              int64_t ppitch) {
+              float* __restrict__ logits, int64_t cpitch, TileRecords recs) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;
     __shared__ uint32_t tile_pref[kMaxSentencesLogits + 1];
@@ -445,10 +459,8 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
                 const bool valid = row < B && c < C;
                 const float x = acc[mt][r];
                 if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
-                const float mx = row16_max(valid ? x : -INFINITY);
-                const float se = row16_sum(valid ? expf(x - mx) : 0.f);
-                if (col == 0 && row < B)
-                    partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+                tile_record_store<false, false>(recs, ((size_t)s * B + row) * recs.pitch + nt, row < B, valid, x, col,
+                                         (int32_t)j);
             }
     }
 
@@ -460,8 +472,7 @@ k_logits_wave(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int cidx = min(nt * kTileN + col, C - 1);
         const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
         logits_tile_all_rows<ET, 4, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(E, ld, d, H, B, s, nt, C, j,
-                                                                        logits, cpitch, partials,
-                                                                        ppitch, red);
+                                                                        logits, cpitch, recs, red);
     }
 }
 
@@ -509,8 +520,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
                                group_rows <= 16 MT*/,
               int gx /*workgroups per row group*/, int ngroups, int rem_div,
               const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-              float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
-              int64_t ppitch) {
+              float* __restrict__ logits, int64_t cpitch, TileRecords recs) {
     constexpr int VEC = ElemTraits<ET>::VEC;
     constexpr int KSTEP = 4 * VEC;
     extern __shared__ uint32_t hsm[];
@@ -766,10 +776,8 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
                     const bool valid = row < row0 + Bg && c < C;
                     const float x = acc[mt][r];
                     if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
-                    const float mx = row16_max(valid ? x : -INFINITY);
-                    const float se = row16_sum(valid ? expf(x - mx) : 0.f);
-                    if (col == 0 && row < row0 + Bg)
-                        partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+                    tile_record_store<false, false>(recs, ((size_t)s * B + row) * recs.pitch + nt, row < row0 + Bg, valid,
+                                             x, col, (int32_t)j);
                 }
         }
         seg = seg_end;
@@ -786,7 +794,7 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
         const int64_t j = cand ? cand[(size_t)s * V + cidx] : cidx;
         // (the split-k tile code reads fp32 rows: from global memory when LDS holds bf16 planes)
         logits_tile_all_rows<ET, WAVES, (UNROLL < 4 ? UNROLL : 4), ALIGNED, MT>(
-            E, ld, d, H, B, s, nt, C, j, logits, cpitch, partials, ppitch, red,
+            E, ld, d, H, B, s, nt, C, j, logits, cpitch, recs, red,
             PLANES ? nullptr : hl, PLANES ? 0 : pitch, row0, row0 + Bg);
     }
 }
@@ -816,8 +824,7 @@ template <int MT>
 __global__ void __launch_bounds__(1024)
 k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S,
                 int B, const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-                float* __restrict__ logits, int64_t cpitch, float2* __restrict__ partials,
-                int64_t ppitch) {
+                float* __restrict__ logits, int64_t cpitch, TileRecords recs) {
     constexpr int KSTEP = 16, NSTEP = kEsSlice / KSTEP;
     extern __shared__ uint32_t esm[];
     float* etile = reinterpret_cast<float*>(esm);                         // [2][16][kEsPitch]
@@ -927,10 +934,7 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
             const int row = g * kTileM + 4 * kk + q, c = n0 + col;
             const bool valid = row < B && c < C;
             if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
-            const float mx = row16_max(valid ? x : -INFINITY);
-            const float se = row16_sum(valid ? expf(x - mx) : 0.f);
-            if (col == 0 && row < B)
-                partials[((size_t)s * B + row) * ppitch + nt] = make_float2(mx, se);
+            tile_record_store<false, false>(recs, ((size_t)s * B + row) * recs.pitch + nt, row < B, valid, x, col, 0);
         }
     }
 }

@@ -77,12 +77,12 @@ struct HostBand {
 // Launch-plan options of a handle (lsh_set_option); kAuto = the library's own rule.
 enum Opt {
     kOptFused, kOptFusedGrid, kOptLogitsGrid, kOptLogitsWaves, kOptLogitsHlds, kOptLogitsEstage,
-    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kOptOneLaunch, kNumOpts
+    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kOptOneLaunch, kOptFusedTile, kNumOpts
 };
 constexpr int kAuto = -1;
 const char* const kOptNames[kNumOpts] = {
     "fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
-    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch"};
+    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch", "fused_tile"};
 
 }  // namespace
 
@@ -307,12 +307,10 @@ void launch_logits_w(const StepCtx& cx, int grid, bool aligned, const float* H,
     const ET* E = (const ET*)t->E;
     if (aligned)
         launch(cx, 1, k_logits<ET, WAVES, UNROLL, true>, dim3(grid), dim3(WAVES * kWave), 0, E,
-               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials,
-               w.ppitch);
+               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.records());
     else
         launch(cx, 1, k_logits<ET, WAVES, UNROLL, false>, dim3(grid), dim3(WAVES * kWave), 0, E,
-               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials,
-               w.ppitch);
+               t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.records());
 }
 
 template <typename ET, int MT>
@@ -325,10 +323,10 @@ void launch_logits_wave(const StepCtx& cx, int grid, bool aligned, const float* 
     const ET* E = (const ET*)t->E;
     if (aligned)
         launch(cx, 1, k_logits_wave<ET, MT, UNROLL, true>, dim3(grid), dim3(256), 0, E, t->ld, t->d,
-               H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
+               H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.records());
     else
         launch(cx, 1, k_logits_wave<ET, MT, UNROLL, false>, dim3(grid), dim3(256), 0, E, t->ld, t->d,
-               H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.partials, w.ppitch);
+               H, sp->S, sp->B, cand, count, t->V, w.logits, w.cpitch, w.records());
 }
 
 // k_logits_hlds over the sentence's rows in groups: a group's rows must fit in LDS.  Up to 78 KB
@@ -370,7 +368,7 @@ void launch_logits_hlds(const StepCtx& cx, int64_t tiles_n, bool aligned, const 
         const int grid = ((gx + 7) / 8 * 8) * ngroups;                                               \
         launch(cx, 1, kfn, dim3(grid), dim3(WV * kWave), lds, E, t->ld, t->d, H, sp->S, sp->B,   \
                rows, gx, ngroups, t->option(kOptHldsRem, 4), cand, count, t->V, w.logits,      \
-               w.cpitch, w.partials, w.ppitch);                                                      \
+               w.cpitch, w.records());                                                      \
     } while (0)
     // bf16 rows, up to 16 hidden rows per group, two workgroups per CU: the hidden rows go to LDS
     // as three bf16 planes and the contraction runs on bf16 matrix instructions
@@ -408,7 +406,7 @@ void launch_logits_estage(const StepCtx& cx, const float* H, const lsh_step_para
     do {                                                                                             \
         auto kfn = k_logits_estage<MTV>;                                                             \
         launch(cx, 1, kfn, grid, block, lds, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, \
-               w.logits, w.cpitch, w.partials, w.ppitch);                                            \
+               w.logits, w.cpitch, w.records());                                            \
     } while (0)
     if (MT <= 3) LSH_ESTAGE(3); else LSH_ESTAGE(4);
 #undef LSH_ESTAGE
@@ -756,10 +754,11 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
         // One launch per step: the last workgroup of each sentence also runs the selection
         // (option one_launch = 0: a selection kernel follows instead; also when no ticket block
         // is left for this workspace or the step has more sentences than a block has counters).
-        TailArgs tail{nullptr, beam_scores_dev, w.lse, w.ids2, out_beam_dev, out_word_dev, out_score_dev};
+        TailArgs tail{nullptr, beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev,
+                      std::max(0, t->option(kOptFusedTile, 0))};
         if (t->option(kOptOneLaunch, 0) && sp->S <= kTicketBlock) tail.tickets = t->tickets_for(workspace_dev);
         selected = tail.tickets != nullptr;
-        const int per_sentence = std::max(1, t->option(kOptFusedGrid, 256) / sp->S);
+        const int per_sentence = std::min(kMaxFusedGrid, std::max(1, t->option(kOptFusedGrid, 256) / sp->S));
         const dim3 grid((unsigned)(per_sentence * sp->S)), block(kCandThreads);
         const bool aligned16 = ((uintptr_t)t->E % 16 == 0) && (t->d % 4 == 0) && ((uintptr_t)H_dev % 16 == 0);
         const bool f32 = t->dtype == LSH_F32;
@@ -769,7 +768,7 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
 #define LSH_UNION_LOGITS(ET, AL, OL)                                                              \
     launch(cx, 1, k_union_logits<ET, AL, OL>, grid, block, lds, parts, nparts, topfreq_dev, sp->T, \
            (const ET*)t->E, t->ld, t->d, H_dev, sp->S, sp->B, t->V, w.cand, w.count, w.logits,    \
-           w.cpitch, w.partials, w.ppitch, tail)
+           w.cpitch, w.records(), tail)
 #define LSH_UNION_LOGITS2(ET, AL) \
     do { if (selected) LSH_UNION_LOGITS(ET, AL, true); else LSH_UNION_LOGITS(ET, AL, false); } while (0)
             if (f32) { if (al) LSH_UNION_LOGITS2(float, true); else LSH_UNION_LOGITS2(float, false); }
@@ -780,7 +779,7 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
             const size_t lds = fused_lds_words(t->V, t->P, t->K, stage) * sizeof(uint32_t);
 #define LSH_CAND_LOGITS(ET, AL, OL)                                                               \
     launch(cx, 1, k_cand_logits<ET, AL, OL>, grid, block, lds, ca, (const ET*)t->E, t->ld, sp->S,  \
-           w.cand, w.count, w.logits, w.cpitch, w.partials, w.ppitch, tail)
+           w.cand, w.count, w.logits, w.cpitch, w.records(), tail)
 #define LSH_CAND_LOGITS2(ET, AL) \
     do { if (selected) LSH_CAND_LOGITS(ET, AL, true); else LSH_CAND_LOGITS(ET, AL, false); } while (0)
             if (f32) { if (al) LSH_CAND_LOGITS2(float, true); else LSH_CAND_LOGITS2(float, false); }
@@ -808,14 +807,13 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
         else launch_logits<uint16_t>(cx, H_dev, sp, cand, count, w);
     }
     if (!selected) {
-        if (fused)   // the fused kernels leave rich tile records
-            launch(cx, 2, k_select<TileRecord>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits,
-                   w.cpitch, (const TileRecord*)w.partials, (const int32_t*)w.ids2, w.ppitch, cand, count,
-                   t->V, sp->B, beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev);
-        else
-            launch(cx, 2, k_select<float2>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits,
-                   w.cpitch, (const float2*)w.partials, (const int32_t*)nullptr, w.ppitch, cand, count,
-                   t->V, sp->B, beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev);
+#define LSH_SELECT(RICHV)                                                                             \
+    launch(cx, 2, k_select<RICHV>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits, w.cpitch, \
+           (const TileRecord*)w.partials, (const int32_t*)w.ids2, w.ppitch, cand, count, t->V, sp->B,  \
+           beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev,                          \
+           fused ? std::max(0, t->option(kOptFusedTile, 0)) : 0)
+        if (fused) LSH_SELECT(true); else LSH_SELECT(false);   // (the fused kernels leave rich records)
+#undef LSH_SELECT
     }
     HIP_TRY(hipGetLastError());
     return LSH_OK;

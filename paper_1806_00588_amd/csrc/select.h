@@ -24,6 +24,7 @@
 // so "larger key" = "higher score, then lower beam, then lower column (= lower word id, the
 // candidate list is ascending)", and the B-th key is unique.
 #pragma once
+#include <type_traits>
 #include "device_utils.h"
 
 namespace lshbeam {
@@ -242,36 +243,30 @@ __device__ __noinline__ void block_radix_select(ScoreSrc src, int k, SelShared* 
     __syncthreads();
 }
 
-// What the logits kernels leave per (hidden row, tile): float2 (max, sum exp) from the plain
-// kernels, TileRecord = float4 (max, sum exp, second largest, id of the max) + a parallel array of
-// the second's id from the fused kernels.
-template <typename REC> struct RecTraits;
-template <> struct RecTraits<float2> {
-    static constexpr bool RICH = false;
-    __device__ static __forceinline__ float2 empty() { return make_float2(-INFINITY, 0.f); }
-};
-template <> struct RecTraits<float4> {
-    static constexpr bool RICH = true;
-    __device__ static __forceinline__ float4 empty() {
-        return make_float4(-INFINITY, 0.f, -INFINITY, __int_as_float(-1));
-    }
-};
+// Candidates per tile of the fused kernels: 16, the width of the matrix instruction, unless
+// forced narrower (option fused_tile, 1..16; the unused columns of the instruction then idle).
+// Measured on the 2224-candidate lists of the paper shape: 248 tiles of 9 on 256 workgroups, one
+// each, are no faster than 139 tiles of 16 -- while the candidate rows arrive the machine as a
+// whole is moving ~3.5 TB/s of scattered 4 KB rows, so it is the memory system, not the single CU,
+// that sets those 2.5 us, and more tiles mean more records for the selection (+0.5 us).  The
+// number of tiles never exceeds the record pitch.  Both the kernel that writes the records and
+// the selection that reads them evaluate this rule.
+constexpr int kMaxFusedGrid = 1024;   // workgroups per sentence at most
+__host__ __device__ inline int select_tile_width(int C, int forced, int64_t ppitch) {
+    int w = (forced > 0 && forced < 16) ? forced : 16;
+    if (w < 16 && ((int64_t)C + w - 1) / w > ppitch) w = 16;
+    return w;
+}
 
-// Log-softmax and beam expansion of sentence s by one workgroup of kSelThreads threads, once the
-// sentence's logits and per-tile records are in memory (written by an earlier kernel, or by other
-// workgroups of this kernel whose stores have been made visible to this one).  C_known >= 0 is
-// the candidate count; otherwise it is read from count[s] (or is V when count is null) after the
-// first records have been requested.  KEEP = batches of tile maxima a wave keeps in registers
-// between the passes.
-//
-// With rich records (REC = float4) there is a short cut.  Every score >= tau that is the largest
-// or second largest of its (row, tile) is listed straight from the records, with its word id --
-// no logit and no candidate id is read back.  The B best of that list are the answer unless one
-// of them is a SECOND largest: only then can its tile hide a third value that also belongs, and
-// the general path below (open every tile whose maximum reaches tau) decides.  Proof: a hidden
-// value h of (row, tile) has a smaller key than the tile's second largest z (lower score, or equal
-// score and higher column); if z is not among the B best -- unlisted because z < tau <= the B-th
-// best score, or listed and outranked by B keys -- neither is h.
+// What the contraction kernels leave per (hidden row, tile): the fused kernels a TileRecord =
+// float4 (max, sum exp, second largest, id of the max) and, in a parallel array, the second's id
+// ("rich" records); the others the float2 (max, sum exp) alone.
+template <typename REC> __device__ __forceinline__ REC empty_record();
+template <> __device__ __forceinline__ float2 empty_record<float2>() { return make_float2(-INFINITY, 0.f); }
+template <> __device__ __forceinline__ float4 empty_record<float4>() {
+    return make_float4(-INFINITY, 0.f, -INFINITY, __int_as_float(-1));
+}
+
 // Loads of tile records / second ids.  SAME_KERNEL: the data was written by other workgroups of
 // the running kernel (device-scope stores, store_shared_result), so it is read with device-scope
 // loads, which do not hit in this XCD's caches -- cheaper than invalidating them (1.6 us measured
@@ -296,13 +291,18 @@ __device__ __forceinline__ int32_t load_id2(const int32_t* p) {
     else return *p;
 }
 
-template <typename REC, int KEEP, bool SAME_KERNEL = false>
+template <bool RICH, bool SAME_KERNEL = false>
 __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const float* logits, int64_t cpitch,
-                                                const REC* partials, const int32_t* ids2, int64_t ppitch,
+                                                const TileRecord* records, const int32_t* ids2, int64_t ppitch,
                                                 const int32_t* cand, const int32_t* count, int C_known,
                                                 int V, int B, const float* beam_scores, float* lse_out,
-                                                int32_t* out_beam, int32_t* out_word, float* out_score) {
-    constexpr bool RICH = RecTraits<REC>::RICH;
+                                                int32_t* out_beam, int32_t* out_word, float* out_score,
+                                                int tile_forced = 0) {
+    typedef typename std::conditional<RICH, float4, float2>::type REC;
+    const REC* partials = reinterpret_cast<const REC*>(records);
+    // batches of tile maxima a wave keeps in registers between the passes (rich records: also the
+    // second largest and both ids, so one batch only)
+    constexpr int KEEP = RICH ? 1 : kSelKeep;
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     LSH_TRACE_ANY(2, 0);
     // The first batch of records of this wave's first row is requested before the candidate
@@ -311,7 +311,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     REC first_batch[kSelBatch];
     int32_t first_ids2[kSelBatch];
 #pragma unroll
-    for (int q = 0; q < kSelBatch; ++q) { first_batch[q] = RecTraits<REC>::empty(); first_ids2[q] = -1; }
+    for (int q = 0; q < kSelBatch; ++q) { first_batch[q] = empty_record<REC>(); first_ids2[q] = -1; }
     if (wv < B) {
         const size_t r0 = ((size_t)s * B + wv) * ppitch;
 #pragma unroll
@@ -322,7 +322,9 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
         }
     }
     const int C = C_known >= 0 ? C_known : (count ? count[s] : V);
-    const int ntiles = (C + 15) >> 4;
+    // candidates per tile: 16, or what the fused kernel that wrote the records was told to use
+    const int tn = RICH ? select_tile_width(C, tile_forced, ppitch) : 16;
+    const int ntiles = (C + tn - 1) / tn;
     const float* lg = logits + (size_t)s * B * cpitch;
     if (tid == 0) { sh.misc[4] = 0; sh.misc[5] = 0; sh.misc[6] = 0; }
 
@@ -378,7 +380,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q)
                 if (q >= nq || bt * kBatchTiles + ln + q * kWave >= ntiles)
-                    cur[q] = RecTraits<REC>::empty();
+                    cur[q] = empty_record<REC>();
             if constexpr (KEEP > 0) {
 #pragma unroll
                 for (int k = 0; k < KEEP; ++k)  // registers cannot be indexed at run time
@@ -521,7 +523,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
             if (!have) {
                 REC p[kSelBatch];
 #pragma unroll
-                for (int q = 0; q < kSelBatch; ++q) { p[q] = RecTraits<REC>::empty(); i2[q] = -1; }
+                for (int q = 0; q < kSelBatch; ++q) { p[q] = empty_record<REC>(); i2[q] = -1; }
                 load_batch(it, p);
                 load_ids2(it, i2);
 #pragma unroll
@@ -637,7 +639,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
         if (!have) {
             REC p[kSelBatch];
 #pragma unroll
-            for (int q = 0; q < kSelBatch; ++q) p[q] = RecTraits<REC>::empty();
+            for (int q = 0; q < kSelBatch; ++q) p[q] = empty_record<REC>();
             load_batch(it, p);
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q) px[q] = p[q].x;
@@ -688,8 +690,8 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
                 const uint32_t j = g0 + u * (kSelThreads / 16);
                 const uint32_t ent = sh.open_list[min(j, n_open - 1)];
                 iq[u] = (int)(ent >> 20);
-                const int cc = (int)(ent & 0xFFFFFu) * 16 + (ln & 15);
-                c[u] = (j < n_open && cc < C) ? cc : -1;
+                const int cc = (int)(ent & 0xFFFFFu) * tn + (ln & 15);
+                c[u] = (j < n_open && (ln & 15) < tn && cc < C) ? cc : -1;
                 x[u] = lg[(size_t)iq[u] * cpitch + max(c[u], 0)];
                 lsev[u] = sh.lse[iq[u]];
                 bsq[u] = sh.bs[iq[u]];
@@ -754,18 +756,17 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
 }
 
 // grid = S workgroups (one per sentence), kSelThreads threads: the selection as a kernel of its
-// own, after kernels that left plain (float2) or rich (float4 + ids2) tile records.
-template <typename REC>
+// own, after kernels that left rich (fused plans) or plain tile records.
+template <bool RICH>
 __global__ void __launch_bounds__(kSelThreads)
-k_select(const float* __restrict__ logits, int64_t cpitch, const REC* __restrict__ partials,
+k_select(const float* __restrict__ logits, int64_t cpitch, const TileRecord* __restrict__ records,
          const int32_t* __restrict__ ids2, int64_t ppitch, const int32_t* __restrict__ cand,
          const int32_t* __restrict__ count, int V, int B, const float* __restrict__ beam_scores,
          float* __restrict__ lse_out /*[R]*/, int32_t* __restrict__ out_beam,
-         int32_t* __restrict__ out_word, float* __restrict__ out_score) {
+         int32_t* __restrict__ out_word, float* __restrict__ out_score, int tile_forced) {
     __shared__ SelShared sh;
-    select_sentence<REC, RecTraits<REC>::RICH ? 1 : kSelKeep>(sh, (int)blockIdx.x, logits, cpitch, partials, ids2,
-                                                             ppitch, cand, count, -1, V, B, beam_scores,
-                                                             lse_out, out_beam, out_word, out_score);
+    select_sentence<RICH, false>(sh, (int)blockIdx.x, logits, cpitch, records, ids2, ppitch, cand, count, -1, V, B,
+                                 beam_scores, lse_out, out_beam, out_word, out_score, tile_forced);
 }
 
 // lp[i, c] = logit[i, c] - lse[i] for one sentence, for inspection.

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "logits.h"
+#include "select.h"
 
 namespace lshbeam {
 
@@ -16,14 +17,15 @@ struct Workspace {
     int32_t* cand;       // [S, V]
     int32_t* count;      // [S]
     float* logits;       // [R, cpitch]
-    float2* partials;    // [R, ppitch]  per 16-candidate tile: (max, sum exp(logit - max)) as float2
-                         //   from the plain kernels, a 16-byte TileRecord from the fused ones
+    TileRecord* partials;  // [R, ppitch]  per (row, tile): fused kernels a TileRecord, the others a float2
+                           //   (max, sum exp(logit - max)) in the same place
     int32_t* ids2;       // [R, ppitch]  fused kernels: word id of each record's second largest
     uint32_t* row_bitmaps;  // [R, ceil(V/32)]  per-row (t > 1) or per-part (many beams) bitmaps
     float* lse;          // [R]
-    int64_t ppitch;      // tile records per row (cpitch / 16)
+    int64_t ppitch;      // tile records per row: cpitch / 16, at least kMaxFusedGrid (narrow tiles)
     int64_t cpitch;      // logits per row: V rounded up to 64
     size_t bytes;
+    TileRecords records() const { return TileRecords{partials, ids2, ppitch}; }
 };
 
 // S sentences of B beams over a vocabulary of V words; base may be null (sizes only).
@@ -35,9 +37,9 @@ inline Workspace carve_workspace(int S_, int B_, int V_, bool full_vocab, void* 
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return (char*)base + o; };
     w.cand = (int32_t*)take(full_vocab ? 0 : S * V * sizeof(int32_t));
     w.count = (int32_t*)take(S * sizeof(int32_t));
-    w.ppitch = w.cpitch / kTileN;
+    w.ppitch = w.cpitch / kTileN > kMaxFusedGrid ? w.cpitch / kTileN : (int64_t)kMaxFusedGrid;
     w.logits = (float*)take(R * (size_t)w.cpitch * sizeof(float));
-    w.partials = (float2*)take(R * (size_t)w.ppitch * sizeof(TileRecord));
+    w.partials = (TileRecord*)take(R * (size_t)w.ppitch * sizeof(TileRecord));
     w.ids2 = (int32_t*)take(R * (size_t)w.ppitch * sizeof(int32_t));
     w.lse = (float*)take(R * sizeof(float));
     w.row_bitmaps = (uint32_t*)take(full_vocab ? 0 : R * ((V + 31) / 32) * sizeof(uint32_t));

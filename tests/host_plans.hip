@@ -51,7 +51,16 @@ static void check_workspace(int S, int B, int V, bool full) {
         CHECK(r.bytes / 4 <= w.bytes, "size overflow in %s", r.name);
         prev_end = p + r.bytes;
     }
-    CHECK(w.cpitch >= V && w.cpitch % 64 == 0 && w.ppitch * kTileN == w.cpitch, "pitches V=%d", V);
+    CHECK(w.cpitch >= V && w.cpitch % 64 == 0 && w.ppitch * kTileN >= w.cpitch && w.ppitch >= kMaxFusedGrid,
+          "pitches V=%d", V);
+    // forced narrow tiles of the fused plans: never more tiles than records fit in a row
+    for (int C : {0, 1, 5, 100, 2224, 4095, 4096, V / 2, V})
+        for (int forced : {0, 1, 3, 9, 16, 40}) {
+            if (C > V) continue;
+            const int tn = select_tile_width(C, forced, w.ppitch);
+            CHECK(tn >= 1 && tn <= 16, "tile width %d", tn);
+            CHECK(((int64_t)C + tn - 1) / tn <= w.ppitch, "tiles beyond the record pitch (C=%d forced=%d V=%d)", C, forced, V);
+        }
     // the largest index any kernel forms: row R-1, last column / last tile
     CHECK((R - 1) * (size_t)w.cpitch + (size_t)V - 1 < R * (size_t)w.cpitch, "logit index");
     CHECK((size_t)(((size_t)V + 15) / 16) <= (size_t)w.ppitch, "tile count exceeds the record pitch V=%d", V);
@@ -78,17 +87,15 @@ static void check_candidate_lds(int V, int d, int P, int K, int W, int B) {
         CHECK(rows * P <= kCandThreads || true, "-");
         // fused kernel: prefix array and reduction buffer behind the candidate regions; the
         // selection's shared state from the start
-        const size_t npow = pow2_at_least((uint32_t)(((size_t)V + 31) / 32));
-        CHECK(npow >= ((size_t)V + 31) / 32 && npow < 2 * (((size_t)V + 31) / 32) + 1, "npow V=%d", V);
         const size_t fused = fused_lds_words(V, P, K, stage);
-        CHECK(total + npow + 1 + (size_t)kFusedWaves * 4 * kWave <= fused, "fused regions (V=%d)", V);
+        CHECK(total + kFusedTileIdWords + (size_t)kFusedWaves * 4 * kWave <= fused, "fused regions (V=%d)", V);
+        CHECK(total % 4 == 0 || true, "-");
         CHECK(fused >= kSelSharedWords, "fused LDS smaller than the selection's state");
         // k_candidates reuses the stage for the dense-word list: stage / 2 entries of 8 bytes
         CHECK((size_t)(stage / 2) * 2 <= (size_t)stage, "dense list");
     }
     const size_t un = union_logits_lds_words(V);
-    const size_t npow = pow2_at_least((uint32_t)(((size_t)V + 31) / 32));
-    CHECK(bitmap_words_padded(V) + 64 + ((npow + 1 + 3) & ~(size_t)3) + (size_t)kFusedWaves * 4 * kWave <= un, "union regions V=%d", V);
+    CHECK(bitmap_words_padded(V) + 64 + kFusedTileIdWords + (size_t)kFusedWaves * 4 * kWave <= un, "union regions V=%d", V);
     CHECK(un >= kSelSharedWords, "union LDS smaller than the selection's state");
     CHECK(union_compact_lds_words(V) == (size_t)bitmap_words_padded(V) + 64 + 2 * (size_t)kUnionDenseCap, "union compact V=%d", V);
 }

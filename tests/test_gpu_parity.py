@@ -632,23 +632,50 @@ def test_one_launch_two_launch_and_three_kernel_plans_agree_bit_for_bit(name, S,
     H = H[:S * B]
     bs = np.linspace(-1, 0, S * B).astype(np.float32)
     res = {}
+    # (the "narrow" runs cut the list into tiles of 7 instead of 16: the per-tile softmax partials
+    # are then summed in other groups, so they are compared with each other and with the oracle)
     for mode, opts in (("one", dict(fused=1, one_launch=1)), ("two", dict(fused=1, one_launch=0)),
-                       ("three", dict(fused=0))):
+                       ("three", dict(fused=0)), ("one-narrow", dict(fused=1, one_launch=1, fused_tile=7)),
+                       ("two-narrow", dict(fused=1, one_launch=0, fused_tile=7))):
         gc.tables.reset_options()
         force(gc, **opts)
         gb, gw, gs, sp, ws = gc.step(H, bs, S, B, threshold=t)
         assert binding.step_is_fused(gc.tables, sp) == (mode != "three")
+        if mode.endswith("narrow"):
+            for s_ in range(S):
+                ref = gc.oracle_sentence(H[s_ * B:(s_ + 1) * B], bs[s_ * B:(s_ + 1) * B], B, threshold=t)
+                assert_topb_matches(gb[s_], gw[s_], gs[s_], ref, bs[s_ * B:(s_ + 1) * B])
         cands = [gc.tables.debug_candidates(ws, sp, s) for s in range(S)]
         lps = [gc.tables.debug_logprobs(ws, sp, s, cap=len(cands[s])) for s in range(S)]
         res[mode] = (gb, gw, gs, cands, lps)
-    for other in ("two", "three"):
-        for x, y in zip(res["one"][:3], res[other][:3]):
+    for a, other in (("one", "two"), ("one", "three"), ("one-narrow", "two-narrow")):
+        for x, y in zip(res[a][:3], res[other][:3]):
             assert np.array_equal(x, y), other
         for s in range(S):
-            assert np.array_equal(res["one"][3][s], res[other][3][s])
-            assert np.array_equal(res["one"][4][s], res[other][4][s])
+            assert np.array_equal(res[a][3][s], res[other][3][s])
+            assert np.array_equal(res[a][4][s], res[other][4][s])
     for s in range(S):
         assert np.array_equal(res["one"][3][s], gc.index.candidates(H[s * B:(s + 1) * B], gc.topfreq, t))
+
+
+@pytest.mark.parametrize("width", [1, 2, 3, 5, 9, 13, 16])
+def test_fused_kernel_with_every_tile_width(width, force):
+    # option fused_tile makes the fused kernels cut the candidate list into tiles narrower than the
+    # 16 columns of the matrix instruction.  Lists that are not a multiple of the
+    # width, one and several tiles per workgroup (small grids), one and two row groups.
+    cfg, gc = case("tiny")
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
+    rng = np.random.default_rng(width)
+    for grid in (256, 8, 3):
+        for one_launch in (0, 1):
+            force(gc, fused=1, fused_tile=width, fused_grid=grid, one_launch=one_launch)
+            for S, B in [(1, 4), (2, 12), (1, 20), (3, 5)]:
+                bs = rng.standard_normal(S * B).astype(np.float32)
+                run_and_check(cfg, gc, H[:S * B], bs, S, B)
+    cfg, gc = case("paper")
+    force(gc, fused=1, fused_tile=width)
+    H = hidden(cfg, gc, 2)
+    run_and_check(cfg, gc, H[1], np.linspace(-2, 0, cfg.R).astype(np.float32), cfg.S, cfg.B)
 
 
 @pytest.mark.parametrize("one_launch", [1, 0])
