@@ -228,6 +228,8 @@ lsh_status lsh_debug_logprobs(const lsh_tables* t, const void* workspace_dev,
  *   "logits_waves"   1 / 4 / 16: contraction driver (a wave per tile; k split over 4 or 16 waves)
  *   "logits_hlds"    0: the wave-per-tile driver keeps the hidden rows in global memory, not LDS
  *   "logits_estage"  0: 33..64 beams take the grouped driver instead of candidate rows through LDS
+ *   "estage_union"   0: sentences hashed in parts get their candidate list from a kernel of its own
+ *                    before that driver, instead of inside it
  *   "hlds_rem"       n: a last round of tiles filling at most 1/n of the waves is split over k (4)
  *   "logits_planes"  0: bf16 rows are widened to fp32 instead of meeting bf16 planes of H
  *   "hlds_rows"      16 / 32: hidden rows per group of the LDS-staged driver

@@ -26,7 +26,8 @@ EXPORTED_SYMBOLS = (
 
 OPTION_AUTO = -1
 OPTION_NAMES = ("fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
-                "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch", "fused_tile")
+                "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch", "fused_tile",
+                "estage_union")
 
 
 class LshBeamError(RuntimeError):

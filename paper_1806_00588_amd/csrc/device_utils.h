@@ -151,14 +151,20 @@ __device__ __forceinline__ void store_shared_result(T* p, T v) {
 // All of this wave's stores have completed (been acknowledged by the memory they went through to).
 __device__ __forceinline__ void publish_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Workgroup barrier for data that is exchanged through LDS only: waits for this wave's LDS
+// operations but, unlike __syncthreads, not for its global loads and stores -- loads that were
+// issued early on purpose stay in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // Workgroup inclusive scan; `wsum` is LDS with at least blockDim.x/64 + 1 words.  Returns the
 // inclusive prefix of v for this thread and the workgroup total in *total.  Ends with a barrier,
-// so wsum may be reused right after.
+// so wsum may be reused right after.  LDS_ONLY: its barriers are lds_barrier.
+template <bool LDS_ONLY = false>
 __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wsum, uint32_t* total) {
     const int nw = blockDim.x >> 6;
     uint32_t incl = wave_incl_scan(v);
     if (lane_id() == kWave - 1) wsum[wave_id()] = incl;
-    __syncthreads();
+    if constexpr (LDS_ONLY) lds_barrier(); else __syncthreads();
     // every wave scans the (at most 64) wave totals itself, lane l taking wsum[l]: one LDS read
     // and a DPP scan instead of a serial loop of dependent LDS reads
     const uint32_t x = (lane_id() < nw) ? wsum[lane_id()] : 0u;
@@ -166,7 +172,7 @@ __device__ __forceinline__ uint32_t block_incl_scan(uint32_t v, uint32_t* wsum, 
     const int wv = __builtin_amdgcn_readfirstlane(wave_id());
     const uint32_t base = wv ? wave_read_lane(sc, wv - 1) : 0u;
     const uint32_t tot = wave_read_lane(sc, nw - 1);
-    __syncthreads();
+    if constexpr (LDS_ONLY) lds_barrier(); else __syncthreads();
     *total = tot;
     return incl + base;
 }

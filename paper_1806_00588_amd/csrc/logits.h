@@ -31,6 +31,7 @@
 //   k_logits_estage  33..64 beams: hidden rows in registers, candidate rows through LDS;
 //   fused.h          the same tiles inside the kernels that also produce the candidate list.
 #pragma once
+#include "candidates.h"
 #include "device_utils.h"
 
 namespace lshbeam {
@@ -69,6 +70,16 @@ struct TileRecords {
     int32_t* id2;      // [rows, pitch] word id of each record's second largest logit, -1 if none
     int64_t pitch;     // records per hidden row
 };
+
+// Records that stand for groups of tiles.  A kernel whose workgroup j of G walks the tiles j,
+// j + G, j + 2G, ... of a sentence leaves one record for every kGroupTiles of them: record
+// j + m G covers the tiles j + (kGroupTiles m + i) G, i < kGroupTiles.  (Fifty rows of per-tile
+// records were 140 KB per sentence, all of which has to enter the one CU that selects.)
+constexpr int kGroupTiles = 8;
+__host__ __device__ inline int group_records(int ntiles, int G) {   // record slots per hidden row
+    const int per_wg = (ntiles + G - 1) / G;
+    return ntiles < G ? ntiles : G * ((per_wg + kGroupTiles - 1) / kGroupTiles);
+}
 
 constexpr int kTileN = 16;  // candidates per tile
 constexpr int kTileM = 16;  // hidden rows per tile
@@ -812,28 +823,160 @@ k_logits_hlds(const ET* __restrict__ E, int64_t ld, int d, const float* __restri
 // the four slices are summed through LDS in slice order, the wave of slice q finishing
 // accumulator register q of its row group (a quarter of the tile's logits and softmax partials
 // each: one wave finishing all of it was the critical path).  One barrier per tile.
+// ONE record (max, sum exp) per hidden row for every kGroupTiles tiles the workgroup walks (the
+// tiles j0 + (kGroupTiles m + i) G, i < kGroupTiles, at index j0 + m G; select.h): the
+// selection's pass over the records is bound by what one CU can pull, and fifty rows of per-tile
+// records were 140 KB per sentence.
 //   LDS: 2 x 16 rows x 1028 floats (pitch 4 modulo 32: conflict-free 16-byte reads) + 2 x 12 KB of
 //   partial tiles = 155.6 KB: one workgroup per CU.  Columns d .. 1023 of the tile are zeroed
 //   once (they meet A operands that are zero, and 0 x garbage may be NaN).
+//
+// UNION: the sentence's candidate list is made here too, from the bitmaps an earlier kernel left
+// for the parts of the sentence (k_part_bitmaps) and the top-frequent words: every workgroup ORs
+// them in the LDS the tiles will use later, scans the popcounts, and the thread that owns a bit
+// whose tile is one of this workgroup's writes its id to the list in memory and, for the
+// workgroup's first kEsIdTiles tiles, to a small LDS table (later tiles read their ids back from
+// the list).  All this runs while the A operands are on their way; the union kernel, its launch
+// and the trip of the list through memory go away.
 constexpr int kEsPitch = 1028, kEsSlice = 256, kEsSlices = 4;
-__host__ __device__ inline size_t estage_lds_bytes() {
-    return ((size_t)2 * kTileN * kEsPitch + (size_t)2 * 12 * 4 * kWave) * 4;
+constexpr int kEsIdTiles = 16;
+constexpr int kEsUnionParts = 6;   // part bitmaps the kernel can OR (64 rows hashed 12 at a time)
+// LDS: the two tiles, the partial tiles, the running record of each of the 64 rows (registers are
+// all taken), and for UNION the id table.
+__host__ __device__ inline size_t estage_lds_bytes(bool with_union = false) {
+    return ((size_t)2 * kTileN * kEsPitch + (size_t)2 * 12 * 4 * kWave + 2 * 64 +
+            (with_union ? kEsIdTiles * kTileN : 0)) * 4;
 }
+// LDS words the union needs inside the tile buffers (bitmap + scan scratch)
+__host__ __device__ inline size_t estage_union_words(int V) { return (size_t)bitmap_words_padded(V) + 64; }
+struct EstageUnion {
+    const uint32_t* parts;    // [S, nparts, ceil(V/32)] bitmaps
+    int nparts;
+    const int32_t* topfreq;   // [T]
+    int T;
+    int32_t* cand;            // out: [S, V] ascending candidate ids
+    int32_t* count;           // out: [S]
+};
 
-template <int MT>
+template <int MT, bool UNION>
 __global__ void __launch_bounds__(1024)
 k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __restrict__ H, int S,
                 int B, const int32_t* __restrict__ cand, const int32_t* __restrict__ count, int V,
-                float* __restrict__ logits, int64_t cpitch, TileRecords recs) {
+                float* __restrict__ logits, int64_t cpitch, TileRecords recs, EstageUnion un) {
     constexpr int KSTEP = 16, NSTEP = kEsSlice / KSTEP;
     extern __shared__ uint32_t esm[];
     float* etile = reinterpret_cast<float*>(esm);                         // [2][16][kEsPitch]
     float* red = etile + 2 * kTileN * kEsPitch;                           // [2][16 waves][3][64]
+    float2* run = reinterpret_cast<float2*>(red + 2 * 12 * 4 * kWave);            // [64 rows] record so far
+    uint32_t* ids_lds = reinterpret_cast<uint32_t*>(run + 64);                    // UNION: [kEsIdTiles][16]
     const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
     const int col = ln & 15, kk = ln >> 4;
     const int g = wv >> 2, q = wv & 3;                                     // row group, k slice
     const int s = blockIdx.x % S, j0 = blockIdx.x / S, G = gridDim.x / S;  // tiles j0, j0 + G, ...
-    const int C = count ? count[s] : V;
+
+    // A operands: rows 16 g + col (clamped), k = 256 q + 16 step + 4 kk + (0..3); zero past d
+    float a[NSTEP][4];
+    auto load_a = [&]() {
+        const int row = min(g * kTileM + col, B - 1);
+        const float* hrow = H + ((size_t)s * B + row) * d;
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            const int k = q * kEsSlice + st * KSTEP + 4 * kk;
+            const float4 h = *reinterpret_cast<const float4*>(hrow + min(k, d - 4));
+            const bool in = k < d && g < MT;
+            a[st][0] = in ? h.x : 0.f; a[st][1] = in ? h.y : 0.f;
+            a[st][2] = in ? h.z : 0.f; a[st][3] = in ? h.w : 0.f;
+        }
+    };
+    int C;
+    if constexpr (UNION) {
+        // Loads return in order: everything the union reads is asked for first (the first 4096
+        // bitmap words of up to kEsUnionParts parts, the first 3072 top-frequent ids), the A operands
+        // after it -- they arrive while the union is being made: the barriers in here are
+        // lds_barrier, which does not wait for them.
+        uint32_t* bm = esm;
+        uint32_t* wsum = bm + bitmap_words_padded(V);
+        const int nwords = (V + 31) >> 5;
+        const uint32_t* pb = un.parts + (size_t)s * un.nparts * nwords;
+        constexpr int SLOTS = 4, PARTS = kEsUnionParts;
+        uint32_t pw[SLOTS][PARTS];
+#pragma unroll
+        for (int u = 0; u < SLOTS; ++u)
+#pragma unroll
+            for (int b = 0; b < PARTS; ++b) pw[u][b] = 0u;
+        // (words past the end repeat the last; parts and slots that do not exist are skipped by
+        // uniform branches: a load that hits in cache costs the load path as much as one that misses)
+#pragma unroll
+        for (int u = 0; u < SLOTS; ++u) {
+            if (u * 1024 >= nwords) break;
+#pragma unroll
+            for (int b = 0; b < PARTS; ++b) {
+                if (b >= un.nparts) break;
+                pw[u][b] = pb[(size_t)b * nwords + min(tid + u * 1024, nwords - 1)];
+            }
+        }
+        const int32_t tf0 = (tid < un.T) ? un.topfreq[tid] : -1;
+        const int32_t tf1 = (tid + 1024 < un.T) ? un.topfreq[tid + 1024] : -1;
+        const int32_t tf2 = (tid + 2048 < un.T) ? un.topfreq[tid + 2048] : -1;
+        __builtin_amdgcn_sched_barrier(0);   // (issue order = the order written here)
+        load_a();
+#pragma unroll
+        for (int u = 0; u < SLOTS; ++u) {
+            uint32_t x = 0;
+#pragma unroll
+            for (int b = 0; b < PARTS; ++b) x |= pw[u][b];
+            if (tid + u * 1024 < nwords) bm[tid + u * 1024] = x;
+        }
+        for (int i = tid + SLOTS * 1024; i < nwords; i += 1024) {
+            uint32_t x = 0;
+            for (int b = 0; b < un.nparts; ++b) x |= pb[(size_t)b * nwords + i];   // (nparts <= kEsUnionParts)
+            bm[i] = x;
+        }
+        lds_barrier();
+        LSH_TRACE(1, 13);
+        if (un.T > 0) mark_ids_of_wave(bm, V, tf0);
+        if (un.T > 1024) mark_ids_of_wave(bm, V, tf1);
+        if (un.T > 2048) mark_ids_of_wave(bm, V, tf2);
+        for (int i = 3072 + tid; i - tid < un.T; i += 1024) mark_ids_of_wave(bm, V, (i < un.T) ? un.topfreq[i] : -1);
+        lds_barrier();
+        const int per_thread = (nwords + 1023) / 1024;
+        const int wbeg = min(tid * per_thread, nwords), wend = min(wbeg + per_thread, nwords);
+        uint32_t mine = 0;
+        for (int i = wbeg; i < wend; ++i) mine += __popc(bm[i]);
+        uint32_t total;
+        uint32_t pos = block_incl_scan<true>(mine, wsum, &total) - mine;   // list position of my first bit
+        C = (int)total;
+        LSH_TRACE(1, 14);
+        // my bits are list positions [pos, pos + mine); of the tiles they fall into, this
+        // workgroup's are those congruent to j0 modulo G: for each, skip to its first bit
+        // (whole words by popcount) and write out at most 16 ids
+        if (mine) {
+            const uint32_t end = pos + mine;
+            const int t0 = (int)(pos >> 4);
+            for (int nt = t0 + (j0 - t0 % G + G) % G; (uint32_t)nt * kTileN < end; nt += G) {
+                const uint32_t lo = max(pos, (uint32_t)nt * kTileN), hi = min(end, (uint32_t)nt * kTileN + kTileN);
+                uint32_t skip = lo - pos;
+                int i = wbeg;
+                uint32_t bits = bm[i];
+                for (uint32_t c = __popc(bits); skip >= c; c = __popc(bits)) { skip -= c; bits = bm[++i]; }
+                for (; skip; --skip) bits &= bits - 1u;
+                const int k = nt / G;
+                for (uint32_t at = lo; at < hi; ++at) {
+                    while (!bits) bits = bm[++i];
+                    const int32_t id = (i << 5) + (__ffs(bits) - 1);
+                    bits &= bits - 1u;
+                    un.cand[(size_t)s * V + at] = id;
+                    if (k < kEsIdTiles) ids_lds[k * kTileN + (int)(at & 15u)] = (uint32_t)id;
+                }
+            }
+        }
+        LSH_TRACE(1, 15);
+        if (j0 == 0 && tid == 0) un.count[s] = C;
+        lds_barrier();   // the table is written and the bitmap done with (the ids of later tiles are read
+                         // back from the list only after many full barriers)
+    } else {
+        C = count ? count[s] : V;
+    }
     const int ntiles = (C + kTileN - 1) / kTileN;
     if (j0 >= ntiles) return;                                             // (whole workgroup)
     LSH_TRACE(1, 0);
@@ -841,6 +984,14 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
     // this wave's candidate row of a tile, 4 KB as up to four 16-byte loads per lane
     const int d4 = d >> 2;
     auto id_of = [&](int nt) -> int64_t {                                  // (any nt >= 0)
+        if constexpr (UNION) {
+            // (waves past the end of the list, and tiles past the last, take a candidate that
+            // exists: their rows are never stored)
+            if (nt >= ntiles) nt = j0;
+            const int cidx = nt * kTileN + (nt * kTileN + wv < C ? wv : 0);
+            const int k = (nt - j0) / G;
+            return k < kEsIdTiles ? (int64_t)ids_lds[k * kTileN + (cidx & 15)] : (int64_t)un.cand[(size_t)s * V + cidx];
+        }
         const int cidx = min(nt * kTileN + wv, C - 1);                     // clamped rows are never stored
         return cand ? (int64_t)cand[(size_t)s * V + cidx] : (int64_t)cidx;
     };
@@ -858,21 +1009,7 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
     };
     load_row(row_of(id_of(j0)));
     int64_t id_next = id_of(j0 + G);   // candidate ids are fetched a tile ahead of their rows
-
-    // A operands: rows 16 g + col (clamped), k = 256 q + 16 step + 4 kk + (0..3); zero past d
-    float a[NSTEP][4];
-    {
-        const int row = min(g * kTileM + col, B - 1);
-        const float* hrow = H + ((size_t)s * B + row) * d;
-#pragma unroll
-        for (int st = 0; st < NSTEP; ++st) {
-            const int k = q * kEsSlice + st * KSTEP + 4 * kk;
-            const float4 h = *reinterpret_cast<const float4*>(hrow + min(k, d - 4));
-            const bool in = k < d && g < MT;
-            a[st][0] = in ? h.x : 0.f; a[st][1] = in ? h.y : 0.f;
-            a[st][2] = in ? h.z : 0.f; a[st][3] = in ? h.w : 0.f;
-        }
-    }
+    if constexpr (!UNION) load_a();
     // zero the columns d .. 1023 of both buffers (never written by the row copies)
     {
         const int padw = kEsSlices * kEsSlice - d;                         // a multiple of 4, < 1024
@@ -887,7 +1024,11 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
     LSH_TRACE(1, 2);
 
     int buf = 0;
-    for (int nt = j0; nt < ntiles; nt += G, buf ^= 1) {
+    // (max, sum exp) of a row over the tiles of the current group: kept in LDS by the lane that
+    // writes the row's records (column 0), which alone reads and writes its slot
+    if (g < MT && col == 0) run[g * kTileM + 4 * kk + q] = make_float2(-INFINITY, 0.f);
+    int kt = 0;                                 // tiles done
+    for (int nt = j0; nt < ntiles; nt += G, buf ^= 1, ++kt) {
         const bool more = nt + G < ntiles;
         if (more) {                                                        // in flight during the contraction
             load_row(row_of(id_next));
@@ -934,7 +1075,22 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
             const int row = g * kTileM + 4 * kk + q, c = n0 + col;
             const bool valid = row < B && c < C;
             if (valid) logits[((size_t)s * B + row) * cpitch + c] = x;
-            tile_record_store<false, false>(recs, ((size_t)s * B + row) * recs.pitch + nt, row < B, valid, x, col, 0);
+            const float mx = row16_max(valid ? x : -INFINITY);
+            const float se = row16_sum(valid ? expf(x - mx) : 0.f);
+            if (col == 0) {
+                // (one fast exponential, no branch: 16 waves share the CU's issue slots, and every
+                // instruction here is paid once per tile by each of them)
+                float2 acc2 = run[g * kTileM + 4 * kk + q];
+                const float hi = fmaxf(acc2.x, mx);
+                const float e = __expf(fminf(acc2.x, mx) - hi);      // exp(-|difference|); 0 for the first tile
+                acc2.y = (mx > acc2.x) ? fmaf(acc2.y, e, se) : fmaf(se, e, acc2.y);
+                acc2.x = hi;
+                const bool group_end = kt % kGroupTiles == kGroupTiles - 1 || !more;
+                if (group_end && row < B)
+                    reinterpret_cast<float2*>(recs.rec)[((size_t)s * B + row) * recs.pitch + j0 +
+                                                        (size_t)(kt / kGroupTiles) * G] = acc2;
+                run[g * kTileM + 4 * kk + q] = group_end ? make_float2(-INFINITY, 0.f) : acc2;
+            }
         }
     }
 }

@@ -77,12 +77,14 @@ struct HostBand {
 // Launch-plan options of a handle (lsh_set_option); kAuto = the library's own rule.
 enum Opt {
     kOptFused, kOptFusedGrid, kOptLogitsGrid, kOptLogitsWaves, kOptLogitsHlds, kOptLogitsEstage,
-    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kOptOneLaunch, kOptFusedTile, kNumOpts
+    kOptHldsRem, kOptLogitsPlanes, kOptHldsRows, kOptPartRows, kOptStageRows, kOptOneLaunch, kOptFusedTile,
+    kOptEstageUnion, kNumOpts
 };
 constexpr int kAuto = -1;
 const char* const kOptNames[kNumOpts] = {
     "fused", "fused_grid", "logits_grid", "logits_waves", "logits_hlds", "logits_estage",
-    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch", "fused_tile"};
+    "hlds_rem", "logits_planes", "hlds_rows", "part_rows", "stage_rows", "one_launch", "fused_tile",
+    "estage_union"};
 
 }  // namespace
 
@@ -394,27 +396,44 @@ void launch_logits_hlds(const StepCtx& cx, int64_t tiles_n, bool aligned, const 
 
 // k_logits_estage: 33..64 beams, fp32 rows of at most 1024 values, 16-byte aligned operands, at
 // most 256 sentences.  About one workgroup per CU, dealt evenly to the sentences.
-void launch_logits_estage(const StepCtx& cx, const float* H, const lsh_step_params* sp,
-                          const int32_t* cand, const int32_t* count, const Workspace& w) {
+// Returns its workgroups per sentence: each leaves one record per hidden row for all its tiles.
+// un, if given: the kernel makes the candidate list itself, from the bitmaps of the sentence's parts.
+int launch_logits_estage(const StepCtx& cx, const float* H, const lsh_step_params* sp,
+                         const int32_t* cand, const int32_t* count, const Workspace& w,
+                         const EstageUnion* un = nullptr) {
     const lsh_tables* t = cx.t;
     const float* E = (const float*)t->E;
     const int MT = (sp->B + kTileM - 1) / kTileM;
-    const size_t lds = estage_lds_bytes();
+    const size_t lds = estage_lds_bytes(un != nullptr);
     const int per_sentence = std::max(1, t->option(kOptLogitsGrid, 256) / sp->S);
     const dim3 grid((unsigned)(per_sentence * sp->S)), block(1024);
-#define LSH_ESTAGE(MTV)                                                                              \
+#define LSH_ESTAGE(MTV, UN)                                                                          \
     do {                                                                                             \
-        auto kfn = k_logits_estage<MTV>;                                                             \
-        launch(cx, 1, kfn, grid, block, lds, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V, \
-               w.logits, w.cpitch, w.records());                                            \
+        auto kfn = k_logits_estage<MTV, UN>;                                                         \
+        launch(cx, 1, kfn, grid, block, lds, E, t->ld, t->d, H, sp->S, sp->B, cand, count, t->V,     \
+               w.logits, w.cpitch, w.records(), un ? *un : EstageUnion{});                           \
     } while (0)
-    if (MT <= 3) LSH_ESTAGE(3); else LSH_ESTAGE(4);
+    if (un) { if (MT <= 3) LSH_ESTAGE(3, true); else LSH_ESTAGE(4, true); }
+    else { if (MT <= 3) LSH_ESTAGE(3, false); else LSH_ESTAGE(4, false); }
 #undef LSH_ESTAGE
+    return per_sentence;
 }
 
+// Whether a step's contraction is k_logits_estage: 33..64 beams, fp32 rows of at most 1024 values,
+// 16-byte aligned operands, at most 256 sentences (option logits_estage = 0: the other drivers).
+bool takes_estage(const lsh_tables* t, const lsh_step_params* sp, const float* H) {
+    const bool aligned = (t->d % 4 == 0) && (t->ld % 4 == 0) && ((uintptr_t)t->E % 16 == 0) && ((uintptr_t)H % 16 == 0);
+    return t->dtype == LSH_F32 && aligned && sp->B > 2 * kTileM && sp->B <= 4 * kTileM &&
+           t->d <= kEsSlices * kEsSlice && sp->S <= 256 && estage_lds_bytes(true) <= kMaxDynLds &&
+           t->option(kOptLogitsEstage, 1) && !t->option(kOptLogitsWaves, 0);
+}
+
+// Returns 0 if the kernel it launched leaves one record per hidden row and tile, else the number
+// of record groups per sentence (see select_sentence).
 template <typename ET>
-void launch_logits(const StepCtx& cx, const float* H, const lsh_step_params* sp,
-                   const int32_t* cand, const int32_t* count, const Workspace& w) {
+int launch_logits(const StepCtx& cx, const float* H, const lsh_step_params* sp,
+                  const int32_t* cand, const int32_t* count, const Workspace& w,
+                  const EstageUnion* un = nullptr) {
     const lsh_tables* t = cx.t;
     constexpr int VEC = ElemTraits<ET>::VEC;
     const bool aligned = (t->d % VEC == 0) && (t->ld % VEC == 0) && ((uintptr_t)t->E % 16 == 0) &&
@@ -434,11 +453,8 @@ void launch_logits(const StepCtx& cx, const float* H, const lsh_step_params* sp,
     const int group_rows = hlds_group_rows(t, sp->S, sp->B, t->d);
     // 33..64 beams: hidden rows in registers, candidate rows through LDS (LSHBEAM_LOGITS_ESTAGE=0:
     // the other drivers)
-    const bool estage_ok = std::is_same<ET, float>::value && aligned && sp->B > 2 * kTileM &&
-                           sp->B <= 4 * kTileM && t->d <= kEsSlices * kEsSlice && sp->S <= 256 &&
-                           estage_lds_bytes() <= kMaxDynLds;
-    if (estage_ok && t->option(kOptLogitsEstage, 1) && !t->option(kOptLogitsWaves, 0)) {
-        launch_logits_estage(cx, H, sp, cand, count, w);
+    if (takes_estage(t, sp, H)) {
+        return launch_logits_estage(cx, H, sp, cand, count, w, un);
     } else if (mode == 1 && group_rows > 0 && t->option(kOptLogitsHlds, 1)) {
         launch_logits_hlds<ET>(cx, tiles_n, aligned, H, sp, cand, count, w, group_rows);
     } else if (mode == 1 && MT <= 4) {
@@ -456,6 +472,7 @@ void launch_logits(const StepCtx& cx, const float* H, const lsh_step_params* sp,
         const int grid = (int)std::min<int64_t>(max_tiles, t->option(kOptLogitsGrid, 2048));
         launch_logits_w<ET, 4>(cx, grid, aligned, H, sp, cand, count, w);
     }
+    return 0;
 }
 
 template <typename ET>
@@ -750,6 +767,7 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
         parts = w.row_bitmaps;
     }
     bool selected = false;   // the step's tail already ran inside the fused kernel
+    int rec_groups = 0;      // tile records per hidden row, if not one per tile (launch_logits)
     if (fused) {
         // One launch per step: the last workgroup of each sentence also runs the selection
         // (option one_launch = 0: a selection kernel follows instead; also when no ticket block
@@ -790,7 +808,15 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
         cand = w.cand;
         count = w.count;
     } else {
-        if (parts) {
+        // a few part bitmaps ahead of k_logits_estage: that kernel ORs them itself (option
+        // estage_union = 0: a union kernel of its own, as for the other drivers)
+        EstageUnion un{parts, nparts, topfreq_dev, sp->T, w.cand, w.count};
+        const bool fold = parts && nparts <= kEsUnionParts && takes_estage(t, sp, H_dev) && t->option(kOptEstageUnion, 1) &&
+                          estage_union_words(t->V) <= (size_t)2 * kTileN * kEsPitch;
+        if (fold) {
+            cand = w.cand;
+            count = w.count;
+        } else if (parts) {
             // union of the sentence's bitmaps + top-frequent words + compaction
             launch(cx, 0, k_union_compact, dim3(sp->S), dim3(kCandThreads),
                    union_compact_lds_words(t->V) * sizeof(uint32_t), parts, nparts, t->V,
@@ -803,16 +829,17 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
             cand = w.cand;
             count = w.count;
         }
-        if (t->dtype == LSH_F32) launch_logits<float>(cx, H_dev, sp, cand, count, w);
-        else launch_logits<uint16_t>(cx, H_dev, sp, cand, count, w);
+        rec_groups = t->dtype == LSH_F32 ? launch_logits<float>(cx, H_dev, sp, cand, count, w, fold ? &un : nullptr)
+                                         : launch_logits<uint16_t>(cx, H_dev, sp, cand, count, w);
     }
     if (!selected) {
-#define LSH_SELECT(RICHV)                                                                             \
-    launch(cx, 2, k_select<RICHV>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits, w.cpitch, \
-           (const TileRecord*)w.partials, (const int32_t*)w.ids2, w.ppitch, cand, count, t->V, sp->B,  \
-           beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev,                          \
-           fused ? std::max(0, t->option(kOptFusedTile, 0)) : 0)
-        if (fused) LSH_SELECT(true); else LSH_SELECT(false);   // (the fused kernels leave rich records)
+#define LSH_SELECT(RICHV, GROUPSV)                                                                    \
+    launch(cx, 2, k_select<RICHV, GROUPSV>, dim3(sp->S), dim3(kSelThreads), 0, (const float*)w.logits,  \
+           w.cpitch, (const TileRecord*)w.partials, (const int32_t*)w.ids2, w.ppitch, cand, count, t->V, \
+           sp->B, beam_scores_dev, w.lse, out_beam_dev, out_word_dev, out_score_dev,                   \
+           fused ? std::max(0, t->option(kOptFusedTile, 0)) : 0, rec_groups)
+        // (the fused kernels leave rich records, k_logits_estage one record for a group of tiles)
+        if (fused) LSH_SELECT(true, false); else if (rec_groups > 0) LSH_SELECT(false, true); else LSH_SELECT(false, false);
 #undef LSH_SELECT
     }
     HIP_TRY(hipGetLastError());
@@ -957,8 +984,10 @@ lsh_status lsh_build_tables(const void* E_dev, const int32_t* perms_dev, const l
 #undef LSH_ALLOW_FUSED
     HIP_TRY(allow_logits_lds<float>());
     HIP_TRY(allow_logits_lds<uint16_t>());
-    HIP_TRY(allow_whole_lds<k_logits_estage<3>>());
-    HIP_TRY(allow_whole_lds<k_logits_estage<4>>());
+    HIP_TRY((allow_whole_lds<k_logits_estage<3, false>>()));
+    HIP_TRY((allow_whole_lds<k_logits_estage<4, false>>()));
+    HIP_TRY((allow_whole_lds<k_logits_estage<3, true>>()));
+    HIP_TRY((allow_whole_lds<k_logits_estage<4, true>>()));
     guard.t = nullptr;
     *out = t;
     return LSH_OK;

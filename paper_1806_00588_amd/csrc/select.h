@@ -26,6 +26,7 @@
 #pragma once
 #include <type_traits>
 #include "device_utils.h"
+#include "logits.h"
 
 namespace lshbeam {
 
@@ -291,13 +292,103 @@ __device__ __forceinline__ int32_t load_id2(const int32_t* p) {
     else return *p;
 }
 
-template <bool RICH, bool SAME_KERNEL = false>
+// The first half of the selection for such records and a sentence of at most 64 beams: 16 lanes
+// per hidden row, all rows at once, lane c of a row's sixteen taking records c, c + 16, ...  (A
+// wave per row, as in the general path, spends a microsecond of instruction issue per row on a
+// few dozen records.)  Leaves the rows' log-sum-exps and beam scores in LDS, lists every tile of
+// every group whose maximum reaches tau in sh.open_list (count in sh.misc[5], which the caller
+// has cleared) and returns tau.
+__device__ __forceinline__ uint32_t select_front_grouped(SelShared& sh, int s, const float2* records, int64_t ppitch,
+                                                         int ntiles, int G, int B, const float* beam_scores,
+                                                         float* lse_out) {
+    const int tid = threadIdx.x, ln = lane_id();
+    const int row = tid >> 4, c = ln & 15;
+    const bool row_ok = row < B;
+    const float bsi = row_ok ? beam_scores[s * B + row] : 0.f;
+    const float2* pr = records + ((size_t)s * B + min(row, B - 1)) * ppitch;
+    const int nrec = group_records(ntiles, G);
+    // Workgroup w of the G has ntiles / G tiles, one more if w < ntiles % G; record j is group
+    // j / G of workgroup j % G.  While every workgroup has one group (the usual case) that is
+    // group 0 of workgroup j: the divisions are taken only otherwise (a lane pays ~40
+    // instructions for each, 16 waves sharing the CU's issue slots).
+    const int full = ntiles / G, rem = ntiles - full * G;   // (uniform)
+    const bool single = nrec <= G;
+    // tiles of record j = group grp of workgroup w (0: a slot nobody wrote), and the first of them
+    auto tiles_of_group = [&](int j, int w, int grp, int* first) {
+        *first = w + kGroupTiles * grp * G;
+        return j < nrec ? max(0, min(kGroupTiles, full + (w < rem ? 1 : 0) - kGroupTiles * grp)) : 0;
+    };
+    auto tiles_of = [&](int j, int* first) {
+        return tiles_of_group(j, single ? j : j % G, single ? 0 : j / G, first);
+    };
+    // the records past the first 64 of a row, c + 64, c + 80, ...: (w, grp) kept up without dividing
+    struct Walk { int j, w, grp; };
+    auto walk_begin = [&]() {
+        const int j = c + 16 * 4;
+        return Walk{j, single ? j : j % G, single ? 0 : j / G};
+    };
+    auto walk_next = [&](Walk& it) {
+        it.j += 16; it.w += 16;
+        while (it.w >= G) { it.w -= G; ++it.grp; }
+    };
+    auto load = [&](int j, int n) {
+        const float2 r = pr[min(j, max(nrec - 1, 0))];
+        return n > 0 ? r : make_float2(-INFINITY, 0.f);
+    };
+    constexpr int KEPT = 4;                       // records per lane held in registers (64 per row)
+    float2 r[KEPT];
+    int ft[KEPT], nt[KEPT];
+#pragma unroll
+    for (int u = 0; u < KEPT; ++u) { nt[u] = tiles_of(c + 16 * u, &ft[u]); r[u] = load(c + 16 * u, nt[u]); }
+    float m = fmaxf(fmaxf(r[0].x, r[1].x), fmaxf(r[2].x, r[3].x));
+    for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
+        int f;
+        m = fmaxf(m, load(it.j, tiles_of_group(it.j, it.w, it.grp, &f)).x);
+    }
+    const float M = row16_max(m);
+    float sum = 0.f;
+    if (M != -INFINITY) {
+#pragma unroll
+        for (int u = 0; u < KEPT; ++u) sum += r[u].y * __expf(r[u].x - M);   // padding: 0 * 0
+        for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
+            int f;
+            const float2 e = load(it.j, tiles_of_group(it.j, it.w, it.grp, &f));
+            sum += e.y * __expf(e.x - M);
+        }
+    }
+    const float lse = M + logf(row16_sum(sum));
+    if (c == 0 && row_ok) { sh.lse[row] = lse; sh.bs[row] = bsi; lse_out[s * B + row] = lse; }
+    const uint32_t lmax = (row_ok && m != -INFINITY) ? f32_sortable(bsi + (m - lse) + 0.0f) : 0u;
+    const uint32_t tau = block_kth_largest_lb(lmax, B, &sh);
+    // every tile of every group whose maximum reaches tau: one reservation per lane
+    auto reaches = [&](float x) { return row_ok && x != -INFINITY && f32_sortable(bsi + (x - lse) + 0.0f) >= tau; };
+    auto put = [&](uint32_t pos, int first, int n) {
+        for (int k = 0; k < n; ++k)
+            if (pos + (uint32_t)k < (uint32_t)kSelOpenCap) sh.open_list[pos + k] = ((uint32_t)row << 20) | (uint32_t)(first + k * G);
+    };
+    int total = 0;
+#pragma unroll
+    for (int u = 0; u < KEPT; ++u) { if (!reaches(r[u].x)) nt[u] = 0; total += nt[u]; }
+    if (total) {
+        uint32_t pos = atomicAdd(&sh.misc[5], (uint32_t)total);
+#pragma unroll
+        for (int u = 0; u < KEPT; ++u) { put(pos, ft[u], nt[u]); pos += (uint32_t)nt[u]; }
+    }
+    for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
+        int f;
+        const int n = tiles_of_group(it.j, it.w, it.grp, &f);
+        if (n > 0 && reaches(load(it.j, n).x)) put(atomicAdd(&sh.misc[5], (uint32_t)n), f, n);
+    }
+    return tau;
+}
+
+template <bool RICH, bool SAME_KERNEL = false, bool GROUPS = false>
 __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const float* logits, int64_t cpitch,
                                                 const TileRecord* records, const int32_t* ids2, int64_t ppitch,
                                                 const int32_t* cand, const int32_t* count, int C_known,
                                                 int V, int B, const float* beam_scores, float* lse_out,
                                                 int32_t* out_beam, int32_t* out_word, float* out_score,
-                                                int tile_forced = 0) {
+                                                int tile_forced = 0, int rec_groups = 0) {
     typedef typename std::conditional<RICH, float4, float2>::type REC;
     const REC* partials = reinterpret_cast<const REC*>(records);
     // batches of tile maxima a wave keeps in registers between the passes (rich records: also the
@@ -308,11 +399,17 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     // The first batch of records of this wave's first row is requested before the candidate
     // count is known (one memory round trip less): indices are clamped to the row's pitch, which
     // is allocated, and what lies beyond the last tile is masked after the load like any padding.
+    // Lane r of a wave asks for the beam score of the wave's r-th row right away too: loads
+    // return in order, so a score asked for inside the loop over the rows would have every
+    // iteration wait for a memory round trip (and for the records requested ahead of it).
+    float bs_pre = 0.f;
+    constexpr bool grouped = GROUPS;
+    if (!grouped && wv + ln * kSelWaves < B) bs_pre = beam_scores[s * B + wv + ln * kSelWaves];   // (B <= 256: ln < 16)
     REC first_batch[kSelBatch];
     int32_t first_ids2[kSelBatch];
 #pragma unroll
     for (int q = 0; q < kSelBatch; ++q) { first_batch[q] = empty_record<REC>(); first_ids2[q] = -1; }
-    if (wv < B) {
+    if (wv < B && !grouped) {
         const size_t r0 = ((size_t)s * B + wv) * ppitch;
 #pragma unroll
         for (int q = 0; q < kSelBatch; ++q) {
@@ -325,8 +422,65 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     // candidates per tile: 16, or what the fused kernel that wrote the records was told to use
     const int tn = RICH ? select_tile_width(C, tile_forced, ppitch) : 16;
     const int ntiles = (C + tn - 1) / tn;
+    // GROUPS: the records stand for groups of tiles (select_front_grouped; rec_groups = the
+    // workgroups per sentence of the kernel that wrote them; at most 64 beams)
+    static_assert(!(GROUPS && RICH), "rich records are per tile");
+    const int nrec = ntiles;
     const float* lg = logits + (size_t)s * B * cpitch;
     if (tid == 0) { sh.misc[4] = 0; sh.misc[5] = 0; sh.misc[6] = 0; }
+    // Ranks the m <= kSelRankCap keys of sh.list by counting (the inner loop split over the
+    // workgroup: thread t compares key e = t % m with one of `parts` slices of the list); ends
+    // with a barrier, ranks in sh.rank.
+    auto rank_list = [&](int m) {
+        if (tid < m) sh.rank[tid] = 0;
+        __syncthreads();
+        if (m > 0) {
+            const int parts = kSelThreads / m;
+            const int e = tid % m, p = tid / m;
+            if (p < parts) {
+                const int chunk = (m + parts - 1) / parts;
+                const int j0 = p * chunk, j1 = min(m, j0 + chunk);
+                const uint64_t mine = sh.list[e];
+                uint32_t rank = 0;
+#pragma unroll 8
+                for (int j = j0; j < j1; ++j) rank += (sh.list[j] > mine) ? 1u : 0u;
+                if (rank) atomicAdd(&sh.rank[e], rank);
+            }
+        }
+        __syncthreads();
+    };
+    // Results from the ranked list: rank r < B goes to slot r; slots beyond the number of finite
+    // scores are (-1, -1, -inf).  The low 24 bits of a key's index are a word id (ids_in_keys) or
+    // a column of the candidate list.
+    const size_t o0 = (size_t)s * B;
+    auto emit = [&](int m, bool ids_in_keys) {
+        for (int e = tid + min(m, B); e < B; e += kSelThreads) {
+            out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
+        }
+        if (tid < m && sh.rank[tid] < (uint32_t)B) {
+            const uint64_t k = sh.list[tid];
+            const size_t o = o0 + sh.rank[tid];
+            const float score = key_value(k);
+            const uint32_t idx = key_index(k);
+            if (score == -INFINITY || score != score) {
+                out_beam[o] = -1; out_word[o] = -1; out_score[o] = -INFINITY;
+            } else {
+                const int c = (int)(idx & 0xFFFFFFu);
+                out_beam[o] = (int)(idx >> 24);
+                out_word[o] = (ids_in_keys || !cand) ? c : cand[(size_t)s * V + c];
+                out_score[o] = score;
+            }
+        }
+    };
+
+    const ScoreSrc src{lg, cpitch, B, C, sh.lse, sh.bs};
+    uint32_t tau;
+    if (grouped) {
+        __syncthreads();   // (the counters)
+        tau = select_front_grouped(sh, s, reinterpret_cast<const float2*>(records), ppitch, ntiles, rec_groups, B,
+                                   beam_scores, lse_out);
+        LSH_TRACE_ANY(2, 2);
+    } else {   // (down to the second pass's list of tiles; not indented)
 
     // ---- per row: log-sum-exp from the tile records, and the lane's best tile-maximum score.
     //      Wave w takes rows w, w + 16, ...; a row is visited in batches of 512 tiles.  The
@@ -342,18 +496,18 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     float keep_z[RICH ? KR : 1][kSelBatch];
     int32_t keep_id1[RICH ? KR : 1][kSelBatch], keep_id2[RICH ? KR : 1][kSelBatch];
     constexpr int kBatchTiles = kWave * kSelBatch;
-    const int nb = (ntiles + kBatchTiles - 1) / kBatchTiles;                     // batches per row
+    const int nb = (nrec + kBatchTiles - 1) / kBatchTiles;                     // batches per row
     const int nit = (wv < B ? (B - wv + kSelWaves - 1) / kSelWaves : 0) * nb;    // of this wave
     // lanes x kSelBatch slots of a batch that hold tiles at all (wave-uniform; the rest is
     // skipped outright: 16 waves on one CU are bound by instruction issue)
-    auto slots_of = [&](int bt) { return min(kSelBatch, (ntiles - bt * kBatchTiles + kWave - 1) / kWave); };
+    auto slots_of = [&](int bt) { return min(kSelBatch, (nrec - bt * kBatchTiles + kWave - 1) / kWave); };
     auto load_batch = [&](int it, REC (&p)[kSelBatch]) {
         const int r = it / nb, bt = it - r * nb;
         const int nq = slots_of(bt);
         const REC* pr = partials + ((size_t)s * B + (wv + r * kSelWaves)) * ppitch;
 #pragma unroll
         for (int q = 0; q < kSelBatch; ++q)
-            if (q < nq) p[q] = load_record<SAME_KERNEL>(pr + min(bt * kBatchTiles + ln + q * kWave, ntiles - 1));
+            if (q < nq) p[q] = load_record<SAME_KERNEL>(pr + min(bt * kBatchTiles + ln + q * kWave, nrec - 1));
     };
     auto load_ids2 = [&](int it, int32_t (&p)[kSelBatch]) {
         const int r = it / nb, bt = it - r * nb;
@@ -361,7 +515,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
         const int32_t* pr = ids2 + ((size_t)s * B + (wv + r * kSelWaves)) * ppitch;
 #pragma unroll
         for (int q = 0; q < kSelBatch; ++q)
-            if (q < nq) p[q] = load_id2<SAME_KERNEL>(pr + min(bt * kBatchTiles + ln + q * kWave, ntiles - 1));
+            if (q < nq) p[q] = load_id2<SAME_KERNEL>(pr + min(bt * kBatchTiles + ln + q * kWave, nrec - 1));
     };
     {
         REC cur[kSelBatch], nxt[kSelBatch];
@@ -375,11 +529,11 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
             if (it + 1 < nit) load_batch(it + 1, nxt);
             if (bt == 0) {
                 m = -INFINITY; sum = 0.f; lmx = -INFINITY;
-                bsi = beam_scores[s * B + i];
+                bsi = __uint_as_float(wave_read_lane(__float_as_uint(bs_pre), r));
             }
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q)
-                if (q >= nq || bt * kBatchTiles + ln + q * kWave >= ntiles)
+                if (q >= nq || bt * kBatchTiles + ln + q * kWave >= nrec)
                     cur[q] = empty_record<REC>();
             if constexpr (KEEP > 0) {
 #pragma unroll
@@ -435,7 +589,6 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     //      (B distinct tile maxima are >= it).  Up to 16 beams every row has its own wave, and
     //      the largest over the waves of "B-th largest lane value in the wave" costs no barrier
     //      per bit; with more beams the B-th largest of all 1024 lane values is much tighter. ----
-    uint32_t tau;
     if (B <= kSelWaves) {
         const uint32_t kth = wave_kth_largest_sort(lmax, B);
         if (ln == 0) sh.wtau[wv] = kth;
@@ -447,51 +600,6 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
         tau = block_kth_largest_lb(lmax, B, &sh);
     }
     LSH_TRACE_ANY(2, 2);
-
-    // Ranks the m <= kSelRankCap keys of sh.list by counting (the inner loop split over the
-    // workgroup: thread t compares key e = t % m with one of `parts` slices of the list); ends
-    // with a barrier, ranks in sh.rank.
-    auto rank_list = [&](int m) {
-        if (tid < m) sh.rank[tid] = 0;
-        __syncthreads();
-        if (m > 0) {
-            const int parts = kSelThreads / m;
-            const int e = tid % m, p = tid / m;
-            if (p < parts) {
-                const int chunk = (m + parts - 1) / parts;
-                const int j0 = p * chunk, j1 = min(m, j0 + chunk);
-                const uint64_t mine = sh.list[e];
-                uint32_t rank = 0;
-#pragma unroll 8
-                for (int j = j0; j < j1; ++j) rank += (sh.list[j] > mine) ? 1u : 0u;
-                if (rank) atomicAdd(&sh.rank[e], rank);
-            }
-        }
-        __syncthreads();
-    };
-    // Results from the ranked list: rank r < B goes to slot r; slots beyond the number of finite
-    // scores are (-1, -1, -inf).  The low 24 bits of a key's index are a word id (ids_in_keys) or
-    // a column of the candidate list.
-    const size_t o0 = (size_t)s * B;
-    auto emit = [&](int m, bool ids_in_keys) {
-        for (int e = tid + min(m, B); e < B; e += kSelThreads) {
-            out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
-        }
-        if (tid < m && sh.rank[tid] < (uint32_t)B) {
-            const uint64_t k = sh.list[tid];
-            const size_t o = o0 + sh.rank[tid];
-            const float score = key_value(k);
-            const uint32_t idx = key_index(k);
-            if (score == -INFINITY || score != score) {
-                out_beam[o] = -1; out_word[o] = -1; out_score[o] = -INFINITY;
-            } else {
-                const int c = (int)(idx & 0xFFFFFFu);
-                out_beam[o] = (int)(idx >> 24);
-                out_word[o] = (ids_in_keys || !cand) ? c : cand[(size_t)s * V + c];
-                out_score[o] = score;
-            }
-        }
-    };
 
     if constexpr (RICH) {
         // ---- the short cut: every largest / second largest score >= tau, from the records ----
@@ -535,7 +643,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
 #pragma unroll
             for (int q = 0; q < kSelBatch; ++q) {
                 if (q >= nq) continue;  // wave-uniform
-                const bool in = t0 + ln + q * kWave < ntiles;
+                const bool in = t0 + ln + q * kWave < nrec;
                 const float s1 = bsi + (x1[q] - lse), s2 = bsi + (x2[q] - lse);
                 if (in && i1[q] >= 0 && f32_sortable(s1 + 0.0f) >= tau) {
                     const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
@@ -614,7 +722,6 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     }
 
     // ---- second pass: tiles whose maximum reaches tau are opened, 16 lanes per tile ----
-    const ScoreSrc src{lg, cpitch, B, C, sh.lse, sh.bs};
     // (a) every wave lists the tiles of its rows that qualify in one workgroup-wide LDS list:
     //     which rows hold them is as uneven as the beam scores (the best beam's row can hold
     //     nearly all), so they are opened by the whole workgroup, not by the row's wave
@@ -658,7 +765,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
             bal[q] = 0;
             if (q < nq) {
                 const int t = t0 + ln + q * kWave;
-                bal[q] = __ballot(t < ntiles && f32_sortable(bsi + (px[q] - lse) + 0.0f) >= tau);
+                bal[q] = __ballot(t < nrec && f32_sortable(bsi + (px[q] - lse) + 0.0f) >= tau);
                 n_mine += (uint32_t)__popcll(bal[q]);
             }
         }
@@ -676,6 +783,7 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
             }
         }
     }
+    }   // (!grouped)
     LSH_TRACE_ANY(2, 6);
     __syncthreads();
     LSH_TRACE_ANY(2, 7);
@@ -757,16 +865,17 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
 
 // grid = S workgroups (one per sentence), kSelThreads threads: the selection as a kernel of its
 // own, after kernels that left rich (fused plans) or plain tile records.
-template <bool RICH>
+template <bool RICH, bool GROUPS>
 __global__ void __launch_bounds__(kSelThreads)
 k_select(const float* __restrict__ logits, int64_t cpitch, const TileRecord* __restrict__ records,
          const int32_t* __restrict__ ids2, int64_t ppitch, const int32_t* __restrict__ cand,
          const int32_t* __restrict__ count, int V, int B, const float* __restrict__ beam_scores,
          float* __restrict__ lse_out /*[R]*/, int32_t* __restrict__ out_beam,
-         int32_t* __restrict__ out_word, float* __restrict__ out_score, int tile_forced) {
+         int32_t* __restrict__ out_word, float* __restrict__ out_score, int tile_forced, int rec_groups) {
     __shared__ SelShared sh;
-    select_sentence<RICH, false>(sh, (int)blockIdx.x, logits, cpitch, records, ids2, ppitch, cand, count, -1, V, B,
-                                 beam_scores, lse_out, out_beam, out_word, out_score, tile_forced);
+    select_sentence<RICH, false, GROUPS>(sh, (int)blockIdx.x, logits, cpitch, records, ids2, ppitch, cand, count, -1,
+                                         V, B, beam_scores, lse_out, out_beam, out_word, out_score, tile_forced,
+                                         rec_groups);
 }
 
 // lp[i, c] = logit[i, c] - lse[i] for one sentence, for inspection.

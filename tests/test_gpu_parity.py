@@ -639,8 +639,11 @@ def test_one_launch_two_launch_and_three_kernel_plans_agree_bit_for_bit(name, S,
                        ("two-narrow", dict(fused=1, one_launch=0, fused_tile=7))):
         gc.tables.reset_options()
         force(gc, **opts)
+        gc.tables.profile_begin(4)
         gb, gw, gs, sp, ws = gc.step(H, bs, S, B, threshold=t)
+        launches = {k: n for k, (_, n) in gc.tables.profile_end().items()}
         assert binding.step_is_fused(gc.tables, sp) == (mode != "three")
+        assert launches["k_select"] == (0 if mode.startswith("one") else 1), (mode, launches)
         if mode.endswith("narrow"):
             for s_ in range(S):
                 ref = gc.oracle_sentence(H[s_ * B:(s_ + 1) * B], bs[s_ * B:(s_ + 1) * B], B, threshold=t)
@@ -759,20 +762,28 @@ def test_contraction_with_hidden_rows_in_lds_or_in_global_memory(hlds, rows, for
     run_and_check(cfg, gc, H[:80], np.zeros(80, np.float32), 2, 40, full_vocab=True)
 
 
+@pytest.mark.parametrize("union", ["inside", "before"])
 @pytest.mark.parametrize("grid", ["256", "4", "1"])
-def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_lds(grid, force):
+def test_contraction_with_hidden_rows_in_registers_and_candidate_rows_through_lds(grid, union, force):
     # 33..64 beams, fp32 rows: the workgroup keeps the hidden rows in registers and double-buffers
     # the tiles' candidate rows through LDS.  Small grids give a workgroup many tiles (both
     # buffers in use, the last tile ragged); d = 1000 leaves 24 zeroed pad columns, d = 64 leaves 960.
+    # Sentences this wide are hashed in parts; the kernel ORs the parts' bitmaps and makes the
+    # candidate list itself (more than 16 tiles per workgroup: ids read back from the list), or
+    # option estage_union = 0 puts a union kernel before it.  One record per row and workgroup
+    # for the selection either way.
     cfg, gc = case("paper")
-    force(gc, logits_grid=int(grid))
+    force(gc, logits_grid=int(grid), estage_union=int(union == "inside"))
     H = hidden(cfg, gc, 12).reshape(-1, cfg.d)                    # 144 rows
     rng = np.random.default_rng(int(grid))
     for S, B in [(2, 50), (1, 33), (2, 64), (3, 48)]:
         bs = rng.standard_normal(S * B).astype(np.float32)
         run_and_check(cfg, gc, H[:S * B], bs, S, B, check_lp=(B == 33))
+    if union == "inside":   # all of V: 2500 tiles, many groups of records per workgroup
+        run_and_check(cfg, gc, H[:80], rng.standard_normal(80).astype(np.float32), 2, 40, full_vocab=True,
+                      check_lp=False)
     cfg, gc = case("tiny")
-    force(gc, logits_grid=int(grid))
+    force(gc, logits_grid=int(grid), estage_union=int(union == "inside"))
     H = hidden(cfg, gc, 20).reshape(-1, cfg.d)
     H = np.concatenate([H, H[::-1] * 0.5 + 0.1, H * 0.25 - 0.1], axis=0)
     for S, B in [(3, 40), (2, 64), (1, 33), (4, 49)]:
