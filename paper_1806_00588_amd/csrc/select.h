@@ -665,36 +665,41 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
         LSH_TRACE_ANY(2, 6);
         const int mr = (int)sh.misc[4];
         if (mr <= kWave) {
-            // The usual case, a few dozen keys: wave 0 ranks the whole list by itself (lane e
-            // holds key e; the others come by lane broadcast), writes the results unless a
-            // second largest is among the B best, and tells the others, who only wait.  (All 16
-            // waves ranking redundantly, to save this barrier, measured slower: they share four
-            // instruction issuers.)
-            if (wv == 0) {
-                const uint64_t mine = (ln < mr) ? sh.list[ln] : 0ull;
-                const bool second = (ln < mr) && sh.open_list[ln] != 0u;
+            // The usual case, a few dozen keys: in every wave lane j holds key j, and wave w ranks
+            // keys 4w .. 4w + 3, each by one ballot ("which keys are larger?").  A key among the
+            // B best is written out at once; if one of them is a second largest, the verdict word
+            // sends everybody on to the general path, which writes all B results again.  (One
+            // wave ranking all keys by a loop of lane broadcasts took 0.6 us; all 16 waves ranking
+            // all keys, to save the barrier, was slower still: they share four instruction issuers.)
+            {
+                const uint64_t mine = (ln < mr) ? sh.list[ln] : 0ull;   // (real keys are never 0)
+                const uint32_t second = (ln < mr && sh.open_list[ln] != 0u) ? 1u : 0u;
                 const uint32_t lo = (uint32_t)mine, hi = (uint32_t)(mine >> 32);
-                uint32_t rank = 0;
-                for (int j = 0; j < mr; ++j) {   // (j is wave-uniform)
-                    const uint64_t other = ((uint64_t)wave_read_lane(hi, j) << 32) | wave_read_lane(lo, j);
-                    rank += (other > mine) ? 1u : 0u;
+                uint64_t key = 0;
+                uint32_t rank = 0xFFFFFFFFu, sec = 0;
+#pragma unroll
+                for (int q = 0; q < kWave / kSelWaves; ++q) {
+                    const int e = wv * (kWave / kSelWaves) + q;   // (wave-uniform)
+                    if (e >= mr) break;
+                    const uint64_t ke = ((uint64_t)wave_read_lane(hi, e) << 32) | wave_read_lane(lo, e);
+                    const uint32_t r = (uint32_t)__popcll(__ballot(mine > ke));
+                    const uint32_t se = wave_read_lane(second, e);
+                    if (ln == q) { key = ke; rank = r; sec = se; }
                 }
-                const bool hidden = __ballot(ln < mr && rank < (uint32_t)B && second) != 0ull;
-                if (ln == 0) sh.misc[6] = hidden ? 1u : 0u;
-                if (!hidden) {
+                if (rank < (uint32_t)B) {   // (lanes 0..3 at most)
+                    if (sec) sh.misc[6] = 1u;
+                    const size_t o = o0 + rank;
+                    const float score = key_value(key);
+                    const uint32_t idx = key_index(key);
+                    const bool none = score == -INFINITY || score != score;
+                    out_beam[o] = none ? -1 : (int)(idx >> 24);
+                    out_word[o] = none ? -1 : (int)(idx & 0xFFFFFFu);
+                    out_score[o] = none ? -INFINITY : score;
+                }
+                if (wv == 0)
                     for (int e = ln + min(mr, B); e < B; e += kWave) {
                         out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
                     }
-                    if (ln < mr && rank < (uint32_t)B) {
-                        const size_t o = o0 + rank;
-                        const float score = key_value(mine);
-                        const uint32_t idx = key_index(mine);
-                        const bool none = score == -INFINITY || score != score;
-                        out_beam[o] = none ? -1 : (int)(idx >> 24);
-                        out_word[o] = none ? -1 : (int)(idx & 0xFFFFFFu);
-                        out_score[o] = none ? -INFINITY : score;
-                    }
-                }
             }
             LSH_TRACE_ANY(2, 4);
             __syncthreads();
