@@ -529,6 +529,40 @@ def test_all_logits_tie_orders_by_beam_then_word():
     assert gb[0].tolist() == [0, 0, 0, 0] and gw[0].tolist() == [0, 1, 2, 3]
 
 
+def test_many_beams_ties_dead_beams_and_padding():
+    # 33..64 beams take the contraction that leaves one tile record per group of tiles and the
+    # selection that reads them 16 lanes per row: its degenerate inputs
+    cfg, gc = case("tiny")
+    B = 40
+    rng = np.random.default_rng(40)
+    Hz = np.zeros((2 * B, cfg.d), dtype=np.float32)
+    # every score of a sentence ties: more qualifying tiles than the selection lists, the exact
+    # radix select decides: lowest beam first, then lowest word
+    bs = np.zeros(2 * B, np.float32)
+    bs[B + 7] = 1.0                                   # second sentence: one beam ahead of the rest
+    gb, gw, gs, sp, ws = gc.step(Hz, bs, 2, B)
+    cand = gc.index.candidates(Hz[:B], gc.topfreq)
+    assert np.array_equal(gc.tables.debug_candidates(ws, sp, 0), cand) and len(cand) >= B
+    assert gb[0].tolist() == [0] * B and gw[0].tolist() == cand[:B].tolist()
+    assert gb[1].tolist() == [7] * B and gw[1].tolist() == cand[:B].tolist()
+    np.testing.assert_allclose(gs[0], -np.log(len(cand)), rtol=1e-6)
+    np.testing.assert_allclose(gs[1], 1 - np.log(len(cand)), rtol=1e-6)
+    # two live beams among 40, then none
+    H = hidden(cfg, gc, 20).reshape(-1, cfg.d)[:B]
+    bs = np.full(B, -np.inf, dtype=np.float32)
+    bs[3], bs[38] = -0.5, 0.25
+    gb, gw, gs, _ = run_and_check(cfg, gc, H, bs, 1, B)
+    assert set(gb[0].tolist()) <= {3, 38}
+    bs[:] = -np.inf
+    gb, gw, gs, sp, ws = gc.step(H, bs, 1, B)
+    assert np.all(gb == -1) and np.all(gw == -1) and np.all(np.isneginf(gs))
+    # fewer finite pairs than beams: one live beam, no LSH hits, five top-frequent words
+    bs[11] = 0.0
+    gb, gw, gs, sp, ws = gc.step(H, bs, 1, B, T=5, threshold=cfg.W + 1)
+    assert (gb[0] >= 0).sum() == 5 and np.all(gb[0][:5] == 11) and np.all(gb[0][5:] == -1)
+    assert sorted(gw[0][:5].tolist()) == sorted(gc.topfreq[:5].tolist()) and np.all(np.isneginf(gs[0][5:]))
+
+
 def test_topfreq_out_of_range_ids_and_duplicates_are_harmless():
     cfg, gc = case("tiny")
     H = hidden(cfg, gc, 1)[0]
