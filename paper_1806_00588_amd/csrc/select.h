@@ -341,7 +341,7 @@ __device__ __forceinline__ uint32_t select_front_grouped(SelShared& sh, int s, c
 #pragma unroll
     for (int u = 0; u < KEPT; ++u) { nt[u] = tiles_of(c + 16 * u, &ft[u]); r[u] = load(c + 16 * u, nt[u]); }
     float m = fmaxf(fmaxf(r[0].x, r[1].x), fmaxf(r[2].x, r[3].x));
-    for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
+    if (nrec > 16 * KEPT) for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
         int f;
         m = fmaxf(m, load(it.j, tiles_of_group(it.j, it.w, it.grp, &f)).x);
     }
@@ -350,7 +350,7 @@ __device__ __forceinline__ uint32_t select_front_grouped(SelShared& sh, int s, c
     if (M != -INFINITY) {
 #pragma unroll
         for (int u = 0; u < KEPT; ++u) sum += r[u].y * __expf(r[u].x - M);   // padding: 0 * 0
-        for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
+        if (nrec > 16 * KEPT) for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
             int f;
             const float2 e = load(it.j, tiles_of_group(it.j, it.w, it.grp, &f));
             sum += e.y * __expf(e.x - M);
@@ -362,22 +362,41 @@ __device__ __forceinline__ uint32_t select_front_grouped(SelShared& sh, int s, c
     const uint32_t tau = block_kth_largest_lb(lmax, B, &sh);
     // every tile of every group whose maximum reaches tau: one reservation per lane
     auto reaches = [&](float x) { return row_ok && x != -INFINITY && f32_sortable(bsi + (x - lse) + 0.0f) >= tau; };
+    // Every instruction here is issued by all 16 waves, four to a SIMD, whether its lanes have
+    // anything to list or not: one reservation per wave (the lanes' counts scanned on the DPP
+    // network), and a wave skips the records none of its lanes lists.  A lane writes the (at most
+    // eight) tiles of its record without a loop: the counts differ from lane to lane.
     auto put = [&](uint32_t pos, int first, int n) {
-        for (int k = 0; k < n; ++k)
-            if (pos + (uint32_t)k < (uint32_t)kSelOpenCap) sh.open_list[pos + k] = ((uint32_t)row << 20) | (uint32_t)(first + k * G);
+#pragma unroll
+        for (int k = 0; k < kGroupTiles; ++k)
+            if (k < n && pos + (uint32_t)k < (uint32_t)kSelOpenCap)
+                sh.open_list[pos + k] = ((uint32_t)row << 20) | (uint32_t)(first + k * G);
     };
     int total = 0;
 #pragma unroll
     for (int u = 0; u < KEPT; ++u) { if (!reaches(r[u].x)) nt[u] = 0; total += nt[u]; }
-    if (total) {
-        uint32_t pos = atomicAdd(&sh.misc[5], (uint32_t)total);
+    {
+        const uint32_t incl = wave_incl_scan((uint32_t)total);
+        const uint32_t wave_total = wave_read_lane(incl, kWave - 1);
+        if (wave_total) {   // (uniform)
+            uint32_t base = 0;
+            if (ln == 0) base = atomicAdd(&sh.misc[5], wave_total);
+            uint32_t pos = wave_read_lane(base, 0) + incl - (uint32_t)total;   // this lane's first entry
 #pragma unroll
-        for (int u = 0; u < KEPT; ++u) { put(pos, ft[u], nt[u]); pos += (uint32_t)nt[u]; }
+            for (int u = 0; u < KEPT; ++u) {
+                if (__ballot(nt[u] > 0) != 0ull) put(pos, ft[u], nt[u]);   // (uniform)
+                pos += (uint32_t)nt[u];
+            }
+        }
     }
-    for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
+    if (nrec > 16 * KEPT) for (Walk it = walk_begin(); it.j < nrec; walk_next(it)) {
         int f;
         const int n = tiles_of_group(it.j, it.w, it.grp, &f);
-        if (n > 0 && reaches(load(it.j, n).x)) put(atomicAdd(&sh.misc[5], (uint32_t)n), f, n);
+        if (n > 0 && reaches(load(it.j, n).x)) {
+            const uint32_t pos = atomicAdd(&sh.misc[5], (uint32_t)n);
+            for (int k = 0; k < n; ++k)
+                if (pos + (uint32_t)k < (uint32_t)kSelOpenCap) sh.open_list[pos + k] = ((uint32_t)row << 20) | (uint32_t)(f + k * G);
+        }
     }
     return tau;
 }
@@ -792,33 +811,42 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
     LSH_TRACE_ANY(2, 6);
     __syncthreads();
     LSH_TRACE_ANY(2, 7);
-    // (b) 16 lanes per tile, 64 tiles per sweep of the workgroup, four sweeps in flight
+    // (b) 16 lanes per tile, 64 tiles per sweep of the workgroup, four sweeps in flight -- eight
+    //     when that makes one round trip to memory of two (the logits were written by other
+    //     XCDs: every sweep batch is a cold read)
     const uint32_t n_open = sh.misc[5];
     if (n_open <= (uint32_t)kSelOpenCap) {
-        for (uint32_t g0 = (uint32_t)(tid >> 4); g0 < n_open; g0 += 4 * (kSelThreads / 16)) {
-            float x[4], lsev[4], bsq[4];
-            int c[4], iq[4];
+        auto open_tiles = [&](auto in_flight) {
+            constexpr int U = decltype(in_flight)::value;
+            for (uint32_t g0 = (uint32_t)(tid >> 4); g0 < n_open; g0 += U * (kSelThreads / 16)) {
+                float x[U], lsev[U], bsq[U];
+                int c[U], iq[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t j = g0 + u * (kSelThreads / 16);
-                const uint32_t ent = sh.open_list[min(j, n_open - 1)];
-                iq[u] = (int)(ent >> 20);
-                const int cc = (int)(ent & 0xFFFFFu) * tn + (ln & 15);
-                c[u] = (j < n_open && (ln & 15) < tn && cc < C) ? cc : -1;
-                x[u] = lg[(size_t)iq[u] * cpitch + max(c[u], 0)];
-                lsev[u] = sh.lse[iq[u]];
-                bsq[u] = sh.bs[iq[u]];
-            }
+                for (int u = 0; u < U; ++u) {
+                    const uint32_t j = g0 + u * (kSelThreads / 16);
+                    const uint32_t ent = sh.open_list[min(j, n_open - 1)];
+                    iq[u] = (int)(ent >> 20);
+                    const int cc = (int)(ent & 0xFFFFFu) * tn + (ln & 15);
+                    c[u] = (j < n_open && (ln & 15) < tn && cc < C) ? cc : -1;
+                    x[u] = lg[(size_t)iq[u] * cpitch + max(c[u], 0)];
+                    lsev[u] = sh.lse[iq[u]];
+                    bsq[u] = sh.bs[iq[u]];
+                }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float sc = bsq[u] + (x[u] - lsev[u]);
-                if (c[u] >= 0 && f32_sortable(sc + 0.0f) >= tau) {
-                    const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
-                    if (pos < (uint32_t)kSelListCap)
-                        sh.list[pos] = make_key(sc, ((uint32_t)iq[u] << 24) | (uint32_t)c[u]);
+                for (int u = 0; u < U; ++u) {
+                    const float sc = bsq[u] + (x[u] - lsev[u]);
+                    if (c[u] >= 0 && f32_sortable(sc + 0.0f) >= tau) {
+                        const uint32_t pos = atomicAdd(&sh.misc[4], 1u);
+                        if (pos < (uint32_t)kSelListCap)
+                            sh.list[pos] = make_key(sc, ((uint32_t)iq[u] << 24) | (uint32_t)c[u]);
+                    }
                 }
             }
-        }
+        };
+        if (n_open > 4u * (kSelThreads / 16) && n_open <= 8u * (kSelThreads / 16))
+            open_tiles(std::integral_constant<int, 8>{});
+        else
+            open_tiles(std::integral_constant<int, 4>{});
         LSH_TRACE_ANY(2, 8);
     } else if (tid == 0) {
         sh.misc[4] = kSelListCap + 1;  // too many qualifying tiles (heavy ties): exact select below
