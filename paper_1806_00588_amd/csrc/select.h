@@ -401,6 +401,178 @@ __device__ __forceinline__ uint32_t select_front_grouped(SelShared& sh, int s, c
     return tau;
 }
 
+// The whole selection for the shape the fused kernels usually serve -- rich records, at most 16
+// beams (a wave per hidden row), at most 512 tiles (eight records per lane) -- written out on its
+// own, because this kernel is bound by instruction issue as much as by its trips to memory: the
+// 16 waves of the workgroup share four SIMDs, a wave's vector instruction takes a SIMD for four
+// cycles, and the general code below spends two fifths of its instructions on cases that cannot
+// occur here (several batches per row, several rows per wave, records kept for a second pass).
+// Same arithmetic and the same keys as the general path's short cut; returns false, having
+// written nothing final, when that path has to decide: more than 64 listed entries, or a second
+// largest among the B best (a tile may hide a third).  C_known < 0: the list's length is count[s];
+// *C_out receives it.  Eight records per lane are asked for before that length is known; a list
+// of up to 256 tiles -- a dozen beams over a few thousand candidates -- then runs the code for
+// four (Q = 4), a longer one the code for eight.  The word id of a tile's second largest logit is
+// fetched only when that logit reaches the threshold (on the benchmark's chained steps: never).
+constexpr int kSmallQ = 8;
+template <bool SAME_KERNEL, int Q>
+__device__ __forceinline__ bool select_rich_small_body(SelShared& sh, int s, float bsi, float4 (&rec)[kSmallQ],
+                                                       const int32_t* ids2_row, int ntiles, int B, float* lse_out,
+                                                       int32_t* out_beam, int32_t* out_word, float* out_score) {
+    const int tid = threadIdx.x, ln = lane_id(), wv = wave_id();
+    const bool has_row = wv < B;
+    if (tid == 0) { sh.misc[4] = 0; sh.misc[6] = 0; }
+
+    // log-sum-exp of the row, the lane's best tile maximum
+    // (the arithmetic of the general path, operation for operation: the plans agree bit for bit)
+    uint32_t best = 0;
+    float lse = 0.f;
+    if (has_row) {
+        float m = -INFINITY;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            if (ln + q * kWave >= ntiles) rec[q] = empty_record<float4>();
+            m = fmaxf(m, rec[q].x);
+        }
+        float sum = 0.f;
+        if (m != -INFINITY) {
+#pragma unroll
+            for (int q = 0; q < Q; ++q) sum += rec[q].y * __expf(rec[q].x - m);   // padding: 0 * 0
+        }
+        const float M = wave_max_f32(m);
+        const float part = wave_sum_f32((m == -INFINITY) ? 0.f : sum * __expf(m - M));
+        lse = M + logf(part);
+        if (ln == 0) lse_out[s * B + wv] = lse;
+        if (m != -INFINITY) best = f32_sortable(bsi + (m - lse) + 0.0f);
+    }
+    // tau: the largest over the rows of "B-th largest lane value of the row" (B distinct tile
+    // maxima are >= it)
+    const uint32_t kth = wave_kth_largest_sort(best, B);
+    if (ln == 0) sh.wtau[wv] = kth;
+    __syncthreads();
+    uint32_t tau = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) tau = max(tau, sh.wtau[w]);
+
+    // every largest / second largest score >= tau, one list reservation per wave
+    if (has_row) {
+        uint32_t key1[Q], key2[Q];
+        int32_t id2[Q];
+        bool any2 = false;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) {
+            key1[q] = f32_sortable(bsi + (rec[q].x - lse) + 0.0f);
+            key2[q] = f32_sortable(bsi + (rec[q].z - lse) + 0.0f);
+            const bool in = ln + q * kWave < ntiles;
+            if (!(in && __float_as_int(rec[q].w) >= 0 && key1[q] >= tau)) key1[q] = 0;   // (real keys are > 0)
+            if (!(in && key2[q] >= tau)) key2[q] = 0;
+            id2[q] = -1;
+            any2 = any2 || key2[q] != 0;
+        }
+        if (__ballot(any2) != 0ull) {   // (uniform; rare)
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                if (key2[q]) id2[q] = load_id2<SAME_KERNEL>(ids2_row + ln + q * kWave);
+                if (id2[q] < 0) key2[q] = 0;
+            }
+        }
+        uint32_t mine = 0;
+#pragma unroll
+        for (int q = 0; q < Q; ++q) mine += (key1[q] ? 1u : 0u) + (key2[q] ? 1u : 0u);
+        const uint32_t incl = wave_incl_scan(mine);
+        const uint32_t wave_total = wave_read_lane(incl, kWave - 1);
+        if (wave_total) {   // (uniform)
+            uint32_t base = 0;
+            if (ln == 0) base = atomicAdd(&sh.misc[4], wave_total);
+            uint32_t pos = wave_read_lane(base, 0) + incl - mine;
+#pragma unroll
+            for (int q = 0; q < Q; ++q) {
+                if (key1[q]) {
+                    if (pos < (uint32_t)kWave) {
+                        sh.list[pos] = ((uint64_t)key1[q] << 32) |
+                                       (uint64_t)(~(((uint32_t)wv << 24) | (uint32_t)__float_as_int(rec[q].w)));
+                        sh.open_list[pos] = 0u;
+                    }
+                    ++pos;
+                }
+                if (key2[q]) {
+                    if (pos < (uint32_t)kWave) {
+                        sh.list[pos] = ((uint64_t)key2[q] << 32) | (uint64_t)(~(((uint32_t)wv << 24) | (uint32_t)id2[q]));
+                        sh.open_list[pos] = 1u;   // a second largest
+                    }
+                    ++pos;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int mr = (int)sh.misc[4];
+    if (mr > kWave) return false;   // (uniform; a longer list is the general path's)
+
+    // ranks by ballot: in every wave lane j holds entry j, wave w ranks entries 4w .. 4w + 3
+    const size_t o0 = (size_t)s * B;
+    const uint64_t mine = (ln < mr) ? sh.list[ln] : 0ull;
+    const uint32_t second = (ln < mr && sh.open_list[ln] != 0u) ? 1u : 0u;
+    const uint32_t lo = (uint32_t)mine, hi = (uint32_t)(mine >> 32);
+    uint64_t key = 0;
+    uint32_t rank = 0xFFFFFFFFu, sec = 0;
+#pragma unroll
+    for (int q = 0; q < kWave / kSelWaves; ++q) {
+        const int e = wv * (kWave / kSelWaves) + q;   // (wave-uniform)
+        if (e >= mr) break;
+        const uint64_t ke = ((uint64_t)wave_read_lane(hi, e) << 32) | wave_read_lane(lo, e);
+        const uint32_t r = (uint32_t)__popcll(__ballot(mine > ke));
+        const uint32_t se = wave_read_lane(second, e);
+        if (ln == q) { key = ke; rank = r; sec = se; }
+    }
+    if (rank < (uint32_t)B) {   // (lanes 0..3 at most)
+        if (sec) sh.misc[6] = 1u;
+        const size_t o = o0 + rank;
+        const float score = key_value(key);
+        const uint32_t idx = key_index(key);
+        const bool none = score == -INFINITY || score != score;
+        out_beam[o] = none ? -1 : (int)(idx >> 24);
+        out_word[o] = none ? -1 : (int)(idx & 0xFFFFFFu);
+        out_score[o] = none ? -INFINITY : score;
+    }
+    if (wv == 0)
+        for (int e = ln + min(mr, B); e < B; e += kWave) {
+            out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
+        }
+    __syncthreads();
+    return sh.misc[6] == 0u;
+}
+
+template <bool SAME_KERNEL>
+__device__ __forceinline__ bool select_rich_small(SelShared& sh, int s, const TileRecord* records, const int32_t* ids2,
+                                                  int64_t ppitch, const int32_t* count, int C_known, int V, int B,
+                                                  const float* beam_scores, float* lse_out, int32_t* out_beam,
+                                                  int32_t* out_word, float* out_score, int tile_forced, int* C_out) {
+    const int ln = lane_id(), wv = wave_id();
+    // everything whose address is known is asked for at once: the row's beam score, its records
+    // (indices clamped to the allocated pitch; what lies past the last tile is masked later) and
+    // the list's length
+    float bsi = 0.f;
+    float4 rec[kSmallQ];
+    const size_t r0 = ((size_t)s * B + min(wv, B - 1)) * ppitch;
+    if (wv < B) {
+        bsi = beam_scores[s * B + wv];
+#pragma unroll
+        for (int q = 0; q < kSmallQ; ++q)
+            rec[q] = load_record<SAME_KERNEL>(records + r0 + min((int64_t)(ln + q * kWave), ppitch - 1));
+    }
+    const int C = C_known >= 0 ? C_known : (count ? count[s] : V);
+    const int tn = select_tile_width(C, tile_forced, ppitch);
+    const int ntiles = (C + tn - 1) / tn;
+    *C_out = C;
+    if (ntiles == 0 || ntiles > kSmallQ * kWave) return false;   // (uniform, like every return here)
+    if (ntiles <= 4 * kWave)
+        return select_rich_small_body<SAME_KERNEL, 4>(sh, s, bsi, rec, ids2 + r0, ntiles, B, lse_out, out_beam, out_word,
+                                                      out_score);
+    return select_rich_small_body<SAME_KERNEL, 8>(sh, s, bsi, rec, ids2 + r0, ntiles, B, lse_out, out_beam, out_word,
+                                                  out_score);
+}
+
 template <bool RICH, bool SAME_KERNEL = false, bool GROUPS = false>
 __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const float* logits, int64_t cpitch,
                                                 const TileRecord* records, const int32_t* ids2, int64_t ppitch,
@@ -408,6 +580,16 @@ __device__ __forceinline__ void select_sentence(SelShared& sh, int s, const floa
                                                 int V, int B, const float* beam_scores, float* lse_out,
                                                 int32_t* out_beam, int32_t* out_word, float* out_score,
                                                 int tile_forced = 0, int rec_groups = 0) {
+    if constexpr (RICH) {
+        if (B <= kSelWaves) {
+            int C_seen = C_known;
+            if (select_rich_small<SAME_KERNEL>(sh, s, records, ids2, ppitch, count, C_known, V, B, beam_scores, lse_out,
+                                               out_beam, out_word, out_score, tile_forced, &C_seen))
+                return;
+            C_known = C_seen;   // (the general path need not ask again)
+            __syncthreads();    // (not this shape, or a tile may hide a winner: everybody has read the verdict)
+        }
+    }
     typedef typename std::conditional<RICH, float4, float2>::type REC;
     const REC* partials = reinterpret_cast<const REC*>(records);
     // batches of tile maxima a wave keeps in registers between the passes (rich records: also the
