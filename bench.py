@@ -161,8 +161,14 @@ class Workload:
                 run_steps(0, count, self.stream_ptr())
         go(warmup)
         torch.cuda.synchronize()
+        done = torch.cuda.Event()
         t = time.perf_counter()
         go(n_steps)
+        # (the host polls for the end of the work before it synchronizes: a blocking wait is woken
+        # tens of microseconds late, which a 20-step run would book as step time)
+        done.record()
+        while not done.query():
+            pass
         torch.cuda.synchronize()
         return time.perf_counter() - t, mode
 
