@@ -447,7 +447,8 @@ __device__ __forceinline__ bool select_rich_small_body(SelShared& sh, int s, flo
     }
     // tau: the largest over the rows of "B-th largest lane value of the row" (B distinct tile
     // maxima are >= it)
-    const uint32_t kth = wave_kth_largest_sort(best, B);
+    // (waves without a row skip the sorting network: their issue slots are the others')
+    const uint32_t kth = has_row ? wave_kth_largest_sort(best, B) : 0u;
     if (ln == 0) sh.wtau[wv] = kth;
     __syncthreads();
     uint32_t tau = 0;

@@ -715,15 +715,17 @@ def test_fused_kernel_with_every_tile_width(width, force):
     run_and_check(cfg, gc, H[1], np.linspace(-2, 0, cfg.R).astype(np.float32), cfg.S, cfg.B)
 
 
+@pytest.mark.parametrize("V", [640, 6400])
 @pytest.mark.parametrize("one_launch", [1, 0])
-def test_winners_that_share_a_tile(one_launch, force):
+def test_winners_that_share_a_tile(one_launch, V, force):
     # The selection of the fused plans works from per-tile records (largest and second largest
     # logit of each row and tile) and must notice when a tile hides a third winner.  Here the
     # candidate list is all of V in id order (every id is "top-frequent"), so tile = id / 16, and
     # the words of one tile are near copies of the hidden direction: for the dominant beam all B
     # winners sit in that one tile; other steps put two winners into one tile, or one per tile.
+    # (40 tiles, or 400: the selection's code for four, or for eight, records per lane)
     rng = np.random.default_rng(16)
-    V, d, K, P, W = 640, 32, 4, 8, 2
+    d, K, P, W = 32, 4, 8, 2
     E = rng.standard_normal((V, d)).astype(np.float32)
     base = rng.standard_normal(d).astype(np.float32)
     for k in range(16):
