@@ -243,7 +243,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     // Everything whose address is known up front is requested before anything is waited for:
     // this thread's band descriptor (its (row-in-chunk, band) pair is fixed), its first
     // top-frequent id, and its share of the first chunk of hidden rows.
-    const uint32_t my_w = (uint32_t)(tid % W);
+    const uint32_t my_w = (uint32_t)(tid - small_div(tid, W) * W);   // (tid < 1024, W <= P <= 1024)
     const BandMeta my_meta = bands[my_w];
     int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
     const float* H0 = H + (size_t)s * B * d;
@@ -327,7 +327,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         };
         if (par_codes) {
             if (tid < rows * P) {
-                const int i = tid / P, p = tid - i * P;
+                const int i = small_div(tid, P), p = tid - i * P;
                 codes[tid] = (uint32_t)wta(stage + (size_t)i * d, lperms + (size_t)p * K);
             }
             __syncthreads();
@@ -337,7 +337,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         int32_t code = 0;
         int4 slot0, slot1;
         if (tid < npairs) {
-            const int i = tid / W;
+            const int i = small_div(tid, W);
             w = my_w;
             for (int q = 0; q < u; ++q) {
                 const int best = par_codes

@@ -90,7 +90,7 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
     const int C = (int)total;
 
     const int tn = select_tile_width(C, tail.tile_forced, recs.pitch);
-    const int ntiles = (C + tn - 1) / tn;
+    const int ntiles = tn == kTileN ? (C + kTileN - 1) >> 4 : (C + tn - 1) / tn;   // (no division in the usual case)
     const int col = ln & 15;
     for (int base = 0; g + base * G < ntiles; base += kFusedRound) {
         // ids of the tiles g + (base + k) G, k < kFusedRound, into tile_ids[k][16]
