@@ -207,7 +207,15 @@ struct CandArgs {
     int T;
     const uint4* cuts;       // per slot: where the vocabulary slices 1, 2, 3 begin inside its span
     int stage_words;         // LDS words for the staged hidden rows (>= d, a multiple of 4)
+    // derived on the host (set_derived), so that no division stands before the kernel's first loads
+    int rows_chunk;          // candidates_rows_per_chunk(B, d, W, stage_words)
+    int u;                   // P / W codes per band
 };
+
+inline void set_derived(CandArgs& a) {
+    a.rows_chunk = candidates_rows_per_chunk(a.B, a.d, a.W, a.stage_words);
+    a.u = a.P / a.W;
+}
 
 // Builds sentence s's presence bitmap (V bits, at smem[0 .. ceil(V/32))) in LDS: hashing, cuckoo
 // probes, bucket walk and the top-frequent words.  Only the sentence's rows [row_begin, row_end)
@@ -234,8 +242,8 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     uint32_t* wsum = p_pref + kCandThreads;                // scan scratch (>= kCandWaves + 1)
 
     const int tid = threadIdx.x;
-    const int u = P / W;
-    const int rows_per_chunk = candidates_rows_per_chunk(B, d, W, stage_words);
+    const int u = a.u;
+    const int rows_per_chunk = a.rows_chunk;
     if (row_end < 0) row_end = B;
     LSH_TRACE(0, 0);
     LSH_TRACE_WG(0);

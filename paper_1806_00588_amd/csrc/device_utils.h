@@ -155,7 +155,7 @@ __device__ __forceinline__ void publish_wait() { asm volatile("s_waitcnt vmcnt(0
 // vector instructions instead of the ~25 of an integer division: (x + 0.5) / y is at least
 // 0.5 / 1024 away from every integer, the float product errs by far less.
 __device__ __forceinline__ int small_div(int x, int y) {
-    return (int)(((float)x + 0.5f) * __frcp_rn((float)y));
+    return (int)(((float)x + 0.5f) * __builtin_amdgcn_rcpf((float)y));   // (v_rcp_f32: 1 ulp, ample here)
 }
 
 // Workgroup barrier for data that is exchanged through LDS only: waits for this wave's LDS

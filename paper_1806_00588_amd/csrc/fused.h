@@ -170,8 +170,9 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
               int32_t* __restrict__ count, float* __restrict__ logits, int64_t cpitch,
               TileRecords recs, TailArgs tail) {
     extern __shared__ uint32_t smem[];
-    const int s = blockIdx.x % S;
-    const int g = blockIdx.x / S, G = gridDim.x / S;
+    // (one sentence, the usual case of this plan: no division before the first loads)
+    const int s = S == 1 ? 0 : blockIdx.x % S;
+    const int g = S == 1 ? blockIdx.x : blockIdx.x / S, G = S == 1 ? gridDim.x : gridDim.x / S;
     const int V = a.V, B = a.B;
     uint32_t* bm = smem;
     uint32_t* wsum = smem + candidates_lds_words(V, a.P, a.K, a.stage_words) - 64;
@@ -182,7 +183,7 @@ k_cand_logits(CandArgs a, const ET* __restrict__ E, int64_t ld, int S, int32_t* 
     // when the whole sentence was hashed in one chunk its hidden rows are still staged in LDS:
     // the contraction takes its A operands from there instead of reading H again
     const float* h_lds = nullptr;
-    if (candidates_rows_per_chunk(B, a.d, a.W, a.stage_words) >= B && (a.d & 3) == 0)
+    if (a.rows_chunk >= B && (a.d & 3) == 0)
         h_lds = reinterpret_cast<const float*>(smem + bitmap_words_padded(V));
     tiles_from_bitmap<ET, ALIGNED, ONE_LAUNCH>(bm, wsum, tile_ids, red, h_lds, E, ld, a.d, a.H, B, V, s, g, G, cand,
                                    count, logits, cpitch, recs, tail, smem);

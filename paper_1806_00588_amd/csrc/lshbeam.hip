@@ -750,6 +750,7 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
     const int stage = stage_words_for(t, sp->B, fused);
     CandArgs ca{H_dev, sp->B, t->d, t->perms_dev, t->P, t->K, t->W, t->bits, t->slots_dev,
                 t->bands_dev, t->words_dev, t->V, topfreq_dev, sp->T, t->cuts_dev, stage};
+    set_derived(ca);
     // Bitmaps made by an earlier kernel, to be OR-ed per sentence: one per hidden row when the
     // hit threshold is above 1 (Eq. 9-10), one per part of the sentence when it has many beams.
     const uint32_t* parts = nullptr;
@@ -762,6 +763,7 @@ lsh_status decode_step_impl(const lsh_tables* t, const float* H_dev, const float
     } else if (const int pr = part_rows_of(t, sp, stage)) {
         nparts = (sp->B + pr - 1) / pr;
         ca.stage_words = candidates_min_stage(t->d);
+        set_derived(ca);
         launch(cx, 4, k_part_bitmaps, dim3(sp->S * nparts), dim3(kCandThreads), (size_t)t->wg_candidates_lds,
                ca, pr, nparts, w.row_bitmaps);
         parts = w.row_bitmaps;
