@@ -231,6 +231,43 @@ def test_maximum_beam_and_sentence_counts():
         assert gc.lsh.step_workspace_bytes(gc.tables, binding.step_params(S_bad, B_bad, 0, 1, False)) == 0
 
 
+# Shapes between the named configurations, chosen to sit on the launch plans' boundaries (16/17,
+# 32/33, 64/65 beams; one, a few and many sentences; 1-, 2- and 4-bit codes; one code per band
+# and five; hidden sizes that are tiny, not a multiple of four, or above 1024; bf16 rows; hit
+# thresholds), each with every sentence checked in full against the oracle, plan left to the
+# library.  (V, d, K, P, W, T, centres, bf16, [(S, B, t), ...])
+_SWEEP = [
+    (5000, 200, 4, 24, 6, 300, 250, False, [(1, 12, 1), (1, 16, 1), (2, 16, 1), (1, 17, 1), (1, 32, 1),
+                                            (1, 33, 1), (1, 48, 1), (1, 64, 1), (1, 65, 1), (6, 12, 1),
+                                            (24, 8, 1), (3, 12, 2), (1, 40, 2)]),
+    (3000, 6, 2, 20, 4, 0, 40, False, [(1, 5, 1), (7, 3, 1), (1, 70, 1)]),
+    (9000, 1001, 3, 12, 12, 128, 300, False, [(1, 12, 1), (2, 33, 1), (12, 6, 1)]),
+    (20000, 1000, 8, 30, 6, 700, 500, False, [(1, 12, 1), (3, 12, 1), (1, 50, 1), (1, 12, 3)]),
+    (7000, 1500, 16, 8, 2, 64, 200, False, [(1, 8, 1), (2, 36, 1), (9, 9, 1)]),
+    (6000, 256, 8, 32, 8, 500, 300, True, [(1, 12, 1), (8, 16, 1), (2, 40, 1), (20, 4, 1), (2, 10, 2)]),
+    (4100, 1024, 8, 16, 4, 1000, 100, True, [(1, 16, 1), (5, 24, 1)]),
+]
+
+
+@pytest.mark.parametrize("shape", _SWEEP, ids=lambda sh: "V%d-d%d-K%d-P%d-W%d-T%d%s" % (
+    sh[0], sh[1], sh[2], sh[3], sh[4], sh[5], "-bf16" if sh[7] else ""))
+def test_shapes_between_the_named_configurations(shape):
+    V, d, K, P, W, T, nc, bf16, runs = shape
+    sd = 1.0 / np.sqrt(d)
+    cfg = workloads.Config("sweep", d, V, 1, 1, K, P, W, T, nc, sd, 0.3 * sd, 0.8, 0.3 * sd, 1,
+                           workloads.BF16 if bf16 else workloads.F32, 0.05)
+    gc = GpuCase.from_config(cfg, seed=V + d)
+    rng = np.random.default_rng(V * 31 + d)
+    for S, B, t in runs:
+        import dataclasses
+        c = dataclasses.replace(cfg, S=S, B=B)
+        H = workloads.make_hidden(c, gc.E, seed=S * 1000 + B, steps=1)[0]
+        bs = (rng.standard_normal(S * B) * 1.5).astype(np.float32)
+        run_and_check(c, gc, H, bs, S, B, threshold=t)
+    S, B, _ = runs[0]
+    run_and_check(c, gc, H[:S * B], bs[:S * B], S, B, full_vocab=True, check_lp=V <= 6000)
+
+
 def test_paper_shape_steps():
     cfg, gc = case("paper")
     H = hidden(cfg, gc, cfg.steps)
