@@ -184,12 +184,20 @@ __device__ __forceinline__ void mark_ids_of_wave(uint32_t* bm, int V, int32_t id
     }
     if (ok && ((todo >> ln) & 1ull)) atomicOr(&bm[word], bit);
 }
+// `second`: list[tid + kCandThreads] likewise (or -1; id_list_second() asks for it).
+__device__ __forceinline__ int32_t id_list_second(const int32_t* __restrict__ list, int T) {
+    const int i = (int)threadIdx.x + kCandThreads;
+    return (T > kCandThreads && i < T) ? list[i] : -1;   // (a uniform branch for short lists)
+}
+template <bool SECOND = false>
 __device__ __forceinline__ void mark_id_list(uint32_t* bm, int V, const int32_t* __restrict__ list,
-                                             int T, int32_t first) {
-    // the first round has its ids in registers: kept apart from the loop so that it contains no
-    // load (and no wait that would also cover loads the caller has in flight)
+                                             int T, int32_t first, int32_t second = -1) {
+    // the first round (with SECOND, the first two) has its ids in registers: kept apart from the
+    // loop so that it contains no load (and no wait that would also cover loads the caller has
+    // in flight)
     if (T > 0) mark_ids_of_wave(bm, V, first);
-    for (int i = kCandThreads + (int)threadIdx.x; i - (int)threadIdx.x < T; i += kCandThreads)
+    if (SECOND && T > kCandThreads) mark_ids_of_wave(bm, V, second);
+    for (int i = (SECOND ? 2 : 1) * kCandThreads + (int)threadIdx.x; i - (int)threadIdx.x < T; i += kCandThreads)
         mark_ids_of_wave(bm, V, (i < T) ? list[i] : -1);
 }
 
@@ -221,6 +229,10 @@ inline void set_derived(CandArgs& a) {
 // probes, bucket walk and the top-frequent words.  Only the sentence's rows [row_begin, row_end)
 // are hashed (row_end < 0: all B).  Called by all kCandThreads threads of a workgroup with
 // candidates_lds_words() words of LDS; ends with a workgroup barrier.
+// DEEP (for the kernels that have the registers): walks of more than eight elements per thread
+// keep twelve span reads in flight, and the second thousand of top-frequent ids is asked for up
+// front too.
+template <bool DEEP = false>
 __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, uint32_t* smem,
                                                       int row_begin = 0, int row_end = -1) {
     const float* __restrict__ H = a.H;
@@ -253,7 +265,8 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     // top-frequent id, and its share of the first chunk of hidden rows.
     const uint32_t my_w = (uint32_t)(tid - small_div(tid, W) * W);   // (tid < 1024, W <= P <= 1024)
     const BandMeta my_meta = bands[my_w];
-    int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
+    const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
+    const int32_t tf_second = DEEP ? id_list_second(topfreq, T) : -1;
     const float* H0 = H + (size_t)s * B * d;
     const bool vec_ok = (((uintptr_t)H0 | ((uintptr_t)d * 4)) & 15) == 0;
     float4 r0 = {}, r1 = {}, r2 = {}, r3 = {};
@@ -361,7 +374,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         // the first chunk's probes are on their way (the bitmap was cleared before the staging
         // barrier; every consumer of the bitmap comes after the barrier that ends the chunk).
         if (!topfreq_marked) {
-            mark_id_list(bm, V, topfreq, T, tf_first);
+            mark_id_list<DEEP>(bm, V, topfreq, T, tf_first, tf_second);
             topfreq_marked = true;
             LSH_TRACE(0, 11);
         }
@@ -384,8 +397,9 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         // to the last pair whose exclusive prefix is <= e.  An index past the end is clamped for
         // the load and skipped for the mark: hundreds of atomics on the last element's word
         // would serialise.  Long walks (several elements per thread) keep four span reads in
-        // flight per thread, short ones two: with four, every thread searches four times even
-        // when the chunk has fewer elements than that.
+        // flight per thread (twelve beyond eight elements per thread: a round is a trip to
+        // memory), short ones two: with four, every thread searches four times even when the
+        // chunk has fewer elements than that.
         auto walk = [&](auto width_tag) {
             constexpr int NW = decltype(width_tag)::value;
             for (uint32_t e0 = tid; e0 < total; e0 += NW * kCandThreads) {
@@ -405,7 +419,8 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
                         atomicOr(&bm[id[q] >> 5], 1u << (id[q] & 31));
             }
         };
-        if (total > 4u * kCandThreads) walk(std::integral_constant<int, 4>{});
+        if (DEEP && total > 8u * kCandThreads) walk(std::integral_constant<int, 12>{});
+        else if (total > 4u * kCandThreads) walk(std::integral_constant<int, 4>{});
         else walk(std::integral_constant<int, 2>{});
         __syncthreads();
         LSH_TRACE(0, 5);
@@ -413,7 +428,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
     }
     if (!topfreq_marked) {  // no rows to hash
         __syncthreads();
-        mark_id_list(bm, V, topfreq, T, tf_first);
+        mark_id_list<DEEP>(bm, V, topfreq, T, tf_first, tf_second);
         __syncthreads();
     }
 }
@@ -518,7 +533,7 @@ k_candidates(CandArgs a, int32_t* __restrict__ cand, int32_t* __restrict__ count
     const int s = blockIdx.x;
     const int nwords = (a.V + 31) >> 5;
     uint32_t* wsum = smem + candidates_lds_words(a.V, a.P, a.K, a.stage_words) - 64;
-    build_presence_bitmap(a, s, smem);
+    build_presence_bitmap<true>(a, s, smem);
     // (the staged hidden rows are no longer needed: their room takes the dense-word list)
     uint2* dlist = reinterpret_cast<uint2*>(smem + bitmap_words_padded(a.V));
     compact_bitmap(smem, nwords, wsum, dlist, a.stage_words / 2, cand + (size_t)s * a.V, count + s);
@@ -536,7 +551,7 @@ k_part_bitmaps(CandArgs a, int part_rows, int nparts, uint32_t* __restrict__ par
     const int s = blockIdx.x / nparts, part = blockIdx.x - s * nparts;
     const int nwords = (a.V + 31) >> 5;
     a.T = 0;
-    build_presence_bitmap(a, s, smem, part * part_rows, min(a.B, (part + 1) * part_rows));
+    build_presence_bitmap<true>(a, s, smem, part * part_rows, min(a.B, (part + 1) * part_rows));
     uint32_t* out = part_bitmaps + (size_t)blockIdx.x * nwords;
     for (int i = threadIdx.x; i < nwords; i += kCandThreads) out[i] = smem[i];
 }
@@ -773,9 +788,10 @@ k_union_compact(const uint32_t* __restrict__ row_bitmaps, int B, int V,
     uint32_t* wsum = smem + bitmap_words_padded(V);
     uint2* dlist = reinterpret_cast<uint2*>(wsum + 64);
     const int32_t tf_first = (tid < T) ? topfreq[tid] : -1;
+    const int32_t tf_second = id_list_second(topfreq, T);
     union_row_bitmaps(row_bitmaps + (size_t)s * B * nwords, B, nwords, bm);
     __syncthreads();
-    mark_id_list(bm, V, topfreq, T, tf_first);
+    mark_id_list<true>(bm, V, topfreq, T, tf_first, tf_second);
     __syncthreads();
     compact_bitmap(bm, nwords, wsum, dlist, kUnionDenseCap, cand + (size_t)s * V, count + s);
 }
