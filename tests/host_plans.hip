@@ -3,6 +3,7 @@
 // V = 2^24, d not a multiple of 4).  Built by tests/test_host_plans.py with hipcc
 // and run on the CPU; no GPU call is made (the kernels in the headers are compiled but never launched).  Every region must start aligned, lie behind its
 // predecessor and end inside what the size function reports.
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
 #include <vector>
@@ -123,7 +124,22 @@ static void check_hlds(int S, int rows, int d) {
         }
 }
 
+// small_div() of the kernels: (int)((x + 0.5f) * r) with r = the hardware's reciprocal of y, which may
+// differ from the correctly rounded 1 / y by one unit in the last place; checked here with r two
+// units off either way, for every x < 1024 and y <= 1024.
+static void check_small_div_margin() {
+    for (int y = 1; y <= 1024; ++y) {
+        const float exact = 1.0f / (float)y;
+        float lo = exact, hi = exact;
+        for (int i = 0; i < 2; ++i) { lo = std::nextafterf(lo, 0.0f); hi = std::nextafterf(hi, 2.0f); }
+        for (float r : {lo, exact, hi})
+            for (int x = 0; x < 1024; ++x)
+                CHECK((int)(((float)x + 0.5f) * r) == x / y, "small_div x=%d y=%d", x, y);
+    }
+}
+
 int main() {
+    check_small_div_margin();
     // workspace: the largest accepted S, B, V and their neighbours, ragged V
     for (int V : {1, 15, 16, 17, 63, 64, 65, 1000, 40000, 100000, 200000, (1 << 24) - 1, 1 << 24})
         for (int S : {1, 2, 64, 4096})
