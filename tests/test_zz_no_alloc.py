@@ -36,15 +36,16 @@ def test_static_scratch_step_equals_the_workspace_step():
     from paper_1806_00588_amd import binding
     cfg = workloads.CONFIGS["paper"]
     gc = GpuCase.from_config(cfg)
-    H = workloads.make_hidden(cfg, gc.E, seed=0, steps=3)
+    H = workloads.make_hidden(cfg, gc.E, seed=0, steps=4).reshape(-1, cfg.d)      # 48 rows
     rng = np.random.default_rng(7)
     assert binding.static_scratch_bytes() == 32 << 20
     # the paper shape, then smaller inputs in the same buffer: fewer beams, a hit threshold, the
-    # full-vocabulary mode, several sentences -- and the paper shape once more
+    # full-vocabulary mode, several sentences, 40 beams (hashed in parts, the list made inside the
+    # contraction kernel) -- and the paper shape once more
     plan = [(1, 12, 1, False), (1, 5, 1, False), (1, 3, 2, False), (1, 2, 1, True), (3, 4, 1, False),
-            (1, 12, 1, False)]
+            (1, 40, 1, False), (1, 12, 1, False)]
     for n, (S, B, t, full) in enumerate(plan):
-        Hs = H[n % 3][:S * B]
+        Hs = np.ascontiguousarray(np.roll(H, -5 * n, axis=0)[:S * B])
         bs = rng.standard_normal(S * B).astype(np.float32)
         (sb, sw, ss), (wb, ww, wsc) = _both(gc, Hs, bs, S, B, cfg.T, t, full)
         assert np.array_equal(sb, wb) and np.array_equal(sw, ww) and np.array_equal(ss, wsc), (S, B, t, full)
