@@ -449,45 +449,53 @@ __device__ __forceinline__ bool select_rich_small_body(SelShared& sh, int s, flo
     // maxima are >= it)
     // (waves without a row skip the sorting network: their issue slots are the others')
     const uint32_t kth = has_row ? wave_kth_largest_sort(best, B) : 0u;
+    LSH_TRACE_ANY(2, 1);
     if (ln == 0) sh.wtau[wv] = kth;
     __syncthreads();
     uint32_t tau = 0;
 #pragma unroll
     for (int w = 0; w < kSelWaves; ++w) tau = max(tau, sh.wtau[w]);
 
-    // every largest / second largest score >= tau, one list reservation per wave
+    // every largest / second largest score >= tau, one list reservation per wave.  A second
+    // largest can reach tau only where the tile's largest does (the score is monotone in the
+    // logit), so it is looked at only there; and a wave skips what none of its lanes needs.
     if (has_row) {
         uint32_t key1[Q], key2[Q];
         int32_t id2[Q];
+        uint32_t mine = 0;
         bool any2 = false;
 #pragma unroll
         for (int q = 0; q < Q; ++q) {
             key1[q] = f32_sortable(bsi + (rec[q].x - lse) + 0.0f);
-            key2[q] = f32_sortable(bsi + (rec[q].z - lse) + 0.0f);
             const bool in = ln + q * kWave < ntiles;
             if (!(in && __float_as_int(rec[q].w) >= 0 && key1[q] >= tau)) key1[q] = 0;   // (real keys are > 0)
-            if (!(in && key2[q] >= tau)) key2[q] = 0;
+            key2[q] = 0;
             id2[q] = -1;
-            any2 = any2 || key2[q] != 0;
+            if (__ballot(key1[q] != 0) != 0ull) {   // (uniform)
+                key2[q] = f32_sortable(bsi + (rec[q].z - lse) + 0.0f);
+                if (!(key1[q] != 0 && key2[q] >= tau)) key2[q] = 0;
+                any2 = any2 || key2[q] != 0;
+                mine += key1[q] ? 1u : 0u;
+            }
         }
-        if (__ballot(any2) != 0ull) {   // (uniform; rare)
+        const bool seconds = __ballot(any2) != 0ull;   // (uniform; rare)
+        if (seconds) {
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
                 if (key2[q]) id2[q] = load_id2<SAME_KERNEL>(ids2_row + ln + q * kWave);
                 if (id2[q] < 0) key2[q] = 0;
+                mine += key2[q] ? 1u : 0u;
             }
         }
-        uint32_t mine = 0;
-#pragma unroll
-        for (int q = 0; q < Q; ++q) mine += (key1[q] ? 1u : 0u) + (key2[q] ? 1u : 0u);
-        const uint32_t incl = wave_incl_scan(mine);
-        const uint32_t wave_total = wave_read_lane(incl, kWave - 1);
-        if (wave_total) {   // (uniform)
+        if (__ballot(mine != 0) != 0ull) {   // (uniform)
+            const uint32_t incl = wave_incl_scan(mine);
+            const uint32_t wave_total = wave_read_lane(incl, kWave - 1);
             uint32_t base = 0;
             if (ln == 0) base = atomicAdd(&sh.misc[4], wave_total);
             uint32_t pos = wave_read_lane(base, 0) + incl - mine;
 #pragma unroll
             for (int q = 0; q < Q; ++q) {
+                if (__ballot(key1[q] != 0) == 0ull) continue;   // (uniform)
                 if (key1[q]) {
                     if (pos < (uint32_t)kWave) {
                         sh.list[pos] = ((uint64_t)key1[q] << 32) |
@@ -496,7 +504,7 @@ __device__ __forceinline__ bool select_rich_small_body(SelShared& sh, int s, flo
                     }
                     ++pos;
                 }
-                if (key2[q]) {
+                if (seconds && key2[q]) {
                     if (pos < (uint32_t)kWave) {
                         sh.list[pos] = ((uint64_t)key2[q] << 32) | (uint64_t)(~(((uint32_t)wv << 24) | (uint32_t)id2[q]));
                         sh.open_list[pos] = 1u;   // a second largest
@@ -508,6 +516,7 @@ __device__ __forceinline__ bool select_rich_small_body(SelShared& sh, int s, flo
     }
     __syncthreads();
     const int mr = (int)sh.misc[4];
+    LSH_TRACE_ANY(2, 3);
     if (mr > kWave) return false;   // (uniform; a longer list is the general path's)
 
     // ranks by ballot: in every wave lane j holds entry j, wave w ranks entries 4w .. 4w + 3
@@ -540,7 +549,9 @@ __device__ __forceinline__ bool select_rich_small_body(SelShared& sh, int s, flo
         for (int e = ln + min(mr, B); e < B; e += kWave) {
             out_beam[o0 + e] = -1; out_word[o0 + e] = -1; out_score[o0 + e] = -INFINITY;
         }
+    LSH_TRACE_ANY(2, 4);
     __syncthreads();
+    LSH_TRACE_ANY(2, 5);
     return sh.misc[6] == 0u;
 }
 
@@ -550,6 +561,7 @@ __device__ __forceinline__ bool select_rich_small(SelShared& sh, int s, const Ti
                                                   const float* beam_scores, float* lse_out, int32_t* out_beam,
                                                   int32_t* out_word, float* out_score, int tile_forced, int* C_out) {
     const int ln = lane_id(), wv = wave_id();
+    LSH_TRACE_ANY(2, 0);
     // everything whose address is known is asked for at once: the row's beam score, its records
     // (indices clamped to the allocated pitch; what lies past the last tile is masked later) and
     // the list's length
