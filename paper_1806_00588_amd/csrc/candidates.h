@@ -127,6 +127,7 @@ constexpr int kCandWaves = kCandThreads / kWave;
 // Hidden values staged in LDS per chunk of rows (floats): at least this much (or one row, if a row
 // is longer), more when a step's sentences have more beams and LDS has room (the host decides per
 // step and passes the size along: CandArgs::stage_words, a multiple of 4).
+constexpr int kDirectFlag = 32;      // word of the scan scratch that holds the direct walk's verdict
 constexpr int kCandStage = 12288;
 constexpr int kCandStageRows = 32;   // a larger stage is sized for at most this many rows
 __host__ __device__ inline int candidates_min_stage(int d) {
@@ -317,6 +318,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
             for (int e = tid; e < nval; e += kCandThreads) stage[e] = Hc[e];
         }
         LSH_TRACE(0, 12);
+        if (tid == 0) wsum[kDirectFlag] = 0u;   // "a span of this chunk is too long for the direct walk"
         __syncthreads();
         LSH_TRACE(0, 2);
         LSH_TRACE_WG(1);
@@ -383,9 +385,52 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         asm volatile("" : "+v"(slot0.x), "+v"(slot0.y), "+v"(slot0.z), "+v"(slot1.x), "+v"(slot1.y),
                           "+v"(slot1.z) :: "memory");
         if (tid < npairs) cuckoo_resolve(slot0, slot1, code, &start, &len);
+        // Short spans are walked without the scan and the search below: kCandThreads / npairs
+        // threads share a span, each taking every subs-th aligned group of four ids of the flat
+        // word array (the array is padded, so a group may reach past a span's end but never past
+        // the allocation), at most kDirectGroups groups per thread.  One span too long for that:
+        // the flat walk for the whole chunk.
+        constexpr int kDirectGroups = 3;
+        const int subs = kCandThreads / npairs;
+        {
+            const size_t flat = (size_t)w * V + start;
+            const uint32_t mis = (uint32_t)flat & 3u;
+            p_start[tid] = (uint32_t)(flat >> 2);               // first group (W * V < 2^34)
+            p_band[tid] = len | (mis << 30);                    // (len <= V <= 2^24)
+            if (((len + mis + 3) >> 2) > (uint32_t)(subs * kDirectGroups)) wsum[kDirectFlag] = 1u;
+        }
         __syncthreads();  // codes[] aliases p_pref
         LSH_TRACE(0, 3);
         LSH_TRACE_WG(2);
+        if (wsum[kDirectFlag] == 0u) {   // (uniform)
+            const int sub = small_div(tid, npairs), pair = tid - sub * npairs;
+            const uint32_t g0 = p_start[pair], lm = p_band[pair];
+            const uint32_t slen = lm & 0x3FFFFFFFu, smis = lm >> 30;
+            const uint32_t ngroups = (sub < subs && slen) ? (slen + smis + 3) >> 2 : 0u;
+            const int4* __restrict__ words4 = reinterpret_cast<const int4*>(words);
+            int4 grp[kDirectGroups];
+#pragma unroll
+            for (int j = 0; j < kDirectGroups; ++j) {
+                const uint32_t g = (uint32_t)(sub + subs * j);
+                if (j > 0 && __ballot(g < ngroups) == 0ull) { grp[j] = make_int4(0, 0, 0, 0); continue; }   // (uniform)
+                grp[j] = words4[(size_t)g0 + (g < ngroups ? g : 0u)];
+            }
+#pragma unroll
+            for (int j = 0; j < kDirectGroups; ++j) {
+                const uint32_t g = (uint32_t)(sub + subs * j);
+                if (__ballot(g < ngroups) == 0ull) continue;   // (uniform)
+                const uint32_t p0 = 4u * g;                    // position of the group's first id in the span + smis
+                const int32_t ids[4] = {grp[j].x, grp[j].y, grp[j].z, grp[j].w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (g < ngroups && p0 + c >= smis && p0 + c < smis + slen)
+                        atomicOr(&bm[ids[c] >> 5], 1u << (ids[c] & 31));
+            }
+            __syncthreads();
+            LSH_TRACE(0, 5);
+            LSH_TRACE_WG(3);
+            continue;
+        }
         uint32_t total;
         const uint32_t incl = block_incl_scan(len, wsum, &total);
         LSH_TRACE(0, 4);
