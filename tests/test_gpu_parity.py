@@ -246,6 +246,9 @@ _SWEEP = [
     (7000, 1500, 16, 8, 2, 64, 200, False, [(1, 8, 1), (2, 36, 1), (9, 9, 1)]),
     (6000, 256, 8, 32, 8, 500, 300, True, [(1, 12, 1), (8, 16, 1), (2, 40, 1), (20, 4, 1), (2, 10, 2)]),
     (4100, 1024, 8, 16, 4, 1000, 100, True, [(1, 16, 1), (5, 24, 1)]),
+    # four buckets per band over 37 words: every span is long for its size, the last one ends with
+    # the word array, and no span starts on a multiple of four
+    (37, 8, 2, 4, 2, 5, 4, False, [(1, 3, 1), (2, 2, 1), (1, 40, 1), (30, 1, 1)]),
 ]
 
 
