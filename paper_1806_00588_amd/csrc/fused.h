@@ -68,6 +68,7 @@ struct TailArgs {
 // barrier that waited for the whole array -- cost a microsecond more.)
 // `tile_ids` has kFusedRound * 16 words, `wsum` >= 17, `red` is the cross-wave reduction buffer;
 // h_lds (or null) are the sentence's hidden rows staged in LDS as [B][d].
+constexpr int kCoopBits = 4;   // list positions of one tile in one thread from which its wave shares the work
 template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
 __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* wsum, uint32_t* tile_ids,
                                                   float (*red)[4][kWave], const float* h_lds,
@@ -93,15 +94,22 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
     const int ntiles = tn == kTileN ? (C + kTileN - 1) >> 4 : (C + tn - 1) / tn;   // (no division in the usual case)
     const int col = ln & 15;
     for (int base = 0; g + base * G < ntiles; base += kFusedRound) {
-        // ids of the tiles g + (base + k) G, k < kFusedRound, into tile_ids[k][16]
-        if (mine) {
-            for (int k = 0; k < kFusedRound; ++k) {
-                const int nt = g + (base + k) * G;
-                if (nt >= ntiles) break;
-                const uint32_t lo = max(run, (uint32_t)(nt * tn));
-                const uint32_t hi = min(min(run + mine, (uint32_t)(nt * tn + tn)), (uint32_t)C);
-                if (lo >= hi) continue;
-                // my (lo - run)-th set bit and the hi - lo - 1 that follow
+        // ids of the tiles g + (base + k) G, k < kFusedRound, into tile_ids[k][16].  A thread
+        // with a few of a tile's positions walks its set bits itself.  One with kCoopBits or more
+        // -- the dense words of the top-frequent ids put a whole tile into one thread, and sixteen
+        // dependent steps of a single lane were the longest thing such a workgroup did -- hands
+        // them to the lanes of its wave: lane c finds the c-th of them by rank (popcounts of the
+        // owner's words, then a five-step search inside the word).
+        for (int k = 0; k < kFusedRound; ++k) {
+            const int nt = g + (base + k) * G;
+            if (nt >= ntiles) break;
+            const uint32_t lo = max(run, (uint32_t)(nt * tn));
+            const uint32_t hi = min(min(run + mine, (uint32_t)(nt * tn + tn)), (uint32_t)C);
+            const uint32_t n = (mine && lo < hi) ? hi - lo : 0u;
+            uint32_t* ids_k = tile_ids + k * kTileN;             // [position in the list - t0]
+            const uint32_t t0 = (uint32_t)(nt * tn);
+            if (n > 0 && n < (uint32_t)kCoopBits) {
+                // my (lo - run)-th set bit and the n - 1 that follow
                 uint32_t skip = lo - run;
                 int i = wbeg;
                 uint32_t bits = bm[i];
@@ -109,8 +117,26 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
                 for (; skip; --skip) bits &= bits - 1u;
                 for (uint32_t pos = lo; pos < hi; ++pos) {
                     while (!bits) bits = bm[++i];
-                    tile_ids[k * kTileN + (int)(pos - (uint32_t)(nt * tn))] = ((uint32_t)i << 5) + (uint32_t)(__ffs(bits) - 1);
+                    ids_k[pos - t0] = ((uint32_t)i << 5) + (uint32_t)(__ffs(bits) - 1);
                     bits &= bits - 1u;
+                }
+            }
+            for (uint64_t heavy = __ballot(n >= (uint32_t)kCoopBits); heavy; heavy &= heavy - 1) {   // (uniform)
+                const int o = __ffsll((unsigned long long)heavy) - 1;
+                const uint32_t o_lo = wave_read_lane(lo, o), o_n = wave_read_lane(n, o), o_run = wave_read_lane(run, o);
+                int i = (int)wave_read_lane((uint32_t)wbeg, o);
+                if ((uint32_t)ln < o_n) {
+                    uint32_t r = o_lo - o_run + (uint32_t)ln;          // my bit's rank in the owner's words
+                    uint32_t bits = bm[i];
+                    for (uint32_t c = __popc(bits); r >= c; c = __popc(bits)) { r -= c; bits = bm[++i]; }
+                    uint32_t at = 0;
+#pragma unroll
+                    for (int half = 16; half >= 1; half >>= 1) {       // the r-th set bit of `bits`
+                        const uint32_t low = bits & ((1u << half) - 1u);
+                        const uint32_t c = __popc(low);
+                        if (r >= c) { r -= c; bits >>= half; at += half; } else { bits = low; }
+                    }
+                    ids_k[o_lo + (uint32_t)ln - t0] = ((uint32_t)i << 5) + at;
                 }
             }
         }
