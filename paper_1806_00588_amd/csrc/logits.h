@@ -849,6 +849,7 @@ __host__ __device__ inline size_t estage_lds_bytes(bool with_union = false) {
 }
 // LDS words the union needs inside the tile buffers (bitmap + scan scratch)
 __host__ __device__ inline size_t estage_union_words(int V) { return (size_t)bitmap_words_padded(V) + 64; }
+constexpr int kEsCoopBits = 4;   // list positions of one tile in one thread from which its wave shares the work
 struct EstageUnion {
     const uint32_t* parts;    // [S, nparts, ceil(V/32)] bitmaps
     int nparts;
@@ -948,26 +949,59 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
         C = (int)total;
         LSH_TRACE(1, 14);
         // my bits are list positions [pos, pos + mine); of the tiles they fall into, this
-        // workgroup's are those congruent to j0 modulo G: for each, skip to its first bit
-        // (whole words by popcount) and write out at most 16 ids
-        if (mine) {
+        // workgroup's are those congruent to j0 modulo G.  A thread with a few positions of such a
+        // tile skips to its first bit (whole words by popcount) and writes the ids out itself; one
+        // with kEsCoopBits or more (the dense words of the top-frequent ids put a whole tile into
+        // one thread) hands them to the lanes of its wave, each finding one id by rank -- sixteen
+        // dependent steps of a single lane, in every workgroup, used to be most of this phase.
+        {
             const uint32_t end = pos + mine;
             const int t0 = (int)(pos >> 4);
-            for (int nt = t0 + (j0 - t0 % G + G) % G; (uint32_t)nt * kTileN < end; nt += G) {
-                const uint32_t lo = max(pos, (uint32_t)nt * kTileN), hi = min(end, (uint32_t)nt * kTileN + kTileN);
-                uint32_t skip = lo - pos;
-                int i = wbeg;
-                uint32_t bits = bm[i];
-                for (uint32_t c = __popc(bits); skip >= c; c = __popc(bits)) { skip -= c; bits = bm[++i]; }
-                for (; skip; --skip) bits &= bits - 1u;
-                const int k = nt / G;
-                for (uint32_t at = lo; at < hi; ++at) {
-                    while (!bits) bits = bm[++i];
-                    const int32_t id = (i << 5) + (__ffs(bits) - 1);
-                    bits &= bits - 1u;
-                    un.cand[(size_t)s * V + at] = id;
-                    if (k < kEsIdTiles) ids_lds[k * kTileN + (int)(at & 15u)] = (uint32_t)id;
+            int nt = t0 + (j0 - t0 % G + G) % G;
+            int k = nt / G;
+            auto pending = [&]() { return mine != 0u && (uint32_t)nt * kTileN < end; };
+            while (__ballot(pending()) != 0ull) {   // (uniform)
+                const bool has = pending();
+                const uint32_t lo = has ? max(pos, (uint32_t)nt * kTileN) : 0u;
+                const uint32_t hi = has ? min(end, (uint32_t)nt * kTileN + kTileN) : 0u;
+                const uint32_t n = hi - lo;
+                if (has && n < (uint32_t)kEsCoopBits) {
+                    uint32_t skip = lo - pos;
+                    int i = wbeg;
+                    uint32_t bits = bm[i];
+                    for (uint32_t c = __popc(bits); skip >= c; c = __popc(bits)) { skip -= c; bits = bm[++i]; }
+                    for (; skip; --skip) bits &= bits - 1u;
+                    for (uint32_t at = lo; at < hi; ++at) {
+                        while (!bits) bits = bm[++i];
+                        const int32_t id = (i << 5) + (__ffs(bits) - 1);
+                        bits &= bits - 1u;
+                        un.cand[(size_t)s * V + at] = id;
+                        if (k < kEsIdTiles) ids_lds[k * kTileN + (int)(at & 15u)] = (uint32_t)id;
+                    }
                 }
+                for (uint64_t heavy = __ballot(has && n >= (uint32_t)kEsCoopBits); heavy; heavy &= heavy - 1) {   // (uniform)
+                    const int o = __ffsll((unsigned long long)heavy) - 1;
+                    const uint32_t o_lo = wave_read_lane(lo, o), o_n = wave_read_lane(n, o), o_pos = wave_read_lane(pos, o);
+                    const int o_k = (int)wave_read_lane((uint32_t)k, o);
+                    int i = (int)wave_read_lane((uint32_t)wbeg, o);
+                    if ((uint32_t)ln < o_n) {
+                        uint32_t r = o_lo - o_pos + (uint32_t)ln;      // my bit's rank in the owner's words
+                        uint32_t bits = bm[i];
+                        for (uint32_t c = __popc(bits); r >= c; c = __popc(bits)) { r -= c; bits = bm[++i]; }
+                        uint32_t bit = 0;
+#pragma unroll
+                        for (int half = 16; half >= 1; half >>= 1) {   // the r-th set bit of `bits`
+                            const uint32_t low = bits & ((1u << half) - 1u);
+                            const uint32_t c = __popc(low);
+                            if (r >= c) { r -= c; bits >>= half; bit += half; } else { bits = low; }
+                        }
+                        const int32_t id = (i << 5) + (int32_t)bit;
+                        const uint32_t at = o_lo + (uint32_t)ln;
+                        un.cand[(size_t)s * V + at] = id;
+                        if (o_k < kEsIdTiles) ids_lds[o_k * kTileN + (int)(at & 15u)] = (uint32_t)id;
+                    }
+                }
+                if (has) { nt += G; ++k; }
             }
         }
         LSH_TRACE(1, 15);
