@@ -410,9 +410,9 @@ __device__ __forceinline__ uint32_t select_front_grouped(SelShared& sh, int s, c
 // Same arithmetic and the same keys as the general path's short cut; returns false, having
 // written nothing final, when that path has to decide: more than 64 listed entries, or a second
 // largest among the B best (a tile may hide a third).  C_known < 0: the list's length is count[s];
-// *C_out receives it.  Eight records per lane are asked for before that length is known; a list
+// *C_out receives it.  Four records per lane are asked for before that length is known; a list
 // of up to 256 tiles -- a dozen beams over a few thousand candidates -- then runs the code for
-// four (Q = 4), a longer one the code for eight.  The word id of a tile's second largest logit is
+// four (Q = 4), a longer one asks for the rest and runs the code for eight.  The word id of a tile's second largest logit is
 // fetched only when that logit reaches the threshold (on the benchmark's chained steps: never).
 constexpr int kSmallQ = 8;
 template <bool SAME_KERNEL, int Q>
