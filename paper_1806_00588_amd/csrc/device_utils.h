@@ -158,6 +158,19 @@ __device__ __forceinline__ int small_div(int x, int y) {
     return (int)(((float)x + 0.5f) * __builtin_amdgcn_rcpf((float)y));   // (v_rcp_f32: 1 ulp, ample here)
 }
 
+// Position of the r-th set bit (r = 0 for the lowest) of a word that has more than r bits set: a
+// five-step search over popcounts of the low halves.
+__device__ __forceinline__ uint32_t nth_set_bit(uint32_t bits, uint32_t r) {
+    uint32_t at = 0;
+#pragma unroll
+    for (int half = 16; half >= 1; half >>= 1) {
+        const uint32_t low = bits & ((1u << half) - 1u);
+        const uint32_t c = __popc(low);
+        if (r >= c) { r -= c; bits >>= half; at += half; } else { bits = low; }
+    }
+    return at;
+}
+
 // Workgroup barrier for data that is exchanged through LDS only: waits for this wave's LDS
 // operations but, unlike __syncthreads, not for its global loads and stores -- loads that were
 // issued early on purpose stay in flight across it.

@@ -129,14 +129,7 @@ __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* 
                     uint32_t r = o_lo - o_run + (uint32_t)ln;          // my bit's rank in the owner's words
                     uint32_t bits = bm[i];
                     for (uint32_t c = __popc(bits); r >= c; c = __popc(bits)) { r -= c; bits = bm[++i]; }
-                    uint32_t at = 0;
-#pragma unroll
-                    for (int half = 16; half >= 1; half >>= 1) {       // the r-th set bit of `bits`
-                        const uint32_t low = bits & ((1u << half) - 1u);
-                        const uint32_t c = __popc(low);
-                        if (r >= c) { r -= c; bits >>= half; at += half; } else { bits = low; }
-                    }
-                    ids_k[o_lo + (uint32_t)ln - t0] = ((uint32_t)i << 5) + at;
+                    ids_k[o_lo + (uint32_t)ln - t0] = ((uint32_t)i << 5) + nth_set_bit(bits, r);
                 }
             }
         }

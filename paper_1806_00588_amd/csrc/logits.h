@@ -988,14 +988,7 @@ k_logits_estage(const float* __restrict__ E, int64_t ld, int d, const float* __r
                         uint32_t r = o_lo - o_pos + (uint32_t)ln;      // my bit's rank in the owner's words
                         uint32_t bits = bm[i];
                         for (uint32_t c = __popc(bits); r >= c; c = __popc(bits)) { r -= c; bits = bm[++i]; }
-                        uint32_t bit = 0;
-#pragma unroll
-                        for (int half = 16; half >= 1; half >>= 1) {   // the r-th set bit of `bits`
-                            const uint32_t low = bits & ((1u << half) - 1u);
-                            const uint32_t c = __popc(low);
-                            if (r >= c) { r -= c; bits >>= half; bit += half; } else { bits = low; }
-                        }
-                        const int32_t id = (i << 5) + (int32_t)bit;
+                        const int32_t id = (i << 5) + (int32_t)nth_set_bit(bits, r);
                         const uint32_t at = o_lo + (uint32_t)ln;
                         un.cand[(size_t)s * V + at] = id;
                         if (o_k < kEsIdTiles) ids_lds[o_k * kTileN + (int)(at & 15u)] = (uint32_t)id;
