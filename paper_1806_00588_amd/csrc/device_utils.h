@@ -160,12 +160,12 @@ __device__ __forceinline__ int small_div(int x, int y) {
 
 // Position of the r-th set bit (r = 0 for the lowest) of a word that has more than r bits set: a
 // five-step search over popcounts of the low halves.
-__device__ __forceinline__ uint32_t nth_set_bit(uint32_t bits, uint32_t r) {
+__host__ __device__ __forceinline__ uint32_t nth_set_bit(uint32_t bits, uint32_t r) {
     uint32_t at = 0;
 #pragma unroll
     for (int half = 16; half >= 1; half >>= 1) {
         const uint32_t low = bits & ((1u << half) - 1u);
-        const uint32_t c = __popc(low);
+        const uint32_t c = (uint32_t)__builtin_popcount(low);
         if (r >= c) { r -= c; bits >>= half; at += half; } else { bits = low; }
     }
     return at;

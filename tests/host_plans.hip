@@ -138,8 +138,24 @@ static void check_small_div_margin() {
     }
 }
 
+// nth_set_bit() against a bit-by-bit walk: every rank of a few thousand words (all one-bit and
+// two-bit words, dense and random ones).
+static void check_nth_set_bit() {
+    std::vector<uint32_t> words = {0xFFFFFFFFu, 0x80000000u, 0x00000001u, 0xAAAAAAAAu, 0x55555555u, 0xFFFF0000u, 0x0000FFFFu};
+    for (int a = 0; a < 32; ++a)
+        for (int b = a; b < 32; ++b) words.push_back((1u << a) | (1u << b));
+    uint64_t x = 0x9E3779B97F4A7C15ull;
+    for (int i = 0; i < 4000; ++i) { x ^= x << 13; x ^= x >> 7; x ^= x << 17; words.push_back((uint32_t)(x >> 16)); }
+    for (uint32_t w : words) {
+        uint32_t r = 0;
+        for (uint32_t bit = 0; bit < 32; ++bit)
+            if (w >> bit & 1u) { CHECK(nth_set_bit(w, r) == bit, "nth_set_bit(%08x, %u)", w, r); ++r; }
+    }
+}
+
 int main() {
     check_small_div_margin();
+    check_nth_set_bit();
     // workspace: the largest accepted S, B, V and their neighbours, ragged V
     for (int V : {1, 15, 16, 17, 63, 64, 65, 1000, 40000, 100000, 200000, (1 << 24) - 1, 1 << 24})
         for (int S : {1, 2, 64, 4096})
