@@ -68,7 +68,7 @@ struct TailArgs {
 // barrier that waited for the whole array -- cost a microsecond more.)
 // `tile_ids` has kFusedRound * 16 words, `wsum` >= 17, `red` is the cross-wave reduction buffer;
 // h_lds (or null) are the sentence's hidden rows staged in LDS as [B][d].
-constexpr int kCoopBits = 4;   // list positions of one tile in one thread from which its wave shares the work
+constexpr int kCoopBits = 8;   // list positions of one tile in one thread from which its wave shares the work
 template <typename ET, bool ALIGNED, bool ONE_LAUNCH>
 __device__ __forceinline__ void tiles_from_bitmap(const uint32_t* bm, uint32_t* wsum, uint32_t* tile_ids,
                                                   float (*red)[4][kWave], const float* h_lds,

@@ -849,7 +849,7 @@ __host__ __device__ inline size_t estage_lds_bytes(bool with_union = false) {
 }
 // LDS words the union needs inside the tile buffers (bitmap + scan scratch)
 __host__ __device__ inline size_t estage_union_words(int V) { return (size_t)bitmap_words_padded(V) + 64; }
-constexpr int kEsCoopBits = 4;   // list positions of one tile in one thread from which its wave shares the work
+constexpr int kEsCoopBits = 8;   // list positions of one tile in one thread from which its wave shares the work
 struct EstageUnion {
     const uint32_t* parts;    // [S, nparts, ceil(V/32)] bitmaps
     int nparts;
