@@ -390,7 +390,7 @@ __device__ __forceinline__ void build_presence_bitmap(const CandArgs& a, int s, 
         // word array (the array is padded, so a group may reach past a span's end but never past
         // the allocation), at most kDirectGroups groups per thread.  One span too long for that:
         // the flat walk for the whole chunk.
-        constexpr int kDirectGroups = 3;
+        constexpr int kDirectGroups = 4;
         const int subs = kCandThreads / npairs;
         {
             const size_t flat = (size_t)w * V + start;
